@@ -1,0 +1,768 @@
+// CPU oracle for one blockwise-distillation step.  TEST INFRASTRUCTURE ONLY:
+// it exists to check the HIP library and to be timed beside it; nothing on the
+// product path may call it.  It shares no code with the HIP path.
+//
+// What it computes (Sec. II-A; Algorithm 1, the load / T.forward / S.forward /
+// S.backward(L) / update_weight lines; Sec. IV-B for the per-block update):
+//   A_0 = x,  A_i = T_i(A_{i-1})         teacher, frozen, BN in inference mode
+//   S^_i = S_i(A_{i-1})                   student, BN with batch statistics
+//   loss_i = mean((S^_i - A_i)^2)         L(delta output), read as MSE
+//   backprop through S_i only, then  v <- mu v + g,  w <- w - lr v.
+// The method only reschedules work (Abstract; Sec. VII-D), so the oracle is the
+// plain definition: direct nested loops over NCHW tensors, no blocking, no
+// BLAS.  `relay` keeps every A_i; `redundant` re-runs T_1..T_{i-1} from A_0 for
+// each block the way the data-parallel baseline does (Sec. II-B, Sec. III).
+// Scalar type R is double (reference of record) or float (noise-floor / timing).
+//
+// Readings where the paper is silent: MSE averaged over all elements; PyTorch
+// form of SGD momentum, no weight decay; teacher BN frozen, student BN in
+// training mode with running statistics updated (eps 1e-5, rate 0.1, unbiased
+// running variance); convolutions are cross-correlations without bias and
+// with zero padding; max-pool gradients go to the first maximum in row-major
+// window order.
+//
+// Pins (tests/test_oracle_*.py): brute-force convolution, 1x1 conv == matrix
+// product, adjoint identities for dgrad/wgrad, BN closed forms, central finite
+// differences of loss_i over every parameter, PyTorch-CPU fp64 autograd on the
+// same blocks, SGD closed form, relay == redundant bitwise, block-order
+// independence.
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <memory>
+#include <string>
+#include <vector>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+namespace {
+
+enum { OP_CBA = 1, OP_POOL = 2, OP_ADD = 3, OP_MIX = 4 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2 };
+constexpr int32_t kMagic = 0x50424431;
+constexpr int kRec = 20;
+
+// ---------------------------------------------------------------------------
+// primitives (NCHW, direct loops)
+// ---------------------------------------------------------------------------
+
+inline int out_dim(int h, int k, int s, int pad) { return (h + 2 * pad - k) / s + 1; }
+
+// Y[n,k,p,q] = sum_{c,r,t} X[n, g*Cg + c, p*s + r - pad, q*s + t - pad] * W[k,c,r,t]
+template <class R>
+void conv_fwd(const R* x, const R* w, R* y, int N, int C, int H, int W, int K, int k,
+              int stride, int pad, int groups) {
+  const int P = out_dim(H, k, stride, pad), Q = out_dim(W, k, stride, pad);
+  const int Cg = C / groups, Kg = K / groups;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int ko = 0; ko < K; ++ko) {
+      const int g = ko / Kg;
+      for (int p = 0; p < P; ++p)
+        for (int q = 0; q < Q; ++q) {
+          R acc = 0;
+          for (int c = 0; c < Cg; ++c)
+            for (int r = 0; r < k; ++r) {
+              const int h = p * stride + r - pad;
+              if (h < 0 || h >= H) continue;
+              for (int t = 0; t < k; ++t) {
+                const int ww = q * stride + t - pad;
+                if (ww < 0 || ww >= W) continue;
+                acc += x[((size_t)(n * C + g * Cg + c) * H + h) * W + ww] *
+                       w[((size_t)(ko * Cg + c) * k + r) * k + t];
+              }
+            }
+          y[((size_t)(n * K + ko) * P + p) * Q + q] = acc;
+        }
+    }
+}
+
+// dX = adjoint of conv_fwd in X: every output position scatters dY*W back.
+template <class R>
+void conv_dgrad(const R* dy, const R* w, R* dx, int N, int C, int H, int W, int K, int k,
+                int stride, int pad, int groups) {
+  const int P = out_dim(H, k, stride, pad), Q = out_dim(W, k, stride, pad);
+  const int Cg = C / groups, Kg = K / groups;
+#pragma omp parallel for schedule(static)
+  for (int n = 0; n < N; ++n) {
+    std::fill(dx + (size_t)n * C * H * W, dx + (size_t)(n + 1) * C * H * W, R(0));
+    for (int ko = 0; ko < K; ++ko) {
+      const int g = ko / Kg;
+      for (int p = 0; p < P; ++p)
+        for (int q = 0; q < Q; ++q) {
+          const R d = dy[((size_t)(n * K + ko) * P + p) * Q + q];
+          for (int c = 0; c < Cg; ++c)
+            for (int r = 0; r < k; ++r) {
+              const int h = p * stride + r - pad;
+              if (h < 0 || h >= H) continue;
+              for (int t = 0; t < k; ++t) {
+                const int ww = q * stride + t - pad;
+                if (ww < 0 || ww >= W) continue;
+                dx[((size_t)(n * C + g * Cg + c) * H + h) * W + ww] +=
+                    d * w[((size_t)(ko * Cg + c) * k + r) * k + t];
+              }
+            }
+        }
+    }
+  }
+}
+
+// dW[k,c,r,t] = sum_{n,p,q} dY[n,k,p,q] * X[n, g*Cg + c, p*s + r - pad, q*s + t - pad]
+template <class R>
+void conv_wgrad(const R* dy, const R* x, R* dw, int N, int C, int H, int W, int K, int k,
+                int stride, int pad, int groups) {
+  const int P = out_dim(H, k, stride, pad), Q = out_dim(W, k, stride, pad);
+  const int Cg = C / groups, Kg = K / groups;
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int ko = 0; ko < K; ++ko)
+    for (int c = 0; c < Cg; ++c) {
+      const int g = ko / Kg;
+      for (int r = 0; r < k; ++r)
+        for (int t = 0; t < k; ++t) {
+          R acc = 0;
+          for (int n = 0; n < N; ++n)
+            for (int p = 0; p < P; ++p) {
+              const int h = p * stride + r - pad;
+              if (h < 0 || h >= H) continue;
+              for (int q = 0; q < Q; ++q) {
+                const int ww = q * stride + t - pad;
+                if (ww < 0 || ww >= W) continue;
+                acc += dy[((size_t)(n * K + ko) * P + p) * Q + q] *
+                       x[((size_t)(n * C + g * Cg + c) * H + h) * W + ww];
+              }
+            }
+          dw[((size_t)(ko * Cg + c) * k + r) * k + t] = acc;
+        }
+    }
+}
+
+// Batch normalisation with batch statistics: per channel over m = N*HW,
+// mu = mean, var = biased variance, xhat = (x-mu)/sqrt(var+eps), y = gamma*xhat+beta.
+template <class R>
+void bn_train_fwd(const R* x, const R* gamma, const R* beta, R* y, R* mean, R* var, int N,
+                  int C, int HW, R eps) {
+  const R m = (R)N * (R)HW;
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    R s = 0;
+    for (int n = 0; n < N; ++n)
+      for (int i = 0; i < HW; ++i) s += x[((size_t)n * C + c) * HW + i];
+    const R mu = s / m;
+    R v = 0;
+    for (int n = 0; n < N; ++n)
+      for (int i = 0; i < HW; ++i) {
+        const R d = x[((size_t)n * C + c) * HW + i] - mu;
+        v += d * d;
+      }
+    v /= m;
+    mean[c] = mu;
+    var[c] = v;
+    const R inv = R(1) / std::sqrt(v + eps);
+    for (int n = 0; n < N; ++n)
+      for (int i = 0; i < HW; ++i) {
+        const size_t o = ((size_t)n * C + c) * HW + i;
+        y[o] = gamma[c] * ((x[o] - mu) * inv) + beta[c];
+      }
+  }
+}
+
+// dbeta = sum dy, dgamma = sum dy*xhat,
+// dx = gamma/sqrt(var+eps) * (dy - dbeta/m - xhat*dgamma/m)
+template <class R>
+void bn_train_bwd(const R* dy, const R* x, const R* gamma, const R* mean, const R* var, R* dx,
+                  R* dgamma, R* dbeta, int N, int C, int HW, R eps) {
+  const R m = (R)N * (R)HW;
+#pragma omp parallel for schedule(static)
+  for (int c = 0; c < C; ++c) {
+    const R inv = R(1) / std::sqrt(var[c] + eps);
+    R sb = 0, sg = 0;
+    for (int n = 0; n < N; ++n)
+      for (int i = 0; i < HW; ++i) {
+        const size_t o = ((size_t)n * C + c) * HW + i;
+        sb += dy[o];
+        sg += dy[o] * ((x[o] - mean[c]) * inv);
+      }
+    dbeta[c] = sb;
+    dgamma[c] = sg;
+    for (int n = 0; n < N; ++n)
+      for (int i = 0; i < HW; ++i) {
+        const size_t o = ((size_t)n * C + c) * HW + i;
+        const R xh = (x[o] - mean[c]) * inv;
+        dx[o] = gamma[c] * inv * (dy[o] - sb / m - xh * sg / m);
+      }
+  }
+}
+
+// Inference-mode BN: y = gamma*(x - rmean)/sqrt(rvar+eps) + beta.
+template <class R>
+void bn_eval(const R* x, const R* gamma, const R* beta, const R* rmean, const R* rvar, R* y,
+             int N, int C, int HW, R eps) {
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int n = 0; n < N; ++n)
+    for (int c = 0; c < C; ++c) {
+      const R inv = R(1) / std::sqrt(rvar[c] + eps);
+      for (int i = 0; i < HW; ++i) {
+        const size_t o = ((size_t)n * C + c) * HW + i;
+        y[o] = gamma[c] * ((x[o] - rmean[c]) * inv) + beta[c];
+      }
+    }
+}
+
+template <class R>
+void act_fwd(const R* x, R* y, size_t n, int act) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < n; ++i) {
+    R v = x[i];
+    if (act == ACT_RELU) v = v > 0 ? v : R(0);
+    if (act == ACT_RELU6) v = v > 0 ? (v < 6 ? v : R(6)) : R(0);
+    y[i] = v;
+  }
+}
+
+// x is the pre-activation; gradient passes where the activation has slope 1.
+template <class R>
+void act_bwd(const R* dy, const R* x, R* dx, size_t n, int act) {
+#pragma omp parallel for schedule(static)
+  for (size_t i = 0; i < n; ++i) {
+    bool pass = true;
+    if (act == ACT_RELU) pass = x[i] > 0;
+    if (act == ACT_RELU6) pass = x[i] > 0 && x[i] < 6;
+    dx[i] = pass ? dy[i] : R(0);
+  }
+}
+
+// Window max over a (-inf)-padded input; idx keeps the flat h*W+w of the first
+// maximum met in row-major window order.
+template <class R>
+void maxpool_fwd(const R* x, R* y, int32_t* idx, int N, int C, int H, int W, int k, int stride,
+                 int pad) {
+  const int P = out_dim(H, k, stride, pad), Q = out_dim(W, k, stride, pad);
+#pragma omp parallel for schedule(static)
+  for (int nc = 0; nc < N * C; ++nc)
+    for (int p = 0; p < P; ++p)
+      for (int q = 0; q < Q; ++q) {
+        R best = -std::numeric_limits<R>::infinity();
+        int bi = -1;
+        for (int r = 0; r < k; ++r) {
+          const int h = p * stride + r - pad;
+          if (h < 0 || h >= H) continue;
+          for (int t = 0; t < k; ++t) {
+            const int ww = q * stride + t - pad;
+            if (ww < 0 || ww >= W) continue;
+            const R v = x[((size_t)nc * H + h) * W + ww];
+            if (bi < 0 || v > best) { best = v; bi = h * W + ww; }
+          }
+        }
+        y[((size_t)nc * P + p) * Q + q] = best;
+        idx[((size_t)nc * P + p) * Q + q] = bi;
+      }
+}
+
+template <class R>
+void maxpool_bwd(const R* dy, const int32_t* idx, R* dx, int N, int C, int H, int W, int P, int Q) {
+#pragma omp parallel for schedule(static)
+  for (int nc = 0; nc < N * C; ++nc) {
+    R* d = dx + (size_t)nc * H * W;
+    std::fill(d, d + (size_t)H * W, R(0));
+    for (int o = 0; o < P * Q; ++o) d[idx[(size_t)nc * P * Q + o]] += dy[(size_t)nc * P * Q + o];
+  }
+}
+
+// loss = (1/M) sum (s-t)^2 ; ds = 2 (s-t) / M
+template <class R>
+R mse(const R* s, const R* t, R* ds, size_t M) {
+  R acc = 0;
+  for (size_t i = 0; i < M; ++i) {
+    const R d = s[i] - t[i];
+    acc += d * d;
+    if (ds) ds[i] = R(2) * d / (R)M;
+  }
+  return acc / (R)M;
+}
+
+// v <- mu v + g ; w <- w - lr v
+template <class R>
+void sgd(R* w, R* v, const R* g, size_t n, R lr, R mu) {
+  for (size_t i = 0; i < n; ++i) {
+    v[i] = mu * v[i] + g[i];
+    w[i] = w[i] - lr * v[i];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// descriptor
+// ---------------------------------------------------------------------------
+
+struct OpD {
+  int type, nin, in[8], c_out, k, stride, pad, groups, act, pofs;
+};
+struct Shape {
+  int c, h, w;
+  size_t numel() const { return (size_t)c * h * w; }
+};
+struct BlockD {
+  std::vector<OpD> ops;
+  std::vector<Shape> shapes;  // value 0 = block input
+};
+
+struct Desc {
+  int B = 0;
+  Shape in{};
+  std::vector<BlockD> net[2];
+  std::vector<double> pool;
+  std::vector<Shape> act;  // A_0..A_B
+
+  bool parse(const int32_t* w, int nw, const double* p, int np, std::string& err) {
+    if (nw < 6 || w[0] != kMagic || w[1] != 1) { err = "bad header"; return false; }
+    B = w[2];
+    in = {w[3], w[4], w[5]};
+    pool.assign(p, p + np);
+    int pos = 6;
+    for (int which = 0; which < 2; ++which) {
+      Shape cur = in;
+      for (int b = 0; b < B; ++b) {
+        if (pos >= nw) { err = "truncated"; return false; }
+        BlockD blk;
+        const int nops = w[pos++];
+        blk.shapes.push_back(cur);
+        for (int j = 0; j < nops; ++j, pos += kRec) {
+          if (pos + kRec > nw) { err = "truncated"; return false; }
+          const int32_t* r = w + pos;
+          OpD o{};
+          o.type = r[0]; o.nin = r[1];
+          for (int i = 0; i < 8; ++i) o.in[i] = r[2 + i];
+          o.c_out = r[10]; o.k = r[11]; o.stride = r[12]; o.pad = r[13];
+          o.groups = r[14]; o.act = r[15]; o.pofs = r[16];
+          for (int i = 0; i < o.nin; ++i)
+            if (o.in[i] < 0 || o.in[i] > j) { err = "input refers forward"; return false; }
+          const Shape s = blk.shapes[o.in[0]];
+          Shape out = s;
+          if (o.type == OP_CBA) {
+            if (o.groups != 1 && (o.groups != s.c || o.c_out != s.c)) { err = "groups"; return false; }
+            out = {o.c_out, out_dim(s.h, o.k, o.stride, o.pad), out_dim(s.w, o.k, o.stride, o.pad)};
+          } else if (o.type == OP_POOL) {
+            out = {s.c, out_dim(s.h, o.k, o.stride, o.pad), out_dim(s.w, o.k, o.stride, o.pad)};
+          } else if (o.type == OP_ADD || o.type == OP_MIX) {
+            for (int i = 1; i < o.nin; ++i) {
+              const Shape t = blk.shapes[o.in[i]];
+              if (t.c != s.c || t.h != s.h || t.w != s.w) { err = "join shapes"; return false; }
+            }
+          } else { err = "op type"; return false; }
+          blk.ops.push_back(o);
+          blk.shapes.push_back(out);
+        }
+        cur = blk.shapes.back();
+        net[which].push_back(std::move(blk));
+      }
+    }
+    act.clear();
+    act.push_back(in);
+    for (int b = 0; b < B; ++b) {
+      const Shape t = net[0][b].shapes.back(), s = net[1][b].shapes.back();
+      if (t.c != s.c || t.h != s.h || t.w != s.w) { err = "teacher/student block shapes differ"; return false; }
+      act.push_back(t);
+    }
+    return true;
+  }
+};
+
+// ---------------------------------------------------------------------------
+// networks
+// ---------------------------------------------------------------------------
+
+struct NetBase {
+  virtual ~NetBase() = default;
+  virtual int set_tensor(int kind, int net, int b, int j, int slot, const double* d, long n) = 0;
+  virtual int get_tensor(int kind, int net, int b, int j, int slot, double* d, long n) = 0;
+  virtual void teacher_relay(const double* x) = 0;
+  virtual void teacher_upto(const double* x, int i, double* out) = 0;
+  virtual long act_numel(int i) = 0;
+  virtual void get_act(int i, double* out) = 0;
+  virtual double student_step(int i, const double* a_prev, const double* a_i, double lr, int mode) = 0;
+  virtual void relay_step(const double* x, double lr, double* losses) = 0;
+  virtual void redundant_step(const double* x, double lr, double* losses) = 0;
+  virtual long value_numel(int b, int v) = 0;
+  virtual void get_value(int b, int v, double* out) = 0;
+};
+
+template <class R>
+struct Cba {
+  std::vector<R> p[5];  // weight, gamma, beta, running mean, running var
+  std::vector<R> g[3];  // gradients of weight, gamma, beta
+  std::vector<R> v[3];  // momentum
+};
+
+template <class R>
+struct Net final : NetBase {
+  Desc d;
+  int N;
+  R mu, eps, rho;
+  std::vector<std::vector<Cba<R>>> par[2];  // [net][block][op]
+  std::vector<std::vector<R>> A;            // relay store A_0..A_B
+  // student forward state of the block last run
+  struct Saved {
+    std::vector<R> conv, mean, var, pre;  // CBA: conv output, batch stats, BN output
+    std::vector<int32_t> idx;             // POOL
+  };
+  std::vector<std::vector<std::vector<R>>> val;  // [block][value]
+  std::vector<std::vector<Saved>> saved;         // [block][op]
+
+  Net(const Desc& desc, int batch, double momentum, double e, double r)
+      : d(desc), N(batch), mu((R)momentum), eps((R)e), rho((R)r) {
+    for (int which = 0; which < 2; ++which) {
+      par[which].resize(d.B);
+      for (int b = 0; b < d.B; ++b) {
+        const BlockD& blk = d.net[which][b];
+        par[which][b].resize(blk.ops.size());
+        for (size_t j = 0; j < blk.ops.size(); ++j) {
+          const OpD& o = blk.ops[j];
+          if (o.type != OP_CBA) continue;
+          const int cin = blk.shapes[o.in[0]].c;
+          Cba<R>& c = par[which][b][j];
+          c.p[0].assign((size_t)o.c_out * (cin / o.groups) * o.k * o.k, R(0));
+          c.p[1].assign(o.c_out, R(1));
+          c.p[2].assign(o.c_out, R(0));
+          c.p[3].assign(o.c_out, R(0));
+          c.p[4].assign(o.c_out, R(1));
+          for (int s = 0; s < 3; ++s) {
+            c.g[s].assign(c.p[s].size(), R(0));
+            c.v[s].assign(c.p[s].size(), R(0));
+          }
+        }
+      }
+    }
+    A.resize(d.B + 1);
+    val.resize(d.B);
+    saved.resize(d.B);
+  }
+
+  std::vector<R>* find(int kind, int net, int b, int j, int slot) {
+    if (net < 0 || net > 1 || b < 0 || b >= d.B) return nullptr;
+    if (j < 0 || j >= (int)d.net[net][b].ops.size()) return nullptr;
+    if (d.net[net][b].ops[j].type != OP_CBA) return nullptr;
+    Cba<R>& c = par[net][b][j];
+    if (kind == 0 && slot >= 0 && slot < 5) return &c.p[slot];
+    if (kind == 1 && slot >= 0 && slot < 3) return &c.g[slot];
+    if (kind == 2 && slot >= 0 && slot < 3) return &c.v[slot];
+    return nullptr;
+  }
+  int set_tensor(int kind, int net, int b, int j, int slot, const double* src, long n) override {
+    auto* t = find(kind, net, b, j, slot);
+    if (!t || (long)t->size() != n) return -1;
+    for (long i = 0; i < n; ++i) (*t)[i] = (R)src[i];
+    return 0;
+  }
+  int get_tensor(int kind, int net, int b, int j, int slot, double* dst, long n) override {
+    auto* t = find(kind, net, b, j, slot);
+    if (!t || (long)t->size() != n) return -1;
+    for (long i = 0; i < n; ++i) dst[i] = (double)(*t)[i];
+    return 0;
+  }
+
+  // ---- teacher: every op in inference mode --------------------------------
+  std::vector<R> teacher_block(int b, const std::vector<R>& x) {
+    const BlockD& blk = d.net[0][b];
+    std::vector<std::vector<R>> v(blk.ops.size() + 1);
+    v[0] = x;
+    for (size_t j = 0; j < blk.ops.size(); ++j) {
+      const OpD& o = blk.ops[j];
+      const Shape si = blk.shapes[o.in[0]], so = blk.shapes[j + 1];
+      std::vector<R>& out = v[j + 1];
+      out.assign((size_t)N * so.numel(), R(0));
+      if (o.type == OP_CBA) {
+        const Cba<R>& c = par[0][b][j];
+        std::vector<R> y(out.size());
+        conv_fwd(v[o.in[0]].data(), c.p[0].data(), y.data(), N, si.c, si.h, si.w, so.c, o.k,
+                 o.stride, o.pad, o.groups);
+        bn_eval(y.data(), c.p[1].data(), c.p[2].data(), c.p[3].data(), c.p[4].data(), y.data(), N,
+                so.c, so.h * so.w, eps);
+        act_fwd(y.data(), out.data(), out.size(), o.act);
+      } else if (o.type == OP_POOL) {
+        std::vector<int32_t> idx(out.size());
+        maxpool_fwd(v[o.in[0]].data(), out.data(), idx.data(), N, si.c, si.h, si.w, o.k, o.stride,
+                    o.pad);
+      } else if (o.type == OP_ADD) {
+        for (size_t i = 0; i < out.size(); ++i) out[i] = v[o.in[0]][i] + v[o.in[1]][i];
+        act_fwd(out.data(), out.data(), out.size(), o.act);
+      } else {  // OP_MIX
+        for (int k = 0; k < o.nin; ++k) {
+          const R p = (R)d.pool[o.pofs + k];
+          for (size_t i = 0; i < out.size(); ++i) out[i] += p * v[o.in[k]][i];
+        }
+      }
+    }
+    return v.back();
+  }
+
+  void teacher_relay(const double* x) override {
+    A[0].resize((size_t)N * d.in.numel());
+    for (size_t i = 0; i < A[0].size(); ++i) A[0][i] = (R)x[i];
+    for (int b = 0; b < d.B; ++b) A[b + 1] = teacher_block(b, A[b]);  // each T_i once
+  }
+  // A_i recomputed from the raw input, T_1..T_i (the baseline's redundant work)
+  std::vector<R> teacher_from_start(const double* x, int i) {
+    std::vector<R> cur((size_t)N * d.in.numel());
+    for (size_t k = 0; k < cur.size(); ++k) cur[k] = (R)x[k];
+    for (int b = 0; b < i; ++b) cur = teacher_block(b, cur);
+    return cur;
+  }
+  void teacher_upto(const double* x, int i, double* out) override {
+    std::vector<R> a = teacher_from_start(x, i);
+    for (size_t k = 0; k < a.size(); ++k) out[k] = (double)a[k];
+  }
+  long act_numel(int i) override { return (long)N * (long)d.act[i].numel(); }
+  void get_act(int i, double* out) override {
+    for (size_t k = 0; k < A[i].size(); ++k) out[k] = (double)A[i][k];
+  }
+
+  // ---- student -------------------------------------------------------------
+  void student_forward(int b, const std::vector<R>& x) {
+    const BlockD& blk = d.net[1][b];
+    auto& v = val[b];
+    auto& sv = saved[b];
+    v.assign(blk.ops.size() + 1, {});
+    sv.assign(blk.ops.size(), {});
+    v[0] = x;
+    for (size_t j = 0; j < blk.ops.size(); ++j) {
+      const OpD& o = blk.ops[j];
+      const Shape si = blk.shapes[o.in[0]], so = blk.shapes[j + 1];
+      std::vector<R>& out = v[j + 1];
+      out.assign((size_t)N * so.numel(), R(0));
+      if (o.type == OP_CBA) {
+        const Cba<R>& c = par[1][b][j];
+        Saved& s = sv[j];
+        s.conv.resize(out.size());
+        s.pre.resize(out.size());
+        s.mean.resize(so.c);
+        s.var.resize(so.c);
+        conv_fwd(v[o.in[0]].data(), c.p[0].data(), s.conv.data(), N, si.c, si.h, si.w, so.c, o.k,
+                 o.stride, o.pad, o.groups);
+        bn_train_fwd(s.conv.data(), c.p[1].data(), c.p[2].data(), s.pre.data(), s.mean.data(),
+                     s.var.data(), N, so.c, so.h * so.w, eps);
+        act_fwd(s.pre.data(), out.data(), out.size(), o.act);
+      } else if (o.type == OP_POOL) {
+        sv[j].idx.resize(out.size());
+        maxpool_fwd(v[o.in[0]].data(), out.data(), sv[j].idx.data(), N, si.c, si.h, si.w, o.k,
+                    o.stride, o.pad);
+      } else if (o.type == OP_ADD) {
+        sv[j].pre.resize(out.size());
+        for (size_t i = 0; i < out.size(); ++i) sv[j].pre[i] = v[o.in[0]][i] + v[o.in[1]][i];
+        act_fwd(sv[j].pre.data(), out.data(), out.size(), o.act);
+      } else {
+        for (int k = 0; k < o.nin; ++k) {
+          const R p = (R)d.pool[o.pofs + k];
+          for (size_t i = 0; i < out.size(); ++i) out[i] += p * v[o.in[k]][i];
+        }
+      }
+    }
+  }
+
+  void update_running_stats(int b) {
+    const BlockD& blk = d.net[1][b];
+    for (size_t j = 0; j < blk.ops.size(); ++j) {
+      if (blk.ops[j].type != OP_CBA) continue;
+      const Shape so = blk.shapes[j + 1];
+      const R m = (R)N * (R)(so.h * so.w);
+      Cba<R>& c = par[1][b][j];
+      for (int k = 0; k < so.c; ++k) {
+        c.p[3][k] = (R(1) - rho) * c.p[3][k] + rho * saved[b][j].mean[k];
+        c.p[4][k] = (R(1) - rho) * c.p[4][k] + rho * saved[b][j].var[k] * m / (m - R(1));
+      }
+    }
+  }
+
+  // gradient of loss_i w.r.t. every parameter of S_i; dval[0] (w.r.t. A_{i-1}) is never formed
+  void student_backward(int b, std::vector<R>& dout) {
+    const BlockD& blk = d.net[1][b];
+    auto& v = val[b];
+    std::vector<std::vector<R>> dv(blk.ops.size() + 1);
+    dv.back() = std::move(dout);
+    auto accumulate = [&](int id, const std::vector<R>& gsrc) {
+      if (id == 0) return;  // the teacher activation is a constant
+      if (dv[id].empty()) dv[id] = gsrc;
+      else for (size_t i = 0; i < gsrc.size(); ++i) dv[id][i] += gsrc[i];
+    };
+    for (int j = (int)blk.ops.size() - 1; j >= 0; --j) {
+      const OpD& o = blk.ops[j];
+      const Shape si = blk.shapes[o.in[0]], so = blk.shapes[j + 1];
+      std::vector<R>& dy = dv[j + 1];
+      if (dy.empty()) continue;  // value feeds nothing on the way to the loss
+      if (o.type == OP_CBA) {
+        Cba<R>& c = par[1][b][j];
+        Saved& s = saved[b][j];
+        std::vector<R> dpre(dy.size()), dconv(dy.size());
+        act_bwd(dy.data(), s.pre.data(), dpre.data(), dy.size(), o.act);
+        bn_train_bwd(dpre.data(), s.conv.data(), c.p[1].data(), s.mean.data(), s.var.data(),
+                     dconv.data(), c.g[1].data(), c.g[2].data(), N, so.c, so.h * so.w, eps);
+        conv_wgrad(dconv.data(), v[o.in[0]].data(), c.g[0].data(), N, si.c, si.h, si.w, so.c, o.k,
+                   o.stride, o.pad, o.groups);
+        if (o.in[0] != 0) {
+          std::vector<R> dx((size_t)N * si.numel());
+          conv_dgrad(dconv.data(), c.p[0].data(), dx.data(), N, si.c, si.h, si.w, so.c, o.k,
+                     o.stride, o.pad, o.groups);
+          accumulate(o.in[0], dx);
+        }
+      } else if (o.type == OP_POOL) {
+        if (o.in[0] != 0) {
+          std::vector<R> dx((size_t)N * si.numel());
+          maxpool_bwd(dy.data(), saved[b][j].idx.data(), dx.data(), N, si.c, si.h, si.w, so.h, so.w);
+          accumulate(o.in[0], dx);
+        }
+      } else if (o.type == OP_ADD) {
+        std::vector<R> dpre(dy.size());
+        act_bwd(dy.data(), saved[b][j].pre.data(), dpre.data(), dy.size(), o.act);
+        accumulate(o.in[0], dpre);
+        accumulate(o.in[1], dpre);
+      } else {
+        for (int k = 0; k < o.nin; ++k) {
+          const R p = (R)d.pool[o.pofs + k];
+          std::vector<R> g(dy.size());
+          for (size_t i = 0; i < dy.size(); ++i) g[i] = p * dy[i];
+          accumulate(o.in[k], g);
+        }
+      }
+      std::vector<R>().swap(dy);
+    }
+  }
+
+  // mode 0: loss only (no state change); 1: loss + gradients; 2: full step
+  R student_step_r(int i, const std::vector<R>& a_prev, const std::vector<R>& a_i, R lr, int mode) {
+    const int b = i - 1;
+    student_forward(b, a_prev);
+    const std::vector<R>& s = val[b].back();
+    std::vector<R> ds(mode ? s.size() : 0);
+    const R loss = mse(s.data(), a_i.data(), mode ? ds.data() : nullptr, s.size());
+    if (mode == 0) return loss;
+    student_backward(b, ds);
+    if (mode == 2) {
+      update_running_stats(b);
+      for (Cba<R>& c : par[1][b])
+        for (int t = 0; t < 3; ++t)
+          if (!c.p[t].empty()) sgd(c.p[t].data(), c.v[t].data(), c.g[t].data(), c.p[t].size(), lr, mu);
+    }
+    return loss;
+  }
+  double student_step(int i, const double* a_prev, const double* a_i, double lr, int mode) override {
+    std::vector<R> ap((size_t)N * d.act[i - 1].numel()), ai((size_t)N * d.act[i].numel());
+    for (size_t k = 0; k < ap.size(); ++k) ap[k] = (R)a_prev[k];
+    for (size_t k = 0; k < ai.size(); ++k) ai[k] = (R)a_i[k];
+    return (double)student_step_r(i, ap, ai, (R)lr, mode);
+  }
+
+  // teacher once, activations kept; every student block trained on (A_{i-1}, A_i)
+  void relay_step(const double* x, double lr, double* losses) override {
+    teacher_relay(x);
+    for (int i = 1; i <= d.B; ++i) losses[i - 1] = (double)student_step_r(i, A[i - 1], A[i], (R)lr, 2);
+  }
+  // block by block, teacher re-run from the input each time (Sec. II-B baseline)
+  void redundant_step(const double* x, double lr, double* losses) override {
+    for (int i = 1; i <= d.B; ++i) {
+      std::vector<R> a_prev = teacher_from_start(x, i - 1);
+      std::vector<R> a_i = teacher_block(i - 1, a_prev);
+      losses[i - 1] = (double)student_step_r(i, a_prev, a_i, (R)lr, 2);
+    }
+  }
+  long value_numel(int b, int v) override {
+    if (b < 0 || b >= d.B || v < 0 || v >= (int)val[b].size()) return -1;
+    return (long)val[b][v].size();
+  }
+  void get_value(int b, int v, double* out) override {
+    for (size_t k = 0; k < val[b][v].size(); ++k) out[k] = (double)val[b][v][k];
+  }
+};
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// C interface for the ctypes wrapper (doubles at the boundary in both precisions)
+// ---------------------------------------------------------------------------
+extern "C" {
+
+void* orc_create(const int32_t* words, int nwords, const double* pool, int npool, int batch,
+                 int precision, double momentum, double eps, double rho) {
+  Desc d;
+  std::string err;
+  if (!d.parse(words, nwords, pool, npool, err)) return nullptr;
+  if (precision == 64) return new Net<double>(d, batch, momentum, eps, rho);
+  if (precision == 32) return new Net<float>(d, batch, momentum, eps, rho);
+  return nullptr;
+}
+void orc_destroy(void* h) { delete static_cast<NetBase*>(h); }
+int orc_set_tensor(void* h, int kind, int net, int b, int j, int slot, const double* d, long n) {
+  return static_cast<NetBase*>(h)->set_tensor(kind, net, b, j, slot, d, n);
+}
+int orc_get_tensor(void* h, int kind, int net, int b, int j, int slot, double* d, long n) {
+  return static_cast<NetBase*>(h)->get_tensor(kind, net, b, j, slot, d, n);
+}
+void orc_teacher_relay(void* h, const double* x) { static_cast<NetBase*>(h)->teacher_relay(x); }
+void orc_teacher_upto(void* h, const double* x, int i, double* out) {
+  static_cast<NetBase*>(h)->teacher_upto(x, i, out);
+}
+long orc_act_numel(void* h, int i) { return static_cast<NetBase*>(h)->act_numel(i); }
+void orc_get_act(void* h, int i, double* out) { static_cast<NetBase*>(h)->get_act(i, out); }
+double orc_student_step(void* h, int i, const double* a_prev, const double* a_i, double lr, int mode) {
+  return static_cast<NetBase*>(h)->student_step(i, a_prev, a_i, lr, mode);
+}
+void orc_relay_step(void* h, const double* x, double lr, double* losses) {
+  static_cast<NetBase*>(h)->relay_step(x, lr, losses);
+}
+void orc_redundant_step(void* h, const double* x, double lr, double* losses) {
+  static_cast<NetBase*>(h)->redundant_step(x, lr, losses);
+}
+long orc_value_numel(void* h, int b, int v) { return static_cast<NetBase*>(h)->value_numel(b, v); }
+void orc_get_value(void* h, int b, int v, double* out) { static_cast<NetBase*>(h)->get_value(b, v, out); }
+int orc_num_threads() {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+// fp64 primitives, exported one by one so that each can be pinned on its own
+void orc_conv_fwd(const double* x, const double* w, double* y, int N, int C, int H, int W, int K,
+                  int k, int stride, int pad, int groups) {
+  conv_fwd(x, w, y, N, C, H, W, K, k, stride, pad, groups);
+}
+void orc_conv_dgrad(const double* dy, const double* w, double* dx, int N, int C, int H, int W,
+                    int K, int k, int stride, int pad, int groups) {
+  conv_dgrad(dy, w, dx, N, C, H, W, K, k, stride, pad, groups);
+}
+void orc_conv_wgrad(const double* dy, const double* x, double* dw, int N, int C, int H, int W,
+                    int K, int k, int stride, int pad, int groups) {
+  conv_wgrad(dy, x, dw, N, C, H, W, K, k, stride, pad, groups);
+}
+void orc_bn_train_fwd(const double* x, const double* gamma, const double* beta, double* y,
+                      double* mean, double* var, int N, int C, int HW, double eps) {
+  bn_train_fwd(x, gamma, beta, y, mean, var, N, C, HW, eps);
+}
+void orc_bn_train_bwd(const double* dy, const double* x, const double* gamma, const double* mean,
+                      const double* var, double* dx, double* dgamma, double* dbeta, int N, int C,
+                      int HW, double eps) {
+  bn_train_bwd(dy, x, gamma, mean, var, dx, dgamma, dbeta, N, C, HW, eps);
+}
+void orc_bn_eval(const double* x, const double* gamma, const double* beta, const double* rmean,
+                 const double* rvar, double* y, int N, int C, int HW, double eps) {
+  bn_eval(x, gamma, beta, rmean, rvar, y, N, C, HW, eps);
+}
+void orc_act_fwd(const double* x, double* y, long n, int act) { act_fwd(x, y, (size_t)n, act); }
+void orc_act_bwd(const double* dy, const double* x, double* dx, long n, int act) {
+  act_bwd(dy, x, dx, (size_t)n, act);
+}
+void orc_maxpool_fwd(const double* x, double* y, int32_t* idx, int N, int C, int H, int W, int k,
+                     int stride, int pad) {
+  maxpool_fwd(x, y, idx, N, C, H, W, k, stride, pad);
+}
+void orc_maxpool_bwd(const double* dy, const int32_t* idx, double* dx, int N, int C, int H, int W,
+                     int P, int Q) {
+  maxpool_bwd(dy, idx, dx, N, C, H, W, P, Q);
+}
+double orc_mse(const double* s, const double* t, double* ds, long M) { return mse(s, t, ds, (size_t)M); }
+void orc_sgd(double* w, double* v, const double* g, long n, double lr, double mu) {
+  sgd(w, v, g, (size_t)n, lr, mu);
+}
+
+}  // extern "C"

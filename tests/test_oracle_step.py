@@ -1,0 +1,147 @@
+"""Pins for the oracle's whole step: PyTorch CPU fp64 autograd on the same
+blocks, central finite differences of loss_i, and the paper's invariants
+(Abstract / Sec. VII-D: relaying changes the schedule, not the mathematics;
+Sec. IV-B: student blocks do not depend on each other's weights)."""
+import numpy as np
+import pytest
+import torch
+
+import torch_ref
+from helpers import make_oracle, max_rel, pattern_workloads
+from oracle import pbd_oracle as orc
+from paper_2301_12443_amd import workloads as W
+
+WORKLOADS = [W.tiny_cnn(batch=4)] + pattern_workloads()
+IDS = [w.name for w in WORKLOADS]
+
+
+@pytest.mark.parametrize("wl", WORKLOADS, ids=IDS)
+def test_step_matches_pytorch_autograd(wl):
+    """Three consecutive steps: activations, losses, gradients, momentum, weights, running stats."""
+    o = make_oracle(wl)
+    shapes = W.activation_shapes(wl)
+    tpar = [torch_ref.block_params(wl, W.NET_TEACHER, b, False) for b in range(wl.B)]
+    spar = [torch_ref.block_params(wl, W.NET_STUDENT, b, True) for b in range(wl.B)]
+    mom = [{k: torch.zeros_like(v) for k, v in p.items() if v.requires_grad} for p in spar]
+    for step in range(3):
+        x = W.make_input(wl, step=step)
+        acts = o.teacher_relay(x)
+        a = torch.from_numpy(x).double()
+        for b in range(wl.B):
+            a_prev = a
+            with torch.no_grad():
+                a, _ = torch_ref.run_block(wl.teacher[b], a_prev, tpar[b], train=False)
+            np.testing.assert_allclose(acts[b + 1].reshape(a.shape), a.numpy(), rtol=0, atol=1e-11)
+            loss_o = o.student_step(b + 1, acts[b], acts[b + 1], wl.lr)
+            s_out, stats = torch_ref.run_block(wl.student[b], a_prev, spar[b], train=True)
+            loss_t = torch.mean((s_out - a) ** 2)
+            assert abs(loss_o - loss_t.item()) <= 1e-11 * abs(loss_t.item())
+            keys = [k for k, v in spar[b].items() if v.requires_grad]
+            grads = torch.autograd.grad(loss_t, [spar[b][k] for k in keys])
+            m = wl.batch * np.prod(shapes[b + 1][1:])
+            with torch.no_grad():
+                for k, g in zip(keys, grads):
+                    go = o.get_tensor(orc.KIND_GRAD, W.NET_STUDENT, b, k[0], k[1], g.shape)
+                    assert max_rel(go, g.numpy()) < 1e-9, (step, b, k)
+                    mom[b][k].mul_(wl.momentum).add_(g)
+                    spar[b][k].sub_(wl.lr * mom[b][k])
+                    wo = o.get_tensor(orc.KIND_PARAM, W.NET_STUDENT, b, k[0], k[1], g.shape)
+                    vo = o.get_tensor(orc.KIND_MOMENTUM, W.NET_STUDENT, b, k[0], k[1], g.shape)
+                    assert max_rel(wo, spar[b][k].numpy()) < 1e-10
+                    assert max_rel(vo, mom[b][k].numpy()) < 1e-9
+                for j, (mu, var) in stats.items():
+                    cnt = wl.batch * np.prod(W.block_shapes(wl.student[b], shapes[b])[j + 1][1:])
+                    rm, rv = spar[b][(j, W.P_RMEAN)], spar[b][(j, W.P_RVAR)]
+                    rm.mul_(0.9).add_(0.1 * mu)
+                    rv.mul_(0.9).add_(0.1 * var * cnt / (cnt - 1))
+                    # (a 1x1 conv fed by a zero-mean BN output has mean ~1e-17: absolute floor)
+                    np.testing.assert_allclose(o.get_tensor(0, 1, b, j, W.P_RMEAN, rm.shape), rm.numpy(),
+                                               rtol=1e-10, atol=1e-14)
+                    np.testing.assert_allclose(o.get_tensor(0, 1, b, j, W.P_RVAR, rv.shape), rv.numpy(),
+                                               rtol=1e-10, atol=1e-14)
+
+
+@pytest.mark.parametrize("wl", WORKLOADS, ids=IDS)
+def test_gradients_match_finite_differences(wl):
+    """Directional central differences of loss_i over each parameter tensor."""
+    o = make_oracle(wl)
+    rng = np.random.default_rng(5)
+    x = W.make_input(wl)
+    acts = o.teacher_relay(x)
+    for b in range(wl.B):
+        o.student_step(b + 1, acts[b], acts[b + 1], 0.0, orc.MODE_GRADS)
+        for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+            if slot not in (W.P_WEIGHT, W.P_GAMMA, W.P_BETA):
+                continue
+            g = o.get_tensor(orc.KIND_GRAD, W.NET_STUDENT, b, j, slot, shape)
+            w0 = o.get_tensor(orc.KIND_PARAM, W.NET_STUDENT, b, j, slot, shape)
+            d = rng.standard_normal(shape)
+            an = float(np.sum(g * d))
+            scale = np.linalg.norm(g) * np.linalg.norm(d) + 1e-12
+            # A ReLU / max-pool kink inside [-h, h] spoils a central difference by a fixed
+            # amount, so shrink h until the interval is kink-free (intervals are nested).
+            errs = []
+            for h in (1e-6, 2e-7, 4e-8):
+                o.set_param(W.NET_STUDENT, b, j, slot, w0 + h * d)
+                lp = o.student_step(b + 1, acts[b], acts[b + 1], 0.0, orc.MODE_LOSS)
+                o.set_param(W.NET_STUDENT, b, j, slot, w0 - h * d)
+                lm = o.student_step(b + 1, acts[b], acts[b + 1], 0.0, orc.MODE_LOSS)
+                errs.append(abs((lp - lm) / (2 * h) - an))
+                if errs[-1] <= 1e-5 * scale + 5e-9:
+                    break
+            o.set_param(W.NET_STUDENT, b, j, slot, w0)
+            assert min(errs) <= 1e-5 * scale + 5e-9, (b, j, slot, an, errs)
+
+
+@pytest.mark.parametrize("wl", WORKLOADS, ids=IDS)
+def test_relay_equals_redundant_baseline_bitwise(wl):
+    """Teacher relaying removes redundant teacher work without changing any number."""
+    a, r = make_oracle(wl), make_oracle(wl)
+    for step in range(2):
+        x = W.make_input(wl, step=step)
+        la, lr_ = a.relay_step(x, wl.lr), r.redundant_step(x, wl.lr)
+        np.testing.assert_array_equal(la, lr_)
+        for i in range(wl.B + 1):
+            np.testing.assert_array_equal(a.teacher_relay(x)[i], a.teacher_upto(x, i))
+    for b in range(wl.B):
+        for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+            np.testing.assert_array_equal(a.get_tensor(0, 1, b, j, slot, shape),
+                                          r.get_tensor(0, 1, b, j, slot, shape))
+
+
+def test_block_order_does_not_matter():
+    """Decoupled updates are legal because blocks share no parameters (Sec. IV-B)."""
+    wl = W.tiny_cnn(batch=4)
+    a, r = make_oracle(wl), make_oracle(wl)
+    x = W.make_input(wl)
+    acts = a.teacher_relay(x)
+    la = [a.student_step(i, acts[i - 1], acts[i], wl.lr) for i in (1, 2, 3, 4)]
+    order = (3, 1, 4, 2)
+    lr_ = dict((i, r.student_step(i, acts[i - 1], acts[i], wl.lr)) for i in order)
+    assert la == [lr_[i] for i in (1, 2, 3, 4)]
+    for b in range(wl.B):
+        for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+            np.testing.assert_array_equal(a.get_tensor(0, 1, b, j, slot, shape),
+                                          r.get_tensor(0, 1, b, j, slot, shape))
+
+
+def test_student_input_is_the_teacher_activation_and_gets_no_gradient():
+    """S_i and T_i read the same A_{i-1}; value 0 of every student block is that array."""
+    wl = W.tiny_cnn(batch=2)
+    o = make_oracle(wl)
+    acts = o.teacher_relay(W.make_input(wl))
+    for i in range(1, wl.B + 1):
+        o.student_step(i, acts[i - 1], acts[i], 0.0, orc.MODE_LOSS)
+        np.testing.assert_array_equal(o.value(i - 1, 0), acts[i - 1])
+
+
+def test_fp32_instance_tracks_fp64():
+    wl = W.tiny_cnn(batch=4)
+    a, f = make_oracle(wl), make_oracle(wl, precision=32)
+    x = W.make_input(wl)
+    la, lf = a.relay_step(x, wl.lr), f.relay_step(x, wl.lr)
+    assert np.max(np.abs(la - lf) / la) < 1e-5
+    for b in range(wl.B):
+        for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+            if slot <= W.P_BETA:
+                assert max_rel(f.get_tensor(1, 1, b, j, slot, shape), a.get_tensor(1, 1, b, j, slot, shape)) < 1e-4
