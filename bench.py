@@ -1,0 +1,123 @@
+"""Throughput of the full relay distillation step on one MI355X.
+
+A step = pbd_distill_step: cast x, teacher relay T_1..T_B (each block once, activations kept in
+HBM), then for every student block forward, MSE loss + gradient, backward and the SGD-momentum
+update.  Prints ONE JSON line (see README for the fields)."""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
+
+
+def roofline_from_profile(prof, steps):
+    """Aggregate the library's per-launch HIP-event timings by kernel class; report the class that
+    takes the most time against the roofline that bounds it."""
+    agg = {}
+    for p in prof:
+        a = agg.setdefault(p["name"], dict(ms=0.0, bytes=0.0, flops=0.0, n=0))
+        a["ms"] += p["ms"]; a["bytes"] += p["bytes"]; a["flops"] += p["flops"]; a["n"] += 1
+    name, a = max(agg.items(), key=lambda kv: kv[1]["ms"])
+    avg_s = a["ms"] / a["n"] * 1e-3
+    ai = a["flops"] / a["bytes"] if a["bytes"] else 0.0
+    if ai >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        achieved, peak, unit, bound = a["flops"] / a["n"] / avg_s / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s", "mfma"
+    else:
+        achieved, peak, unit, bound = a["bytes"] / a["n"] / avg_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+    classes = {k: dict(ms_per_step=round(v["ms"] / steps, 4), launches_per_step=v["n"] // steps,
+                       gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] else 0.0,
+                       tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] else 0.0)
+               for k, v in sorted(agg.items(), key=lambda kv: -kv[1]["ms"])}
+    return dict(bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit, frac=round(achieved / peak, 4),
+                traffic=None, kernel=name, avg_launch_us=round(avg_s * 1e6, 2),
+                launches_per_step=a["n"] // steps), classes
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands (fp32 instance, OpenMP), timed on the host cores on the same workload."""
+    from oracle import pbd_oracle as orc
+    from paper_2301_12443_amd import workloads as W
+    words, pool = W.pack(wl)
+    o = orc.Oracle(words, pool, wl.batch, precision=32, momentum=wl.momentum)
+    for net, b, j, slot, arr in W.iter_params(wl):
+        o.set_param(net, b, j, slot, arr)
+    x = W.make_input(wl)
+    o.relay_step(x, wl.lr)                      # first-touch
+    t0 = time.time()
+    n = 2
+    for _ in range(n):
+        o.relay_step(x, wl.lr)
+    dt = (time.time() - t0) / n
+    return dict(value=round(wl.batch / dt, 1), unit="samples/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"fp32 oracle relay_step, full batch {wl.batch}, mean of {n} steps after 1 warm-up")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="vgg16_dsconv")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--classes", action="store_true", help="also print the per-kernel-class table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU relay step only: run with --gpus 1 "
+              "(this build has no multi-GPU path; DESIGN.md says how it would shard)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2301_12443_amd import pbd, workloads as W
+    wl = W.CONFIGS[args.config]()
+    d = pbd.Distiller(wl)
+    d.bind("cuda:0")
+    d.load_params()
+    x = torch.from_numpy(W.make_input(wl)).cuda()       # resident in HBM before the timed region
+
+    for _ in range(args.warmup):
+        d.distill_step(x, wl.lr)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        d.distill_step(x, wl.lr)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    losses = d.losses.cpu().numpy()
+    assert all(l == l and l > 0 for l in losses), losses
+
+    # per-kernel timings with HIP events on the library's stream (separate, profiled steps)
+    psteps = 5
+    d.set_profile(True); d.reset_profile()
+    for _ in range(psteps):
+        d.distill_step(x, wl.lr)
+    prof = d.get_profile()
+    d.set_profile(False)
+    roof, classes = roofline_from_profile(prof, psteps)
+    if args.classes:
+        for k, v in classes.items():
+            print(f"{k:24s} {v}", file=sys.stderr)
+
+    rec = {
+        "metric": "distillation samples/sec/GPU (full relay step)",
+        "value": round(wl.batch * args.steps / dt, 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.precision == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: batch {wl.batch}, input {wl.in_shape}, {wl.B} blocks, "
+                               "teacher relay + student fwd/MSE/bwd/SGD-momentum", "lr": wl.lr},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

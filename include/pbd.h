@@ -1,0 +1,157 @@
+/* pbd.h - C ABI of the MI355X blockwise-distillation library (libpbd.so).
+ *
+ * One GPU runs the whole step of blockwise distillation (Sec. II-A): the frozen
+ * teacher is evaluated once, block by block, and every activation
+ * A_0 = x, A_i = T_i(A_{i-1}) stays resident in device memory ("internal
+ * relaying", Sec. VII-A; the one-device form of teacher relaying, Sec. IV-A).
+ * Student block S_i then reads A_{i-1}, is compared with A_i by a mean squared
+ * error, is back-propagated and is updated at once with SGD-momentum
+ * (Algorithm 1: load, T.forward, S.forward, S.backward(L), update_weight; the
+ * update needs no barrier because blocks share no parameters, Sec. IV-B).
+ *
+ * Conventions
+ *  - Every function returns PBD_OK (0) or a negative pbd_status; nothing throws
+ *    or aborts.  pbd_last_error() gives the text of the last failure of a context.
+ *    Arguments are validated on the host before any kernel is launched.
+ *  - "host" pointers are ordinary CPU memory; "device" pointers are HIP device
+ *    memory owned by the caller.  The library never allocates device memory: the
+ *    caller hands it one workspace (pbd_bind) that must outlive the context's use.
+ *  - All kernels are enqueued on the stream given to pbd_bind; calls return
+ *    without waiting unless stated.  Kernel faults surface in pbd_sync.
+ *  - Blocks are numbered as in the paper for the step calls (i = 1..B) and from
+ *    0 (b = i-1) where a single tensor of a block is addressed.
+ *  - Host-side tensors are float32 in the textbook layouts: activations NCHW,
+ *    convolution weights [C_out][C_in/groups][k][k].  Device activations are
+ *    channel-last (NHWC) with the channel count padded to a multiple of 8.
+ */
+#ifndef PBD_H_
+#define PBD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PBD_OK = 0,
+  PBD_EINVAL = -1,   /* null pointer, index out of range, non-finite scalar */
+  PBD_ESHAPE = -2,   /* descriptor inconsistent, tensor size or view mismatch */
+  PBD_ENOMEM_WS = -3,/* workspace missing, too small or misaligned */
+  PBD_ESTATE = -4,   /* call out of order (not bound, no relay yet) */
+  PBD_EHIP = -5      /* a HIP runtime call failed */
+} pbd_status;
+
+enum { PBD_F32 = 0, PBD_BF16 = 1 };                       /* arithmetic / storage type */
+enum { PBD_TEACHER = 0, PBD_STUDENT = 1 };                /* net */
+enum { PBD_WEIGHT = 0, PBD_GAMMA = 1, PBD_BETA = 2, PBD_RMEAN = 3, PBD_RVAR = 4 }; /* slot */
+enum { PBD_PARAM = 0, PBD_GRAD = 1, PBD_MOMENTUM = 2 };   /* kind */
+
+typedef struct pbd_ctx pbd_ctx;
+
+typedef struct {
+  int32_t batch;        /* N, samples per step */
+  int32_t precision;    /* PBD_F32: everything float32.  PBD_BF16: bf16 tensors and MFMA
+                           operands, fp32 accumulation, statistics, gradients of
+                           parameters, master weights and optimiser state */
+  float momentum;       /* mu of  v <- mu v + g ; w <- w - lr v */
+  float bn_eps;         /* added to the variance inside batch normalisation */
+  float bn_momentum;    /* rate of the student's running statistics */
+  int32_t force_direct; /* nonzero: run every convolution with the plain direct kernels
+                           (testing aid; the MFMA kernels are the default for bf16) */
+} pbd_opts;
+
+/* A borrowed view of an activation inside the workspace. */
+typedef struct {
+  void* ptr;            /* device; element (n,h,w,c) at ((n*h_ + h)*w_ + w)*c_phys + c */
+  int32_t n, c, h, w;
+  int32_t c_phys;       /* channels per pixel in memory, >= c, multiple of 8; pads are 0 */
+  int32_t dtype;        /* PBD_F32 or PBD_BF16 */
+} pbd_tensor;
+
+/* One timed kernel launch (see pbd_set_profile). */
+typedef struct {
+  char name[32];        /* kernel class, e.g. "conv_fwd_mfma", "bn_apply" */
+  float ms;             /* HIP-event time of this launch on the bound stream */
+  double bytes;         /* algorithmic bytes: tensors the operation must touch once */
+  double flops;         /* algorithmic flops: 2 x MACs of the unpadded problem, else 0 */
+  int32_t net, block, op;
+} pbd_prof_entry;
+
+/* Build a context from a packed descriptor (host).  words/pool: the int32 record
+ * stream and float64 pool that list the teacher blocks T_i and student blocks S_i
+ * (Sec. II-A: both map A_{i-1} to tensors of one shape; create checks it).  Header
+ * MAGIC 0x50424431, version 1, B, C0, H0, W0; then per net (teacher, student) and
+ * block: n_ops and n_ops records of 20 words
+ * [type, n_in, in0..in7, c_out, k, stride, pad, groups, act, pool_offset, 0,0,0];
+ * type 1 conv+BN+activation, 2 max-pool, 3 add(+activation), 4 weighted sum.  Pure
+ * host work, no GPU needed.  *out is owned by the caller until pbd_destroy. */
+int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t npool,
+               const pbd_opts* opts, pbd_ctx** out);
+void pbd_destroy(pbd_ctx* ctx);
+
+/* Text of the last error of ctx (host, owned by ctx; valid until the next call).
+ * With ctx == NULL: why the last pbd_create on this thread failed. */
+const char* pbd_last_error(const pbd_ctx* ctx);
+
+int32_t pbd_num_blocks(const pbd_ctx* ctx);
+
+/* Bytes of device workspace the context needs (relay store A_0..A_B, parameters,
+ * optimiser state, saved activations, gradients, reduction scratch). */
+size_t pbd_workspace_bytes(const pbd_ctx* ctx);
+
+/* Adopt dev_ws (device, 256-byte aligned, >= pbd_workspace_bytes) and hip_stream
+ * (a hipStream_t, may be null for the default stream).  Zero-fills parameters and
+ * optimiser state, sets BN to the identity.  The caller keeps ownership. */
+int pbd_bind(pbd_ctx* ctx, void* dev_ws, size_t bytes, void* hip_stream);
+
+/* Copy one parameter tensor from host float32 (textbook layout) into the workspace,
+ * or one parameter / gradient / momentum tensor back.  n = element count of the
+ * textbook shape.  Both wait for the stream.  Slots RMEAN/RVAR exist for PBD_PARAM only. */
+int pbd_load_param(pbd_ctx* ctx, int32_t net, int32_t b, int32_t op, int32_t slot,
+                   const float* host, size_t n);
+int pbd_read_tensor(pbd_ctx* ctx, int32_t kind, int32_t net, int32_t b, int32_t op,
+                    int32_t slot, float* host, size_t n);
+
+/* Copy A_i (i = 0..B) of the last relay to host as float32 NCHW; waits. */
+int pbd_read_act(pbd_ctx* ctx, int32_t i, float* host, size_t n);
+/* Copy value v of student block b (0 = its input, j+1 = output of op j) as saved by
+ * the last pbd_student_step on that block, float32 NCHW; valid until another block
+ * is stepped (blocks share scratch).  Testing aid; waits. */
+int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
+
+/* Teacher relay (Algorithm 1, load + T.forward; Sec. IV-A, Sec. VII-A).  x_dev:
+ * device float32 NCHW [batch][C0][H0][W0].  Runs T_1..T_B once each in inference
+ * mode and keeps every activation.  A (host array of B+1 views, may be null) gets
+ * A_0..A_B, borrowed from the workspace and valid until the next relay. */
+int pbd_teacher_relay(pbd_ctx* ctx, const float* x_dev, pbd_tensor* A);
+
+/* One student block (Algorithm 1, S.forward, S.backward(L), update_weight; Sec. II-A
+ * for L; Sec. IV-B for the immediate update).  i in 1..B.  A_prev, A_i: views returned
+ * by the last relay for A_{i-1} and A_i (checked).  Forward with batch statistics,
+ * loss_i = mean((S_i(A_{i-1}) - A_i)^2), backward through S_i only, then
+ * v <- mu v + g, w <- w - lr v on S_i's parameters and the running-statistics
+ * update.  loss_dev: device float32 scalar written by the stream (no host wait).
+ * Any order of i gives the same results. */
+int pbd_student_step(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i,
+                     float lr, float* loss_dev);
+
+/* The whole step: relay, then every student block; no teacher block runs twice.
+ * losses_dev: device float32[B].  Same results as the two calls above. */
+int pbd_distill_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
+
+/* Wait for the bound stream; reports asynchronous failures. */
+int pbd_sync(pbd_ctx* ctx);
+
+/* Profiling: when on, every kernel launch is bracketed by HIP events on the bound
+ * stream.  pbd_get_profile waits, then copies up to max entries of the launches
+ * recorded since the last pbd_reset_profile and returns how many there were. */
+int pbd_set_profile(pbd_ctx* ctx, int32_t on);
+int pbd_reset_profile(pbd_ctx* ctx);
+int pbd_get_profile(pbd_ctx* ctx, pbd_prof_entry* out, int32_t max);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PBD_H_ */

@@ -21,6 +21,15 @@
 // with zero padding; max-pool gradients go to the first maximum in row-major
 // window order.
 //
+// Optional storage rounding (storage = 1): the bf16 path of the method keeps tensors
+// (activations, compute copies of weights, activation gradients) in bfloat16 and
+// everything else in wider precision.  ReLU masks, max-pool winners and the bf16
+// codes themselves are decisions taken by floating point, and a gradient summed over
+// a kinked network is discontinuous in them; so that both sides take those decisions
+// in the same precision, this mode rounds to bfloat16 (nearest even) exactly where the
+// path stores a tensor and keeps every other operation in R.  storage = 0 is the
+// plain definition and stays the reference for losses and activations.
+//
 // Pins (tests/test_oracle_*.py): brute-force convolution, 1x1 conv == matrix
 // product, adjoint identities for dgrad/wgrad, BN closed forms, central finite
 // differences of loss_i over every parameter, PyTorch-CPU fp64 autograd on the
@@ -292,6 +301,18 @@ void sgd(R* w, R* v, const R* g, size_t n, R lr, R mu) {
   }
 }
 
+// nearest-even rounding to bfloat16 (8 significand bits), the storage type of the bf16 path
+inline double round_bf16(double v) {
+  float f = (float)v;
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7f800000u) == 0x7f800000u) return (double)f;  // inf / nan unchanged
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  std::memcpy(&f, &u, 4);
+  return (double)f;
+}
+
 // ---------------------------------------------------------------------------
 // descriptor
 // ---------------------------------------------------------------------------
@@ -385,6 +406,7 @@ struct NetBase {
   virtual void relay_step(const double* x, double lr, double* losses) = 0;
   virtual void redundant_step(const double* x, double lr, double* losses) = 0;
   virtual long value_numel(int b, int v) = 0;
+  virtual double kink_margin(int b) = 0;
   virtual void get_value(int b, int v, double* out) = 0;
 };
 
@@ -410,8 +432,22 @@ struct Net final : NetBase {
   std::vector<std::vector<std::vector<R>>> val;  // [block][value]
   std::vector<std::vector<Saved>> saved;         // [block][op]
 
-  Net(const Desc& desc, int batch, double momentum, double e, double r)
-      : d(desc), N(batch), mu((R)momentum), eps((R)e), rho((R)r) {
+  int storage = 0;  // 1: round stored tensors to bfloat16
+
+  void rnd(std::vector<R>& v) const {
+    if (!storage) return;
+#pragma omp parallel for schedule(static)
+    for (size_t i = 0; i < v.size(); ++i) v[i] = (R)round_bf16((double)v[i]);
+  }
+  // the compute copy of a weight tensor
+  std::vector<R> stored(const std::vector<R>& w) const {
+    std::vector<R> c = w;
+    rnd(c);
+    return c;
+  }
+
+  Net(const Desc& desc, int batch, double momentum, double e, double r, int st)
+      : d(desc), N(batch), mu((R)momentum), eps((R)e), rho((R)r), storage(st) {
     for (int which = 0; which < 2; ++which) {
       par[which].resize(d.B);
       for (int b = 0; b < d.B; ++b) {
@@ -475,11 +511,13 @@ struct Net final : NetBase {
       if (o.type == OP_CBA) {
         const Cba<R>& c = par[0][b][j];
         std::vector<R> y(out.size());
-        conv_fwd(v[o.in[0]].data(), c.p[0].data(), y.data(), N, si.c, si.h, si.w, so.c, o.k,
+        const std::vector<R> w = stored(c.p[0]);
+        conv_fwd(v[o.in[0]].data(), w.data(), y.data(), N, si.c, si.h, si.w, so.c, o.k,
                  o.stride, o.pad, o.groups);
         bn_eval(y.data(), c.p[1].data(), c.p[2].data(), c.p[3].data(), c.p[4].data(), y.data(), N,
                 so.c, so.h * so.w, eps);
         act_fwd(y.data(), out.data(), out.size(), o.act);
+        rnd(out);
       } else if (o.type == OP_POOL) {
         std::vector<int32_t> idx(out.size());
         maxpool_fwd(v[o.in[0]].data(), out.data(), idx.data(), N, si.c, si.h, si.w, o.k, o.stride,
@@ -487,11 +525,13 @@ struct Net final : NetBase {
       } else if (o.type == OP_ADD) {
         for (size_t i = 0; i < out.size(); ++i) out[i] = v[o.in[0]][i] + v[o.in[1]][i];
         act_fwd(out.data(), out.data(), out.size(), o.act);
+        rnd(out);
       } else {  // OP_MIX
         for (int k = 0; k < o.nin; ++k) {
           const R p = (R)d.pool[o.pofs + k];
           for (size_t i = 0; i < out.size(); ++i) out[i] += p * v[o.in[k]][i];
         }
+        rnd(out);
       }
     }
     return v.back();
@@ -500,12 +540,14 @@ struct Net final : NetBase {
   void teacher_relay(const double* x) override {
     A[0].resize((size_t)N * d.in.numel());
     for (size_t i = 0; i < A[0].size(); ++i) A[0][i] = (R)x[i];
+    rnd(A[0]);
     for (int b = 0; b < d.B; ++b) A[b + 1] = teacher_block(b, A[b]);  // each T_i once
   }
   // A_i recomputed from the raw input, T_1..T_i (the baseline's redundant work)
   std::vector<R> teacher_from_start(const double* x, int i) {
     std::vector<R> cur((size_t)N * d.in.numel());
     for (size_t k = 0; k < cur.size(); ++k) cur[k] = (R)x[k];
+    rnd(cur);
     for (int b = 0; b < i; ++b) cur = teacher_block(b, cur);
     return cur;
   }
@@ -538,11 +580,14 @@ struct Net final : NetBase {
         s.pre.resize(out.size());
         s.mean.resize(so.c);
         s.var.resize(so.c);
-        conv_fwd(v[o.in[0]].data(), c.p[0].data(), s.conv.data(), N, si.c, si.h, si.w, so.c, o.k,
+        const std::vector<R> w = stored(c.p[0]);
+        conv_fwd(v[o.in[0]].data(), w.data(), s.conv.data(), N, si.c, si.h, si.w, so.c, o.k,
                  o.stride, o.pad, o.groups);
+        rnd(s.conv);
         bn_train_fwd(s.conv.data(), c.p[1].data(), c.p[2].data(), s.pre.data(), s.mean.data(),
                      s.var.data(), N, so.c, so.h * so.w, eps);
         act_fwd(s.pre.data(), out.data(), out.size(), o.act);
+        rnd(out);
       } else if (o.type == OP_POOL) {
         sv[j].idx.resize(out.size());
         maxpool_fwd(v[o.in[0]].data(), out.data(), sv[j].idx.data(), N, si.c, si.h, si.w, o.k,
@@ -551,13 +596,61 @@ struct Net final : NetBase {
         sv[j].pre.resize(out.size());
         for (size_t i = 0; i < out.size(); ++i) sv[j].pre[i] = v[o.in[0]][i] + v[o.in[1]][i];
         act_fwd(sv[j].pre.data(), out.data(), out.size(), o.act);
+        rnd(out);
       } else {
         for (int k = 0; k < o.nin; ++k) {
           const R p = (R)d.pool[o.pofs + k];
           for (size_t i = 0; i < out.size(); ++i) out[i] += p * v[o.in[k]][i];
         }
+        rnd(out);
       }
     }
+  }
+
+  // Diagnostic, not part of the step: how close the last forward of block b came to a point
+  // where its gradient is discontinuous - the smallest |pre| (and |pre - 6| for ReLU6) over
+  // rectified elements, and the smallest winner-to-runner-up gap over max-pool windows whose
+  // winner is positive.  A comparison at finite precision is meaningless below this margin.
+  double kink_margin(int b) override {
+    const BlockD& blk = d.net[1][b];
+    double m = std::numeric_limits<double>::infinity();
+    for (size_t j = 0; j < blk.ops.size(); ++j) {
+      const OpD& o = blk.ops[j];
+      if ((o.type == OP_CBA || o.type == OP_ADD) && o.act != ACT_NONE) {
+        const Saved& sv = saved[b][j];
+        // a residual sum is not normalised: measure its distance from the kink in units of its rms
+        double unit = 1.0;
+        if (o.type == OP_ADD) {
+          double ss = 0.0;
+          for (R p : sv.pre) ss += (double)p * (double)p;
+          unit = std::max(1.0, std::sqrt(ss / (double)sv.pre.size()));
+        }
+        for (size_t i = 0; i < sv.pre.size(); ++i) {
+          // a channel fed by an all-zero input is zero in any arithmetic: not a coincidence
+          if (o.type == OP_CBA && sv.conv[i] == R(0) && sv.pre[i] == R(0)) continue;
+          const double p = (double)sv.pre[i];
+          m = std::min(m, std::fabs(p) / unit);
+          if (o.act == ACT_RELU6) m = std::min(m, std::fabs(p - 6.0) / unit);
+        }
+      } else if (o.type == OP_POOL) {
+        const Shape si = blk.shapes[o.in[0]], so = blk.shapes[j + 1];
+        const std::vector<R>& x = val[b][o.in[0]];
+        for (int nc = 0; nc < N * si.c; ++nc)
+          for (int p = 0; p < so.h; ++p)
+            for (int q = 0; q < so.w; ++q) {
+              double best = -std::numeric_limits<double>::infinity(), second = best;
+              for (int r = 0; r < o.k; ++r)
+                for (int t = 0; t < o.k; ++t) {
+                  const int h = p * o.stride + r - o.pad, w = q * o.stride + t - o.pad;
+                  if (h < 0 || h >= si.h || w < 0 || w >= si.w) continue;
+                  const double v = (double)x[((size_t)nc * si.h + h) * si.w + w];
+                  if (v > best) { second = best; best = v; } else if (v > second) second = v;
+                }
+              if (best > 0 && std::isfinite(second)) m = std::min(m, best - second);
+            }
+      }
+    }
+    return m;
   }
 
   void update_running_stats(int b) {
@@ -584,6 +677,7 @@ struct Net final : NetBase {
       if (id == 0) return;  // the teacher activation is a constant
       if (dv[id].empty()) dv[id] = gsrc;
       else for (size_t i = 0; i < gsrc.size(); ++i) dv[id][i] += gsrc[i];
+      rnd(dv[id]);  // a stored activation gradient
     };
     for (int j = (int)blk.ops.size() - 1; j >= 0; --j) {
       const OpD& o = blk.ops[j];
@@ -597,11 +691,13 @@ struct Net final : NetBase {
         act_bwd(dy.data(), s.pre.data(), dpre.data(), dy.size(), o.act);
         bn_train_bwd(dpre.data(), s.conv.data(), c.p[1].data(), s.mean.data(), s.var.data(),
                      dconv.data(), c.g[1].data(), c.g[2].data(), N, so.c, so.h * so.w, eps);
+        rnd(dconv);
         conv_wgrad(dconv.data(), v[o.in[0]].data(), c.g[0].data(), N, si.c, si.h, si.w, so.c, o.k,
                    o.stride, o.pad, o.groups);
         if (o.in[0] != 0) {
           std::vector<R> dx((size_t)N * si.numel());
-          conv_dgrad(dconv.data(), c.p[0].data(), dx.data(), N, si.c, si.h, si.w, so.c, o.k,
+          const std::vector<R> w = stored(c.p[0]);
+          conv_dgrad(dconv.data(), w.data(), dx.data(), N, si.c, si.h, si.w, so.c, o.k,
                      o.stride, o.pad, o.groups);
           accumulate(o.in[0], dx);
         }
@@ -636,6 +732,7 @@ struct Net final : NetBase {
     std::vector<R> ds(mode ? s.size() : 0);
     const R loss = mse(s.data(), a_i.data(), mode ? ds.data() : nullptr, s.size());
     if (mode == 0) return loss;
+    rnd(ds);
     student_backward(b, ds);
     if (mode == 2) {
       update_running_stats(b);
@@ -682,12 +779,12 @@ struct Net final : NetBase {
 extern "C" {
 
 void* orc_create(const int32_t* words, int nwords, const double* pool, int npool, int batch,
-                 int precision, double momentum, double eps, double rho) {
+                 int precision, double momentum, double eps, double rho, int storage) {
   Desc d;
   std::string err;
   if (!d.parse(words, nwords, pool, npool, err)) return nullptr;
-  if (precision == 64) return new Net<double>(d, batch, momentum, eps, rho);
-  if (precision == 32) return new Net<float>(d, batch, momentum, eps, rho);
+  if (precision == 64) return new Net<double>(d, batch, momentum, eps, rho, storage);
+  if (precision == 32) return new Net<float>(d, batch, momentum, eps, rho, storage);
   return nullptr;
 }
 void orc_destroy(void* h) { delete static_cast<NetBase*>(h); }
@@ -712,6 +809,7 @@ void orc_relay_step(void* h, const double* x, double lr, double* losses) {
 void orc_redundant_step(void* h, const double* x, double lr, double* losses) {
   static_cast<NetBase*>(h)->redundant_step(x, lr, losses);
 }
+double orc_kink_margin(void* h, int b) { return static_cast<NetBase*>(h)->kink_margin(b); }
 long orc_value_numel(void* h, int b, int v) { return static_cast<NetBase*>(h)->value_numel(b, v); }
 void orc_get_value(void* h, int b, int v, double* out) { static_cast<NetBase*>(h)->get_value(b, v, out); }
 int orc_num_threads() {

@@ -40,7 +40,7 @@ def lib():
         L = C.CDLL(build())
         L.orc_create.restype = C.c_void_p
         L.orc_create.argtypes = [_ip, C.c_int, _dp, C.c_int, C.c_int, C.c_int,
-                                 C.c_double, C.c_double, C.c_double]
+                                 C.c_double, C.c_double, C.c_double, C.c_int]
         L.orc_destroy.argtypes = [C.c_void_p]
         for f in (L.orc_set_tensor, L.orc_get_tensor):
             f.restype = C.c_int
@@ -57,6 +57,8 @@ def lib():
         L.orc_value_numel.restype = C.c_long
         L.orc_value_numel.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.orc_get_value.argtypes = [C.c_void_p, C.c_int, C.c_int, _dp]
+        L.orc_kink_margin.restype = C.c_double
+        L.orc_kink_margin.argtypes = [C.c_void_p, C.c_int]
         L.orc_num_threads.restype = C.c_int
         conv = [_dp, _dp, _dp] + [C.c_int] * 9
         L.orc_conv_fwd.argtypes = conv
@@ -207,20 +209,22 @@ def sgd(w, v, g, lr, mu):
 class Oracle:
     """One teacher/student pair described by packed descriptor words."""
 
-    def __init__(self, words, pool, batch, precision=64, momentum=0.9, eps=1e-5, rho=0.1):
+    def __init__(self, words, pool, batch, precision=64, momentum=0.9, eps=1e-5, rho=0.1,
+                 storage=None):
+        """storage="bf16": round every stored tensor to bfloat16 (see the C++ header)."""
         self._words = np.ascontiguousarray(words, dtype=np.int32)
         self._pool = np.ascontiguousarray(pool, dtype=np.float64)
         self.batch = batch
         self.B = int(self._words[2])
         self.h = lib().orc_create(self._words.ctypes.data_as(_ip), self._words.size,
                                   _d(self._pool), self._pool.size, batch, precision,
-                                  momentum, eps, rho)
+                                  momentum, eps, rho, 1 if storage == "bf16" else 0)
         if not self.h:
             raise ValueError("oracle rejected the descriptor")
 
     def __del__(self):
-        if getattr(self, "h", None):
-            lib().orc_destroy(self.h)
+        if getattr(self, "h", None) and _lib is not None:
+            _lib.orc_destroy(self.h)
             self.h = None
 
     def set_param(self, net, b, j, slot, arr, kind=KIND_PARAM):
@@ -267,6 +271,10 @@ class Oracle:
         losses = np.empty(self.B)
         lib().orc_redundant_step(self.h, _d(x), lr, _d(losses))
         return losses
+
+    def kink_margin(self, b):
+        """Smallest distance of block b's last forward from a ReLU / ReLU6 / max-pool kink."""
+        return lib().orc_kink_margin(self.h, b)
 
     def value(self, b, v):
         n = lib().orc_value_numel(self.h, b, v)

@@ -1,0 +1,424 @@
+// Dense convolution kernels for gfx950 (CDNA4), channel-last tensors.
+//
+//  * igemm_kernel: forward and backward-data as an implicit GEMM on the bf16
+//    matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).  Rows of the
+//    GEMM are output pixels, columns are output channels, the reduction runs over
+//    (r, s, c) in 16-byte chunks of 8 channels gathered straight from the NHWC
+//    tensor into LDS; weights are kept reduction-contiguous ([K][R][S][C] for
+//    forward, [C][R][S][K] for backward-data) so both operands are read from LDS
+//    with one 128-bit load per lane.  128 x BN x 32 tiles, 4 wavefronts of 64,
+//    LDS double buffering with register prefetch.
+//  * wgrad_kernel: backward-weight.  The reduction runs over pixels, which is the
+//    strided direction of NHWC memory, so every thread loads an 8 pixel x 8 channel
+//    block, transposes it in registers and stores reduction-contiguous rows to LDS
+//    (XOR-swizzled against bank conflicts).  The pixel range is split over
+//    workgroups; partial tiles go to scratch and are summed by an ordered second
+//    stage, so the result does not depend on scheduling.
+//  * direct kernels: plain one-thread-per-output loops in fp32, used for the
+//    float32 precision and as a cross-check of the MFMA kernels.
+#pragma once
+#include "ew_kernels.h"
+
+namespace pbd {
+
+struct ConvGeom {
+  int N, H, W, C;      // input tensor [N][H][W][C]   (C physical, multiple of 8)
+  int P, Q, K;         // output tensor [N][P][Q][K]
+  int R, S, stride, pad;
+};
+
+// ---------------------------------------------------------------------------
+// direct kernels (fp32 accumulate)
+// ---------------------------------------------------------------------------
+// y[m][k] = sum_{r,s,c} x[n, p*st+r-pad, q*st+s-pad, c] * w[k][r][s][c]
+template <class T, class WT>
+__global__ void conv_direct_fwd_kernel(const T* __restrict__ x, const WT* __restrict__ w,
+                                       T* __restrict__ y, const float* __restrict__ a,
+                                       const float* __restrict__ b, int act, ConvGeom g) {
+  const long total = (long)g.N * g.P * g.Q * g.K;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int k = (int)(i % g.K);
+    long pix = i / g.K;
+    const int q = (int)(pix % g.Q); pix /= g.Q;
+    const int p = (int)(pix % g.P);
+    const int n = (int)(pix / g.P);
+    float acc = 0.f;
+    for (int r = 0; r < g.R; ++r) {
+      const int h = p * g.stride + r - g.pad;
+      if (h < 0 || h >= g.H) continue;
+      for (int s = 0; s < g.S; ++s) {
+        const int ww = q * g.stride + s - g.pad;
+        if (ww < 0 || ww >= g.W) continue;
+        const T* xp = x + (((long)n * g.H + h) * g.W + ww) * g.C;
+        const WT* wp = w + (((long)k * g.R + r) * g.S + s) * g.C;
+        for (int c = 0; c < g.C; ++c) acc = fmaf((float)xp[c], (float)wp[c], acc);
+      }
+    }
+    if (a) acc = fmaf(acc, a[k], b[k]);
+    y[i] = (T)apply_act(acc, act);
+  }
+}
+
+// dx[n,h,w,c] (+)= sum_{k,r,s} dy[n,(h+pad-r)/st,(w+pad-s)/st,k] * w[k][r][s][c]
+template <class T, class WT>
+__global__ void conv_direct_dgrad_kernel(const T* __restrict__ dy, const WT* __restrict__ w,
+                                         T* __restrict__ dx, int accumulate, ConvGeom g) {
+  const long total = (long)g.N * g.H * g.W * g.C;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % g.C);
+    long pix = i / g.C;
+    const int ww = (int)(pix % g.W); pix /= g.W;
+    const int h = (int)(pix % g.H);
+    const int n = (int)(pix / g.H);
+    float acc = accumulate ? (float)dx[i] : 0.f;
+    for (int r = 0; r < g.R; ++r) {
+      const int ph = h + g.pad - r;
+      if (ph < 0 || ph % g.stride) continue;
+      const int p = ph / g.stride;
+      if (p >= g.P) continue;
+      for (int s = 0; s < g.S; ++s) {
+        const int qw = ww + g.pad - s;
+        if (qw < 0 || qw % g.stride) continue;
+        const int q = qw / g.stride;
+        if (q >= g.Q) continue;
+        const T* dp = dy + (((long)n * g.P + p) * g.Q + q) * g.K;
+        for (int k = 0; k < g.K; ++k)
+          acc = fmaf((float)dp[k], (float)w[(((long)k * g.R + r) * g.S + s) * g.C + c], acc);
+      }
+    }
+    dx[i] = (T)acc;
+  }
+}
+
+// dw[k][r][s][c] = sum_{n,p,q} dy[n,p,q,k] * x[n, p*st+r-pad, q*st+s-pad, c]
+template <class T>
+__global__ void conv_direct_wgrad_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                         float* __restrict__ dw, ConvGeom g) {
+  const long total = (long)g.K * g.R * g.S * g.C;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+    const int c = (int)(i % g.C);
+    long t = i / g.C;
+    const int s = (int)(t % g.S); t /= g.S;
+    const int r = (int)(t % g.R);
+    const int k = (int)(t / g.R);
+    float acc = 0.f;
+    for (int n = 0; n < g.N; ++n)
+      for (int p = 0; p < g.P; ++p) {
+        const int h = p * g.stride + r - g.pad;
+        if (h < 0 || h >= g.H) continue;
+        for (int q = 0; q < g.Q; ++q) {
+          const int ww = q * g.stride + s - g.pad;
+          if (ww < 0 || ww >= g.W) continue;
+          acc = fmaf((float)dy[(((long)n * g.P + p) * g.Q + q) * g.K + k],
+                     (float)x[(((long)n * g.H + h) * g.W + ww) * g.C + c], acc);
+        }
+      }
+    dw[i] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// MFMA implicit GEMM: forward (MODE 0) and backward-data (MODE 1)
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Generic view: Out[m][j] = sum_kk Agather(m, kk) * Bw[j][kk]
+//   rows m = (n, a, b) over an [N][HO][WO] grid, columns j < NC, kk = (r*S+s)*CA + c
+//   MODE 0: source pixel (a*st + r - pad, b*st + s - pad) of A = x    [N][HA][WA][CA]
+//   MODE 1: source pixel ((a+pad-r)/st, (b+pad-s)/st)     of A = dy   [N][HA][WA][CA]
+struct IgemmArgs {
+  int N, HA, WA, CA;
+  int HO, WO, NC;
+  int R, S, stride, pad;
+  int M;      // N*HO*WO
+  int Kred;   // R*S*CA
+};
+
+enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2 };
+
+constexpr int IG_BM = 128, IG_BK = 32, IG_PITCH = IG_BK + 8;
+
+template <int MODE, int BN, int EPI>
+__global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A,
+                                                    const bf16_t* __restrict__ Bw,
+                                                    bf16_t* __restrict__ Out,
+                                                    const float* __restrict__ ep_a,
+                                                    const float* __restrict__ ep_b, int act,
+                                                    IgemmArgs g) {
+  constexpr int WAVES_M = (BN == 128) ? 2 : 4, WAVES_N = 4 / WAVES_M;
+  constexpr int TM = IG_BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
+  constexpr int B_LOADS = (BN * 4 + 255) / 256;  // 16-byte chunks of the weight tile per thread
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][IG_BM * IG_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * IG_PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int m0 = blockIdx.x * IG_BM, n0 = blockIdx.y * BN;
+  const int chunk = tid & 3;
+
+  // the two A rows this thread stages, decoded once
+  int rn[2], ra[2], rb[2];
+  bool rvalid[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = m0 + (tid >> 2) + 64 * i;
+    rvalid[i] = m < g.M;
+    const int mm = rvalid[i] ? m : 0;
+    rb[i] = mm % g.WO;
+    const int t = mm / g.WO;
+    ra[i] = t % g.HO;
+    rn[i] = t / g.HO;
+  }
+  // reduction position of this thread's chunk: kk = rs*CA + c
+  int c = chunk * 8, rs = 0;
+  while (c >= g.CA) { c -= g.CA; ++rs; }
+
+  uint4 areg[2], breg[B_LOADS];
+  auto load_tile = [&](int kt) {
+    (void)kt;
+    const int r = rs / g.S, s = rs - r * g.S;
+    const bool kvalid = rs < g.R * g.S;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      int h, w;
+      bool ok = rvalid[i] && kvalid;
+      if (MODE == 0) {
+        h = ra[i] * g.stride + r - g.pad;
+        w = rb[i] * g.stride + s - g.pad;
+      } else {
+        const int th = ra[i] + g.pad - r, tw = rb[i] + g.pad - s;
+        ok = ok && th >= 0 && tw >= 0 && (th % g.stride) == 0 && (tw % g.stride) == 0;
+        h = th / g.stride;
+        w = tw / g.stride;
+      }
+      ok = ok && h >= 0 && h < g.HA && w >= 0 && w < g.WA;
+      areg[i] = ok ? *reinterpret_cast<const uint4*>(A + (((long)rn[i] * g.HA + h) * g.WA + w) * g.CA + c)
+                   : make_uint4(0, 0, 0, 0);
+    }
+    const int kk = rs * g.CA + c;
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+      const int row = (tid >> 2) + 64 * i;
+      const bool ok = row < BN && (n0 + row) < g.NC && kvalid;
+      breg[i] = ok ? *reinterpret_cast<const uint4*>(Bw + (long)(n0 + row) * g.Kred + kk)
+                   : make_uint4(0, 0, 0, 0);
+    }
+    c += IG_BK;
+    while (c >= g.CA) { c -= g.CA; ++rs; }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      *reinterpret_cast<uint4*>(&As[buf][((tid >> 2) + 64 * i) * IG_PITCH + chunk * 8]) = areg[i];
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) {
+      const int row = (tid >> 2) + 64 * i;
+      if (row < BN) *reinterpret_cast<uint4*>(&Bs[buf][row * IG_PITCH + chunk * 8]) = breg[i];
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk = (g.Kred + IG_BK - 1) / IG_BK;
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_tile(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < IG_BK / 16; ++ks) {
+      bf16x8 af[TM], bfr[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        af[i] = *reinterpret_cast<const bf16x8*>(
+            &As[buf][(wm * TM * 32 + i * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        bfr[j] = *reinterpret_cast<const bf16x8*>(
+            &Bs[buf][(wn * TN * 32 + j * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_tile(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds column j = lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
+    if (col >= g.NC) continue;
+    float ea = 1.f, eb = 0.f;
+    if (EPI == EPI_AFFINE_ACT) { ea = ep_a[col]; eb = ep_b[col]; }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * TM * 32 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row >= g.M) continue;
+        float o = acc[i][j][v];
+        bf16_t* dst = Out + (long)row * g.NC + col;
+        if (EPI == EPI_AFFINE_ACT) o = apply_act(fmaf(o, ea, eb), act);
+        if (EPI == EPI_ACCUM) o += (float)*dst;
+        *dst = (bf16_t)o;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// MFMA backward-weight:  dW[k][j] = sum_m dy[m][k] * Xgather(m, j),  j = (r*S+s)*C + c
+// Tile T x T outputs, BKP pixels per step; grid = (tiles_k, tiles_j, splits).
+// ---------------------------------------------------------------------------
+struct WgradArgs {
+  int N, H, W, C;     // x  [N][H][W][C]
+  int P, Q, K;        // dy [N][P][Q][K]
+  int R, S, stride, pad;
+  int M;              // N*P*Q
+  int J;              // R*S*C
+  int pix_per_split;  // multiple of BKP
+};
+
+__device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
+  // in[p] = 8 channels of pixel p (as 4 dwords); out[c] = 8 pixels of channel c
+  const uint32_t* I = reinterpret_cast<const uint32_t*>(in);
+  uint32_t* O = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t lo = I[(2 * i) * 4 + j], hi = I[(2 * i + 1) * 4 + j];
+      O[(2 * j) * 4 + i] = (lo & 0xffffu) | (hi << 16);
+      O[(2 * j + 1) * 4 + i] = (lo >> 16) | (hi & 0xffff0000u);
+    }
+}
+
+template <int T, int BKP>
+__global__ __launch_bounds__(256) void wgrad_kernel(const bf16_t* __restrict__ dy,
+                                                    const bf16_t* __restrict__ x,
+                                                    float* __restrict__ part, WgradArgs g) {
+  static_assert((2 * T / 8) * (BKP / 8) == 256, "one 8x8 block per thread");
+  constexpr int PITCH = BKP + 8;          // bf16 elements per LDS row
+  constexpr int UNITS = BKP / 8;          // 16-byte units per row
+  constexpr int CH = T / 8;               // channel chunks per operand
+  constexpr int TW = T / 64;              // 32x32 MFMA tiles per wave per dim (waves 2x2)
+  __shared__ __attribute__((aligned(16))) bf16_t As[T * PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[T * PITCH];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int k0 = blockIdx.x * T, j0 = blockIdx.y * T;
+  const long mbeg = (long)blockIdx.z * g.pix_per_split;
+  const long mend = min((long)g.M, mbeg + g.pix_per_split);
+
+  const bool isA = tid < 128;
+  const int blk = isA ? tid : tid - 128;
+  const int cc = blk % CH, pg = blk / CH;   // channel chunk, pixel group
+  // B threads: column chunk -> (r, s, c0), fixed for the whole loop
+  int br = 0, bs = 0, bc = 0;
+  bool colvalid;
+  if (isA) {
+    colvalid = (k0 + cc * 8) < g.K;
+  } else {
+    const int j = j0 + cc * 8;
+    colvalid = j < g.J;
+    const int rs = colvalid ? j / g.C : 0;
+    bc = colvalid ? j - rs * g.C : 0;
+    br = rs / g.S;
+    bs = rs - br * g.S;
+  }
+
+  f32x16 acc[TW][TW];
+#pragma unroll
+  for (int i = 0; i < TW; ++i)
+#pragma unroll
+    for (int j = 0; j < TW; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  for (long ms = mbeg; ms < mend; ms += BKP) {
+    uint4 in[8], tr[8];
+    const long mfirst = ms + pg * 8;
+    if (isA) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const long m = mfirst + p;
+        in[p] = (colvalid && m < mend)
+                    ? *reinterpret_cast<const uint4*>(dy + m * g.K + k0 + cc * 8)
+                    : make_uint4(0, 0, 0, 0);
+      }
+    } else {
+      long t = mfirst;
+      int q = (int)(t % g.Q); t /= g.Q;
+      int p_ = (int)(t % g.P);
+      int n = (int)(t / g.P);
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const long m = mfirst + p;
+        const int h = p_ * g.stride + br - g.pad, w = q * g.stride + bs - g.pad;
+        const bool ok = colvalid && m < mend && h >= 0 && h < g.H && w >= 0 && w < g.W;
+        in[p] = ok ? *reinterpret_cast<const uint4*>(x + (((long)n * g.H + h) * g.W + w) * g.C + bc)
+                   : make_uint4(0, 0, 0, 0);
+        if (++q == g.Q) { q = 0; if (++p_ == g.P) { p_ = 0; ++n; } }
+      }
+    }
+    transpose8x8(in, tr);
+    __syncthreads();  // previous step's MFMA reads are done
+    bf16_t* dstbase = isA ? As : Bs;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int row = cc * 8 + i;
+      const int unit = pg ^ (cc & 7);       // swizzle: rows 8 apart would share banks
+      *reinterpret_cast<uint4*>(&dstbase[row * PITCH + unit * 8]) = tr[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < BKP / 16; ++ks) {
+      bf16x8 af[TW], bfr[TW];
+#pragma unroll
+      for (int i = 0; i < TW; ++i) {
+        const int row = wm * TW * 32 + i * 32 + (lane & 31);
+        const int unit = (ks * 2 + (lane >> 5)) ^ ((row >> 3) & 7);
+        af[i] = *reinterpret_cast<const bf16x8*>(&As[row * PITCH + unit * 8]);
+      }
+#pragma unroll
+      for (int j = 0; j < TW; ++j) {
+        const int row = wn * TW * 32 + j * 32 + (lane & 31);
+        const int unit = (ks * 2 + (lane >> 5)) ^ ((row >> 3) & 7);
+        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[row * PITCH + unit * 8]);
+      }
+#pragma unroll
+      for (int i = 0; i < TW; ++i)
+#pragma unroll
+        for (int j = 0; j < TW; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  static_assert(UNITS >= 8, "swizzle needs 8 units per row");
+
+  float* out = part + (long)blockIdx.z * g.K * g.J;
+#pragma unroll
+  for (int j = 0; j < TW; ++j) {
+    const int col = j0 + wn * TW * 32 + j * 32 + (lane & 31);
+    if (col >= g.J) continue;
+#pragma unroll
+    for (int i = 0; i < TW; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = k0 + wm * TW * 32 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row < g.K) out[(long)row * g.J + col] = acc[i][j][v];
+      }
+  }
+}
+
+}  // namespace pbd

@@ -1,0 +1,677 @@
+// Bandwidth-bound kernels of the blockwise-distillation step for gfx950:
+// layout/cast, batch normalisation (statistics, apply, backward), activations,
+// max-pool, residual add, candidate mix, depthwise convolution, fused MSE loss +
+// gradient, fused SGD-momentum.  Tensors are channel-last (NHWC); a thread owns
+// one vector of 8 consecutive channels, so a wavefront touches contiguous
+// 1 KiB (bf16) or 2 KiB (fp32) runs and every access is a 16-byte transaction.
+// All reductions are two-stage and ordered (no atomics), which keeps a step
+// bit-reproducible and independent of the order in which blocks are trained
+// (Sec. IV-B: blocks share no parameters).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pbd {
+
+typedef __bf16 bf16_t;
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2 };
+
+__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+// round-to-nearest-even pair conversion (v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf2(float a, float b) {
+  typedef float f2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+  f2 v = {a, b};
+  b2 r = __builtin_convertvector(v, b2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+template <class T> struct IO;
+template <> struct IO<float> {
+  static __device__ __forceinline__ void ld(const float* p, float v[8]) {
+    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void st(float* p, const float v[8]) {
+    reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct IO<bf16_t> {
+  static __device__ __forceinline__ void ld(const bf16_t* p, float v[8]) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    v[0] = bf_lo(u.x); v[1] = bf_hi(u.x); v[2] = bf_lo(u.y); v[3] = bf_hi(u.y);
+    v[4] = bf_lo(u.z); v[5] = bf_hi(u.z); v[6] = bf_lo(u.w); v[7] = bf_hi(u.w);
+  }
+  static __device__ __forceinline__ void st(bf16_t* p, const float v[8]) {
+    uint4 u;
+    u.x = pack_bf2(v[0], v[1]); u.y = pack_bf2(v[2], v[3]);
+    u.z = pack_bf2(v[4], v[5]); u.w = pack_bf2(v[6], v[7]);
+    *reinterpret_cast<uint4*>(p) = u;
+  }
+};
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == ACT_RELU) return v > 0.f ? v : 0.f;
+  if (act == ACT_RELU6) return v > 0.f ? (v < 6.f ? v : 6.f) : 0.f;
+  return v;
+}
+// slope of the activation at pre-activation v (1 where it passes the gradient)
+__device__ __forceinline__ bool act_pass(float v, int act) {
+  if (act == ACT_RELU) return v > 0.f;
+  if (act == ACT_RELU6) return v > 0.f && v < 6.f;
+  return true;
+}
+
+// ---------------------------------------------------------------------------
+// layout / cast:  x float32 NCHW  ->  A_0  T NHWC with Cp channels (pads = 0)
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ void cast_input_kernel(const float* __restrict__ x, T* __restrict__ out, int N, int C,
+                                  int HW, int Cp) {
+  const long nvec = (long)N * HW * (Cp / 8);
+  const int ncv = Cp / 8;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    const long pix = i / ncv;
+    const int n = (int)(pix / HW), hw = (int)(pix % HW);
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int c = cv * 8 + k;
+      v[k] = c < C ? x[((long)n * C + c) * HW + hw] : 0.f;
+    }
+    IO<T>::st(out + i * 8, v);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// inference-mode BN folded to  y = a*x + b  (teacher; Sec. II-A: the teacher is
+// pretrained and only evaluated)
+// ---------------------------------------------------------------------------
+__global__ void bn_fold_kernel(const float* gamma, const float* beta, const float* rmean,
+                               const float* rvar, float* a, float* b, int C, float eps) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  const float s = gamma[c] / sqrtf(rvar[c] + eps);
+  a[c] = s;
+  b[c] = beta[c] - rmean[c] * s;
+}
+
+// training-mode BN + activation:  z = act(gamma * ((y - mean) * invstd) + beta)
+template <class T>
+__global__ void bn_apply_kernel(const T* __restrict__ y, T* __restrict__ z,
+                                const float* __restrict__ mean, const float* __restrict__ invstd,
+                                const float* __restrict__ gamma, const float* __restrict__ beta,
+                                long nvec, int ncv, int act) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int c0 = (int)(i % ncv) * 8;
+    float v[8];
+    IO<T>::ld(y + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      v[k] = apply_act(fmaf(gamma[c0 + k], (v[k] - mean[c0 + k]) * invstd[c0 + k], beta[c0 + k]), act);
+    IO<T>::st(z + i * 8, v);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// per-channel column reductions over the M = N*H*W rows of an NHWC matrix.
+// Block = 256 threads = cvl channel-vector lanes x (256/cvl) row lanes; grid =
+// (column slabs, row chunks).  Each block writes one ordered partial.
+// ---------------------------------------------------------------------------
+struct ColGrid {
+  int cvl;        // channel-vector lanes per block (power of two <= 32)
+  int slabs;      // ceil(ncv / cvl)
+  int chunks;     // row chunks (gridDim.y)
+  long rows_per_chunk;
+};
+
+// in-block ordered reduction of NV floats per thread over the row lanes
+template <int NV>
+__device__ __forceinline__ void block_col_reduce(float (&acc)[NV], float* smem, int cvl, int cv_lane,
+                                                 int row_lane, float* out /*[NV]*/, bool& owner) {
+  const int rl = 256 / cvl;
+  owner = false;
+  // smem layout [row_lane][cv_lane][NV]
+#pragma unroll
+  for (int k = 0; k < NV; ++k) smem[(row_lane * cvl + cv_lane) * NV + k] = acc[k];
+  __syncthreads();
+  if (row_lane == 0) {
+    owner = true;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+      float s = 0.f;
+      for (int r = 0; r < rl; ++r) s += smem[(r * cvl + cv_lane) * NV + k];
+      out[k] = s;
+    }
+  }
+  __syncthreads();
+}
+
+// part[chunk][0][c] = sum (y - piv), part[chunk][1][c] = sum (y - piv)^2 with the pivot
+// piv[c] = y[row 0][c]: shifting by a sample of the channel keeps the variance free of the
+// cancellation that  E[y^2] - mean^2  suffers when |mean| >> std
+template <class T>
+__global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, float* __restrict__ part,
+                                                       long M, int Cp, ColGrid g) {
+  extern __shared__ float smem[];
+  const int ncv = Cp / 8;
+  const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
+  const int cv = blockIdx.x * g.cvl + cv_lane;
+  const long r0 = blockIdx.y * g.rows_per_chunk;
+  const long r1 = min(M, r0 + g.rows_per_chunk);
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+  if (cv < ncv) {
+    float piv[8];
+    IO<T>::ld(y + (long)cv * 8, piv);
+    for (long r = r0 + row_lane; r < r1; r += rl) {
+      float v[8];
+      IO<T>::ld(y + (r * ncv + cv) * 8, v);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float d = v[k] - piv[k];
+        acc[k] += d;
+        acc[8 + k] = fmaf(d, d, acc[8 + k]);
+      }
+    }
+  }
+  float out[16];
+  bool owner;
+  block_col_reduce<16>(acc, smem, g.cvl, cv_lane, row_lane, out, owner);
+  if (owner && cv < ncv) {
+    float* p = part + (long)blockIdx.y * 2 * Cp + cv * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { p[k] = out[k]; p[Cp + k] = out[8 + k]; }
+  }
+}
+
+// mean, biased variance -> inv std; running statistics
+//   rm <- (1-rho) rm + rho mean,  rv <- (1-rho) rv + rho var m/(m-1)
+template <class T>
+__global__ void bn_finalize_kernel(const float* __restrict__ part, const T* __restrict__ y, int chunks,
+                                   int Cp, double m, float* mean, float* invstd, float* rmean,
+                                   float* rvar, float eps, float rho) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= Cp) return;
+  double s1 = 0.0, s2 = 0.0;
+  for (int k = 0; k < chunks; ++k) {
+    s1 += (double)part[(long)k * 2 * Cp + c];
+    s2 += (double)part[(long)k * 2 * Cp + Cp + c];
+  }
+  const double shift = s1 / m;
+  const double mu = (double)(float)y[c] + shift;
+  double var = s2 / m - shift * shift;
+  if (var < 0.0) var = 0.0;
+  mean[c] = (float)mu;
+  invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
+  rmean[c] = (1.f - rho) * rmean[c] + rho * (float)mu;
+  rvar[c] = (1.f - rho) * rvar[c] + rho * (float)(var * m / (m - 1.0));
+}
+
+// BN backward, stage 1: with xhat = (y - mean)*invstd, pre = gamma*xhat + beta and
+// dpre = [act passes at pre] * dz:  part[chunk][0][c] = sum dpre, part[chunk][1][c] = sum dpre*xhat
+template <class T>
+__global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
+    const T* __restrict__ dz, const T* __restrict__ y, const float* __restrict__ gamma,
+    const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
+    float* __restrict__ part, long M, int Cp, int act, ColGrid g) {
+  extern __shared__ float smem[];
+  const int ncv = Cp / 8;
+  const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
+  const int cv = blockIdx.x * g.cvl + cv_lane;
+  const long r0 = blockIdx.y * g.rows_per_chunk;
+  const long r1 = min(M, r0 + g.rows_per_chunk);
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+  if (cv < ncv) {
+    float av[8], bv[8], mv[8], iv[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      av[k] = gamma[cv * 8 + k]; bv[k] = beta[cv * 8 + k]; mv[k] = mean[cv * 8 + k]; iv[k] = invstd[cv * 8 + k];
+    }
+    for (long r = r0 + row_lane; r < r1; r += rl) {
+      float d[8], v[8];
+      IO<T>::ld(dz + (r * ncv + cv) * 8, d);
+      IO<T>::ld(y + (r * ncv + cv) * 8, v);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float xh = (v[k] - mv[k]) * iv[k];
+        const float dp = act_pass(fmaf(av[k], xh, bv[k]), act) ? d[k] : 0.f;
+        acc[k] += dp;
+        acc[8 + k] = fmaf(dp, xh, acc[8 + k]);
+      }
+    }
+  }
+  float out[16];
+  bool owner;
+  block_col_reduce<16>(acc, smem, g.cvl, cv_lane, row_lane, out, owner);
+  if (owner && cv < ncv) {
+    float* p = part + (long)blockIdx.y * 2 * Cp + cv * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { p[k] = out[k]; p[Cp + k] = out[8 + k]; }
+  }
+}
+
+// stage 2: dbeta, dgamma (the parameter gradients) and the per-channel terms
+// k2 = dbeta/m, k3 = dgamma/m of  dy = gamma*invstd*(dpre - k2 - xhat*k3)
+__global__ void bn_bwd_finalize_kernel(const float* __restrict__ part, int chunks, int Cp, double m,
+                                       float* g_gamma, float* g_beta, float* k2, float* k3) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= Cp) return;
+  double sb = 0.0, sg = 0.0;
+  for (int k = 0; k < chunks; ++k) {
+    sb += (double)part[(long)k * 2 * Cp + c];
+    sg += (double)part[(long)k * 2 * Cp + Cp + c];
+  }
+  g_beta[c] = (float)sb;
+  g_gamma[c] = (float)sg;
+  k2[c] = (float)(sb / m);
+  k3[c] = (float)(sg / m);
+}
+
+// stage 3: gradient w.r.t. the convolution output, written over dz in place
+template <class T>
+__global__ void bn_bwd_apply_kernel(T* __restrict__ dz, const T* __restrict__ y,
+                                    const float* __restrict__ gamma, const float* __restrict__ beta,
+                                    const float* __restrict__ mean, const float* __restrict__ invstd,
+                                    const float* __restrict__ k2, const float* __restrict__ k3,
+                                    long nvec, int ncv, int act) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int c0 = (int)(i % ncv) * 8;
+    float d[8], v[8];
+    IO<T>::ld(dz + i * 8, d);
+    IO<T>::ld(y + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int c = c0 + k;
+      const float xh = (v[k] - mean[c]) * invstd[c];
+      const float dp = act_pass(fmaf(gamma[c], xh, beta[c]), act) ? d[k] : 0.f;
+      d[k] = gamma[c] * invstd[c] * (dp - k2[c] - xh * k3[c]);
+    }
+    IO<T>::st(dz + i * 8, d);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// max-pool; idx keeps the window position r*k+t of the first maximum
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ z, uint8_t* __restrict__ idx,
+                                   int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad) {
+  const long nvec = (long)N * P * Q * ncv;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int q = (int)(pix % Q); pix /= Q;
+    const int p = (int)(pix % P);
+    const int n = (int)(pix / P);
+    float best[8];
+    int bi[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { best[e] = 0.f; bi[e] = -1; }
+    for (int r = 0; r < k; ++r) {
+      const int h = p * stride + r - pad;
+      if (h < 0 || h >= H) continue;
+      for (int t = 0; t < k; ++t) {
+        const int w = q * stride + t - pad;
+        if (w < 0 || w >= W) continue;
+        float v[8];
+        IO<T>::ld(x + ((((long)n * H + h) * W + w) * ncv + cv) * 8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (bi[e] < 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = r * k + t; }
+      }
+    }
+    IO<T>::st(z + i * 8, best);
+    if (idx) {
+      uint2 pk;
+      pk.x = (uint32_t)bi[0] | ((uint32_t)bi[1] << 8) | ((uint32_t)bi[2] << 16) | ((uint32_t)bi[3] << 24);
+      pk.y = (uint32_t)bi[4] | ((uint32_t)bi[5] << 8) | ((uint32_t)bi[6] << 16) | ((uint32_t)bi[7] << 24);
+      *reinterpret_cast<uint2*>(idx + i * 8) = pk;
+    }
+  }
+}
+
+// gather form: every input pixel collects from the windows that chose it
+template <class T>
+__global__ void maxpool_bwd_kernel(const T* __restrict__ dz, const uint8_t* __restrict__ idx,
+                                   T* __restrict__ dx, int N, int H, int W, int P, int Q, int ncv,
+                                   int k, int stride, int pad, int accumulate) {
+  const long nvec = (long)N * H * W * ncv;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int w = (int)(pix % W); pix /= W;
+    const int h = (int)(pix % H);
+    const int n = (int)(pix / H);
+    float acc[8];
+    if (accumulate) IO<T>::ld(dx + i * 8, acc);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    }
+    for (int r = 0; r < k; ++r) {
+      const int ph = h + pad - r;
+      if (ph < 0 || ph % stride) continue;
+      const int p = ph / stride;
+      if (p >= P) continue;
+      for (int t = 0; t < k; ++t) {
+        const int qw = w + pad - t;
+        if (qw < 0 || qw % stride) continue;
+        const int q = qw / stride;
+        if (q >= Q) continue;
+        const long o = ((((long)n * P + p) * Q + q) * ncv + cv) * 8;
+        const uint2 pk = *reinterpret_cast<const uint2*>(idx + o);
+        float d[8];
+        IO<T>::ld(dz + o, d);
+        const uint32_t me = (uint32_t)(r * k + t);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t word = e < 4 ? pk.x : pk.y;
+          if (((word >> (8 * (e & 3))) & 0xffu) == me) acc[e] += d[e];
+        }
+      }
+    }
+    IO<T>::st(dx + i * 8, acc);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// joins: z = act(sum_k p_k v_k) forward; backward fans  s_k*[act passes at z]*dz
+// out to up to 8 destinations, each either written or accumulated
+// ---------------------------------------------------------------------------
+struct Join {
+  const void* src[8];
+  void* dst[8];
+  float p[8];
+  int accumulate[8];
+  int n;
+};
+
+template <class T>
+__global__ void join_fwd_kernel(Join j, T* __restrict__ z, long nvec, int act) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int k = 0; k < j.n; ++k) {
+      float v[8];
+      IO<T>::ld(static_cast<const T*>(j.src[k]) + i * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(j.p[k], v[e], acc[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = apply_act(acc[e], act);
+    IO<T>::st(z + i * 8, acc);
+  }
+}
+
+// z is the post-activation output: for ReLU the gradient passes where z > 0
+template <class T>
+__global__ void join_bwd_kernel(Join j, const T* __restrict__ dz, const T* __restrict__ z, long nvec, int act) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    float d[8];
+    IO<T>::ld(dz + i * 8, d);
+    if (act != ACT_NONE) {
+      float v[8];
+      IO<T>::ld(z + i * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = act_pass(v[e], act) ? d[e] : 0.f;
+    }
+    for (int k = 0; k < j.n; ++k) {
+      T* dst = static_cast<T*>(j.dst[k]);
+      if (!dst) continue;
+      float o[8];
+      if (j.accumulate[k]) {
+        IO<T>::ld(dst + i * 8, o);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = fmaf(j.p[k], d[e], o[e]);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = j.p[k] * d[e];
+      }
+      IO<T>::st(dst + i * 8, o);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// fused MSE loss + gradient (Sec. II-A, L(delta output)):
+//   part[block] = sum (s-t)^2 ;  ds = 2 (s-t) / M ;  loss = sum(part) / M
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void mse_kernel(const T* __restrict__ s, const T* __restrict__ t,
+                                                  T* __restrict__ ds, float* __restrict__ part,
+                                                  long nvec, float two_over_m) {
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    float a[8], b[8];
+    IO<T>::ld(s + i * 8, a);
+    IO<T>::ld(t + i * 8, b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float d = a[e] - b[e];
+      acc = fmaf(d, d, acc);
+      a[e] = d * two_over_m;
+    }
+    IO<T>::st(ds + i * 8, a);
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s2 = 128; s2 > 0; s2 >>= 1) {
+    if ((int)threadIdx.x < s2) red[threadIdx.x] += red[threadIdx.x + s2];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part[blockIdx.x] = red[0];
+}
+
+__global__ void mse_final_kernel(const float* __restrict__ part, int n, double inv_m, float* loss) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double s = 0.0;
+    for (int i = 0; i < n; ++i) s += (double)part[i];
+    *loss = (float)(s * inv_m);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// fused SGD-momentum over one block's flat parameter arena (Algorithm 1,
+// update_weight; Sec. IV-B):  v <- mu v + g ; w <- w - lr v ; compute copy <- rne(w)
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ void sgd_momentum_kernel(float* __restrict__ w, float* __restrict__ v,
+                                    const float* __restrict__ g, T* __restrict__ wc, long n4,
+                                    float lr, float mu) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n4; i += (long)gridDim.x * blockDim.x) {
+    float4 wv = reinterpret_cast<float4*>(w)[i], vv = reinterpret_cast<float4*>(v)[i];
+    const float4 gv = reinterpret_cast<const float4*>(g)[i];
+    vv.x = fmaf(mu, vv.x, gv.x); vv.y = fmaf(mu, vv.y, gv.y);
+    vv.z = fmaf(mu, vv.z, gv.z); vv.w = fmaf(mu, vv.w, gv.w);
+    wv.x -= lr * vv.x; wv.y -= lr * vv.y; wv.z -= lr * vv.z; wv.w -= lr * vv.w;
+    reinterpret_cast<float4*>(v)[i] = vv;
+    reinterpret_cast<float4*>(w)[i] = wv;
+    if (wc) {
+      uint2 pk;
+      pk.x = pack_bf2(wv.x, wv.y);
+      pk.y = pack_bf2(wv.z, wv.w);
+      reinterpret_cast<uint2*>(wc)[i] = pk;
+    }
+  }
+}
+
+// compute copy <- rne(master) without an update (after parameters were loaded)
+__global__ void cast_params_kernel(const float* __restrict__ w, bf16_t* __restrict__ wc, long n4) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n4; i += (long)gridDim.x * blockDim.x) {
+    const float4 wv = reinterpret_cast<const float4*>(w)[i];
+    uint2 pk;
+    pk.x = pack_bf2(wv.x, wv.y);
+    pk.y = pack_bf2(wv.z, wv.w);
+    reinterpret_cast<uint2*>(wc)[i] = pk;
+  }
+}
+
+// Transposed weight copies for backward-data: src [K][RS][C] -> dst [C][RS][K].
+struct TransposeEntry { long src, dst; int K, RS, C; };
+template <class T>
+__global__ void transpose_weights_kernel(const T* __restrict__ wc, T* __restrict__ wt,
+                                         const TransposeEntry* __restrict__ table) {
+  const TransposeEntry e = table[blockIdx.y];
+  const long n = (long)e.K * e.RS * e.C;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    // i enumerates the destination so that stores are contiguous
+    const int k = (int)(i % e.K);
+    const long t = i / e.K;
+    const int rs = (int)(t % e.RS);
+    const int c = (int)(t / e.RS);
+    wt[e.dst + i] = wc[e.src + ((long)k * e.RS + rs) * e.C + c];
+  }
+}
+
+// out[j] = sum_s part[s*stride + j]   (ordered second stage of split reductions)
+__global__ void sum_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long n,
+                                    int splits, long stride) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    float s = 0.f;
+    for (int k = 0; k < splits; ++k) s += part[(long)k * stride + i];
+    out[i] = s;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// depthwise convolution, weights [k*k][Cp] (channel-last)
+// ---------------------------------------------------------------------------
+template <class T, class WT>
+__global__ void dw_fwd_kernel(const T* __restrict__ x, const WT* __restrict__ w, T* __restrict__ y,
+                              const float* __restrict__ a, const float* __restrict__ b, int act,
+                              int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad) {
+  const long nvec = (long)N * P * Q * ncv;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int q = (int)(pix % Q); pix /= Q;
+    const int p = (int)(pix % P);
+    const int n = (int)(pix / P);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int r = 0; r < k; ++r) {
+      const int h = p * stride + r - pad;
+      if (h < 0 || h >= H) continue;
+      for (int t = 0; t < k; ++t) {
+        const int ww = q * stride + t - pad;
+        if (ww < 0 || ww >= W) continue;
+        float v[8], f[8];
+        IO<T>::ld(x + ((((long)n * H + h) * W + ww) * ncv + cv) * 8, v);
+        IO<WT>::ld(w + ((long)(r * k + t) * ncv + cv) * 8, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], f[e], acc[e]);
+      }
+    }
+    if (a) {  // folded inference-mode BN + activation (teacher)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = apply_act(fmaf(acc[e], a[cv * 8 + e], b[cv * 8 + e]), act);
+    }
+    IO<T>::st(y + i * 8, acc);
+  }
+}
+
+template <class T, class WT>
+__global__ void dw_dgrad_kernel(const T* __restrict__ dy, const WT* __restrict__ w, T* __restrict__ dx,
+                                int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad,
+                                int accumulate) {
+  const long nvec = (long)N * H * W * ncv;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int ww = (int)(pix % W); pix /= W;
+    const int h = (int)(pix % H);
+    const int n = (int)(pix / H);
+    float acc[8];
+    if (accumulate) IO<T>::ld(dx + i * 8, acc);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    }
+    for (int r = 0; r < k; ++r) {
+      const int ph = h + pad - r;
+      if (ph < 0 || ph % stride) continue;
+      const int p = ph / stride;
+      if (p >= P) continue;
+      for (int t = 0; t < k; ++t) {
+        const int qw = ww + pad - t;
+        if (qw < 0 || qw % stride) continue;
+        const int q = qw / stride;
+        if (q >= Q) continue;
+        float d[8], f[8];
+        IO<T>::ld(dy + ((((long)n * P + p) * Q + q) * ncv + cv) * 8, d);
+        IO<WT>::ld(w + ((long)(r * k + t) * ncv + cv) * 8, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(d[e], f[e], acc[e]);
+      }
+    }
+    IO<T>::st(dx + i * 8, acc);
+  }
+}
+
+// dW[r][t][c] = sum over output pixels dY * X(shifted).  grid = (slabs, chunks, k):
+// blockIdx.z picks the tap row r; each thread keeps k x 8 accumulators.
+template <class T, int KMAX>
+__global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                       float* __restrict__ part, int N, int H, int W,
+                                                       int P, int Q, int Cp, int k, int stride, int pad,
+                                                       ColGrid g) {
+  extern __shared__ float smem[];
+  const int ncv = Cp / 8;
+  const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
+  const int cv = blockIdx.x * g.cvl + cv_lane;
+  const int r = blockIdx.z;
+  const long M = (long)N * P * Q;
+  const long r0 = blockIdx.y * g.rows_per_chunk;
+  const long r1 = min(M, r0 + g.rows_per_chunk);
+  float acc[KMAX][8];
+#pragma unroll
+  for (int t = 0; t < KMAX; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
+  if (cv < ncv)
+    for (long m = r0 + row_lane; m < r1; m += rl) {
+      long pix = m;
+      const int q = (int)(pix % Q); pix /= Q;
+      const int p = (int)(pix % P);
+      const int n = (int)(pix / P);
+      const int h = p * stride + r - pad;
+      if (h < 0 || h >= H) continue;
+      float d[8];
+      IO<T>::ld(dy + (m * ncv + cv) * 8, d);
+#pragma unroll
+      for (int t = 0; t < KMAX; ++t) {
+        const int ww = q * stride + t - pad;
+        if (t < k && ww >= 0 && ww < W) {
+          float v[8];
+          IO<T>::ld(x + ((((long)n * H + h) * W + ww) * ncv + cv) * 8, v);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(d[e], v[e], acc[t][e]);
+        }
+      }
+    }
+  // ordered reduction over the row lanes, one tap at a time
+#pragma unroll
+  for (int t = 0; t < KMAX; ++t) {
+    if (t >= k) break;
+    float out[8];
+    bool owner;
+    block_col_reduce<8>(acc[t], smem, g.cvl, cv_lane, row_lane, out, owner);
+    if (owner && cv < ncv) {
+      float* p = part + ((long)blockIdx.y * k * k + r * k + t) * Cp + cv * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p[e] = out[e];
+    }
+  }
+}
+
+}  // namespace pbd

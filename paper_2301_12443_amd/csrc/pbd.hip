@@ -1,0 +1,1077 @@
+// Host side of libpbd.so: descriptor parsing, workspace planning, the per-block
+// executors and the C ABI declared in include/pbd.h.
+//
+// One step (Algorithm 1 on one device, "internal relaying" of Sec. VII-A):
+//   relay   : A_0 <- cast(x);  A_i <- T_i(A_{i-1}) once each, all kept in HBM
+//   student : for each i: forward S_i on A_{i-1} with batch statistics, fused MSE
+//             loss + gradient against A_i, backward through S_i (no gradient for
+//             A_{i-1}), and the SGD-momentum update straight after (Sec. IV-B).
+// Everything is enqueued on the caller's stream; the library owns no device memory.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/pbd.h"
+#include "conv_kernels.h"
+#include "ew_kernels.h"
+
+using namespace pbd;
+
+namespace {
+
+enum { OP_CBA = 1, OP_POOL = 2, OP_ADD = 3, OP_MIX = 4 };
+constexpr int32_t kMagic = 0x50424431;
+constexpr int kRec = 20;
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+inline int round8(int c) { return (c + 7) / 8 * 8; }
+inline int out_dim(int h, int k, int s, int pad) { return (h + 2 * pad - k) / s + 1; }
+
+struct Shape { int c, h, w; };
+struct OpD { int type, nin, in[8], c_out, k, stride, pad, groups, act, pofs; };
+
+struct OpPlan {
+  OpD d;
+  Shape in, out;
+  int cin_p, cout_p;
+  bool dw;
+  size_t wn = 0;            // physical weight elements
+  // teacher: byte offsets in the parameter region
+  size_t t_w = 0, t_gamma = 0, t_beta = 0, t_rmean = 0, t_rvar = 0, t_a = 0, t_b = 0;
+  // student: element offsets in the block's flat arena; byte offsets for statistics
+  size_t e_w = 0, e_gamma = 0, e_beta = 0;
+  size_t s_rmean = 0, s_rvar = 0, s_mean = 0, s_invstd = 0, s_k2 = 0, s_k3 = 0;
+  long e_wt = -1;           // element offset in the block's transposed-weight arena
+  // scratch byte offsets
+  size_t y = 0, idx = 0;
+};
+
+struct BlockPlan {
+  std::vector<OpPlan> ops;
+  std::vector<Shape> shapes;     // values, 0 = block input
+  std::vector<size_t> val;       // scratch byte offset of each value (>=1)
+  std::vector<size_t> dval;      // scratch byte offset of each value's gradient (student)
+  size_t arena_elems = 0;        // student: w, gamma, beta of all ops, flat
+  size_t master = 0, mom = 0, grad = 0, wc = 0, wt = 0, table = 0;  // byte offsets (param region)
+  size_t wt_elems = 0;
+  std::vector<TransposeEntry> ttable;
+  size_t scratch_bytes = 0;
+  bool dirty = true;             // compute copies stale w.r.t. master weights
+};
+
+}  // namespace
+
+struct pbd_ctx {
+  pbd_opts o{};
+  int B = 0;
+  Shape in{};
+  std::vector<double> pool;
+  std::vector<BlockPlan> net[2];
+  std::vector<Shape> act;               // A_0..A_B
+  std::vector<size_t> act_off;          // byte offsets (relay region)
+  size_t esz = 4;                       // bytes per tensor element
+  // regions (byte offsets from the workspace base)
+  size_t r_param = 0, r_relay = 0, r_tscr = 0, r_sscr = 0, r_red = 0, total = 0;
+  size_t red_bytes = 0;
+  char* ws = nullptr;
+  hipStream_t stream = nullptr;
+  bool bound = false, relayed = false, fold_dirty = true;
+  int last_block = -1;                  // student block whose saved values are in scratch
+  std::string err;
+  // profiling
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev;
+  std::vector<pbd_prof_entry> prof;
+};
+
+namespace {
+
+thread_local std::string g_create_err;  // why the last pbd_create on this thread failed
+
+int fail(pbd_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf; else g_create_err = buf;
+  return code;
+}
+
+#define HIP_TRY(c, expr)                                                                    \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(c, PBD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// ---------------------------------------------------------------------------
+// descriptor -> plan (host only)
+// ---------------------------------------------------------------------------
+bool parse_net(pbd_ctx* c, const int32_t* w, int nw, int& pos, int which, std::string& err) {
+  Shape cur = c->in;
+  for (int b = 0; b < c->B; ++b) {
+    if (pos >= nw) { err = "descriptor truncated"; return false; }
+    BlockPlan bp;
+    const int nops = w[pos++];
+    if (nops < 1) { err = "block without operations"; return false; }
+    bp.shapes.push_back(cur);
+    for (int j = 0; j < nops; ++j, pos += kRec) {
+      if (pos + kRec > nw) { err = "descriptor truncated"; return false; }
+      const int32_t* r = w + pos;
+      OpPlan op{};
+      OpD& o = op.d;
+      o.type = r[0]; o.nin = r[1];
+      for (int i = 0; i < 8; ++i) o.in[i] = r[2 + i];
+      o.c_out = r[10]; o.k = r[11]; o.stride = r[12]; o.pad = r[13];
+      o.groups = r[14]; o.act = r[15]; o.pofs = r[16];
+      if (o.nin < 1 || o.nin > 8) { err = "bad input count"; return false; }
+      for (int i = 0; i < o.nin; ++i)
+        if (o.in[i] < 0 || o.in[i] > j) { err = "operation input refers forward"; return false; }
+      if (o.act < 0 || o.act > 2) { err = "unknown activation"; return false; }
+      const Shape s = bp.shapes[o.in[0]];
+      Shape out = s;
+      if (o.type == OP_CBA) {
+        if (o.nin != 1 || o.k < 1 || o.k > 7 || o.stride < 1 || o.stride > 2 || o.pad != o.k / 2 ||
+            o.c_out < 1) { err = "unsupported convolution geometry"; return false; }
+        if (o.groups != 1 && (o.groups != s.c || o.c_out != s.c)) { err = "groups must be 1 or C_in == C_out"; return false; }
+        if (o.groups == 1 && o.c_out % 8) { err = "dense convolution needs C_out % 8 == 0"; return false; }
+        out = {o.c_out, out_dim(s.h, o.k, o.stride, o.pad), out_dim(s.w, o.k, o.stride, o.pad)};
+      } else if (o.type == OP_POOL) {
+        if (o.nin != 1 || o.k < 1 || o.k > 15 || o.stride < 1 || o.pad < 0 || o.pad >= o.k) { err = "unsupported pooling geometry"; return false; }
+        out = {s.c, out_dim(s.h, o.k, o.stride, o.pad), out_dim(s.w, o.k, o.stride, o.pad)};
+      } else if (o.type == OP_ADD || o.type == OP_MIX) {
+        if (o.type == OP_ADD && o.nin != 2) { err = "add takes two inputs"; return false; }
+        if (o.type == OP_MIX && (o.pofs < 0 || o.pofs + o.nin > (int)c->pool.size())) { err = "mix weights outside the pool"; return false; }
+        for (int i = 1; i < o.nin; ++i) {
+          const Shape t = bp.shapes[o.in[i]];
+          if (t.c != s.c || t.h != s.h || t.w != s.w) { err = "joined values differ in shape"; return false; }
+        }
+      } else { err = "unknown operation type"; return false; }
+      if (out.h < 1 || out.w < 1) { err = "empty output"; return false; }
+      op.in = s; op.out = out;
+      op.cin_p = round8(s.c); op.cout_p = round8(out.c);
+      op.dw = o.type == OP_CBA && o.groups != 1;
+      if (o.type == OP_CBA) op.wn = op.dw ? (size_t)o.k * o.k * op.cout_p : (size_t)o.c_out * o.k * o.k * op.cin_p;
+      bp.ops.push_back(op);
+      bp.shapes.push_back(out);
+    }
+    cur = bp.shapes.back();
+    c->net[which].push_back(std::move(bp));
+  }
+  return true;
+}
+
+size_t tensor_bytes(const pbd_ctx* c, Shape s) {
+  return align_up((size_t)c->o.batch * s.h * s.w * round8(s.c) * c->esz);
+}
+
+ColGrid col_grid(long M, int Cp) {
+  ColGrid g;
+  const int ncv = Cp / 8;
+  int cvl = 1;
+  while (cvl < ncv && cvl < 32) cvl *= 2;
+  g.cvl = cvl;
+  g.slabs = (ncv + cvl - 1) / cvl;
+  const int rl = 256 / cvl;
+  long chunks = (M + (long)rl * 8 - 1) / ((long)rl * 8);
+  const long cap = std::max(1, 2048 / g.slabs);
+  chunks = std::max(1L, std::min(chunks, cap));
+  g.rows_per_chunk = (M + chunks - 1) / chunks;
+  g.chunks = (int)((M + g.rows_per_chunk - 1) / g.rows_per_chunk);
+  return g;
+}
+
+struct WgradCfg { int T, BKP, tiles_k, tiles_j, splits, pix_per_split; };
+WgradCfg wgrad_cfg(long M, int K, int J) {
+  WgradCfg w;
+  if (K >= 128 && J >= 128) { w.T = 128; w.BKP = 64; } else { w.T = 64; w.BKP = 128; }
+  w.tiles_k = (K + w.T - 1) / w.T;
+  w.tiles_j = (J + w.T - 1) / w.T;
+  const long tiles = (long)w.tiles_k * w.tiles_j;
+  long splits = std::max(1L, 1024 / tiles);
+  const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
+  splits = std::min(splits, max_by_mem);
+  splits = std::min(splits, (M + w.BKP - 1) / w.BKP);
+  long pps = (M + splits - 1) / splits;
+  pps = (pps + w.BKP - 1) / w.BKP * w.BKP;
+  w.pix_per_split = (int)pps;
+  w.splits = (int)((M + pps - 1) / pps);
+  return w;
+}
+
+constexpr int kMseBlocks = 1024;
+
+int plan(pbd_ctx* c) {
+  const size_t es = c->esz;
+  const bool bf = c->o.precision == PBD_BF16;
+  size_t p = 0;  // parameter region cursor
+  auto take = [&](size_t bytes) { size_t o = p; p += align_up(bytes); return o; };
+  size_t red = 0;
+  auto need_red = [&](size_t bytes) { red = std::max(red, bytes); };
+  need_red(kMseBlocks * sizeof(float));
+
+  // teacher parameters
+  for (BlockPlan& bp : c->net[0])
+    for (OpPlan& op : bp.ops) {
+      if (op.d.type != OP_CBA) continue;
+      op.t_w = take(op.wn * es);
+      op.t_gamma = take(op.cout_p * 4); op.t_beta = take(op.cout_p * 4);
+      op.t_rmean = take(op.cout_p * 4); op.t_rvar = take(op.cout_p * 4);
+      op.t_a = take(op.cout_p * 4); op.t_b = take(op.cout_p * 4);
+    }
+  // student parameters: one flat arena per block
+  for (BlockPlan& bp : c->net[1]) {
+    size_t e = 0, et = 0;
+    for (OpPlan& op : bp.ops) {
+      if (op.d.type != OP_CBA) continue;
+      op.e_w = e; e += op.wn;
+      op.e_gamma = e; e += op.cout_p;
+      op.e_beta = e; e += op.cout_p;
+      for (size_t* s : {&op.s_rmean, &op.s_rvar, &op.s_mean, &op.s_invstd, &op.s_k2, &op.s_k3})
+        *s = take(op.cout_p * 4);
+      // transposed copy for backward-data of dense convolutions that need it
+      if (!op.dw && op.d.in[0] != 0 && bf) {
+        op.e_wt = (long)et;
+        bp.ttable.push_back({(long)op.e_w, (long)et, op.d.c_out, op.d.k * op.d.k, op.cin_p});
+        et += op.wn;
+      }
+    }
+    bp.arena_elems = e;
+    bp.wt_elems = et;
+    bp.master = take(e * 4); bp.mom = take(e * 4); bp.grad = take(e * 4);
+    bp.wc = bf ? take(e * 2) : bp.master;
+    bp.wt = take(std::max<size_t>(et, 1) * es);
+    bp.table = take(std::max<size_t>(bp.ttable.size(), 1) * sizeof(TransposeEntry));
+  }
+  c->r_param = 0;
+  size_t cur = align_up(p);
+  // relay store A_0..A_B
+  c->r_relay = cur;
+  c->act_off.clear();
+  size_t r = 0;
+  for (Shape s : c->act) { c->act_off.push_back(r); r += tensor_bytes(c, s); }
+  cur += r;
+  // teacher scratch: every value of the largest block except its output (-> relay)
+  size_t tmax = 0;
+  for (BlockPlan& bp : c->net[0]) {
+    size_t s = 0;
+    bp.val.assign(bp.shapes.size(), 0);
+    for (size_t v = 1; v + 1 < bp.shapes.size(); ++v) { bp.val[v] = s; s += tensor_bytes(c, bp.shapes[v]); }
+    bp.scratch_bytes = s;
+    tmax = std::max(tmax, s);
+  }
+  c->r_tscr = cur; cur += align_up(tmax);
+  // student scratch per block: values, conv outputs, pool indices, value gradients
+  size_t smax = 0;
+  for (BlockPlan& bp : c->net[1]) {
+    size_t s = 0;
+    bp.val.assign(bp.shapes.size(), 0);
+    bp.dval.assign(bp.shapes.size(), 0);
+    for (size_t v = 1; v < bp.shapes.size(); ++v) {
+      bp.val[v] = s; s += tensor_bytes(c, bp.shapes[v]);
+      bp.dval[v] = s; s += tensor_bytes(c, bp.shapes[v]);
+      OpPlan& op = bp.ops[v - 1];
+      const long M = (long)c->o.batch * op.out.h * op.out.w;
+      if (op.d.type == OP_CBA) {
+        op.y = s; s += tensor_bytes(c, op.out);
+        const ColGrid g = col_grid(M, op.cout_p);
+        need_red((size_t)g.chunks * 2 * op.cout_p * 4);
+        if (op.dw) {
+          need_red((size_t)g.chunks * op.d.k * op.d.k * op.cout_p * 4);
+        } else if (bf && !c->o.force_direct) {
+          const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
+          need_red((size_t)w.splits * op.wn * 4);
+        }
+      } else if (op.d.type == OP_POOL) {
+        op.idx = s; s += align_up((size_t)M * op.cout_p);
+      }
+    }
+    bp.scratch_bytes = s;
+    smax = std::max(smax, s);
+  }
+  c->r_sscr = cur; cur += align_up(smax);
+  c->r_red = cur; c->red_bytes = align_up(red); cur += c->red_bytes;
+  c->total = cur;
+  return PBD_OK;
+}
+
+// ---------------------------------------------------------------------------
+// launch plumbing
+// ---------------------------------------------------------------------------
+inline int grid_for(long n, int block = 256, int cap = 256 * 32) {
+  return (int)std::max(1L, std::min<long>((n + block - 1) / block, cap));
+}
+
+struct ProfScope {
+  pbd_ctx* c;
+  bool on;
+  ProfScope(pbd_ctx* ctx, const char* name, double bytes, double flops, int net, int block, int op) : c(ctx), on(ctx->prof_on) {
+    if (!on) return;
+    pbd_prof_entry e{};
+    snprintf(e.name, sizeof e.name, "%s", name);
+    e.bytes = bytes; e.flops = flops; e.net = net; e.block = block; e.op = op;
+    c->prof.push_back(e);
+    const size_t need = c->prof.size() * 2;
+    while (c->ev.size() < need) { hipEvent_t ev; (void)hipEventCreate(&ev); c->ev.push_back(ev); }
+    (void)hipEventRecord(c->ev[need - 2], c->stream);
+  }
+  ~ProfScope() { if (on) (void)hipEventRecord(c->ev[c->prof.size() * 2 - 1], c->stream); }
+};
+
+template <class T> struct Exec {
+  pbd_ctx* c;
+  hipStream_t st;
+  int net = 0, blk = 0, opi = 0;
+  explicit Exec(pbd_ctx* ctx) : c(ctx), st(ctx->stream) {}
+
+  T* ws(size_t off) const { return reinterpret_cast<T*>(c->ws + off); }
+  float* wsf(size_t off) const { return reinterpret_cast<float*>(c->ws + off); }
+  T* relay(int i) const { return ws(c->r_relay + c->act_off[i]); }
+  float* red() const { return wsf(c->r_red); }
+  double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
+  bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
+
+  // ---- convolution forward (dense) --------------------------------------
+  void conv_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
+    const int N = c->o.batch;
+    const double flops = 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k * op.in.c;
+    const double bytes = bytes_of(op.in) + bytes_of(op.out) + (double)op.wn * sizeof(T);
+    if (mfma()) {
+      if constexpr (sizeof(T) == 2) {
+        IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
+                    op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p};
+        ProfScope ps(c, a ? "conv_fwd_mfma_affine" : "conv_fwd_mfma", bytes, flops, net, blk, opi);
+        launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE);
+      }
+    } else {
+      ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
+      ProfScope ps(c, "conv_fwd_direct", bytes, flops, net, blk, opi);
+      conv_direct_fwd_kernel<T, T><<<grid_for((long)g.N * g.P * g.Q * g.K), 256, 0, st>>>(x, w, y, a, b, act, g);
+    }
+  }
+
+  template <int MODE>
+  void launch_igemm(const IgemmArgs& g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
+                    const float* b, int act, int epi) {
+    const int BN = g.NC >= 128 ? 128 : (g.NC > 32 ? 64 : 32);
+    dim3 grid((g.M + IG_BM - 1) / IG_BM, (g.NC + BN - 1) / BN);
+#define PBD_IG(BN_, EPI_) igemm_kernel<MODE, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, out, a, b, act, g)
+#define PBD_IG_BN(EPI_) do { if (BN == 128) PBD_IG(128, EPI_); else if (BN == 64) PBD_IG(64, EPI_); else PBD_IG(32, EPI_); } while (0)
+    if (epi == EPI_AFFINE_ACT) PBD_IG_BN(EPI_AFFINE_ACT);
+    else if (epi == EPI_ACCUM) PBD_IG_BN(EPI_ACCUM);
+    else PBD_IG_BN(EPI_STORE);
+#undef PBD_IG_BN
+#undef PBD_IG
+  }
+
+  // ---- convolution backward-data (dense) ---------------------------------
+  void conv_dgrad(const OpPlan& op, const T* dy, const T* w, const T* wt, T* dx, bool accumulate) {
+    const int N = c->o.batch;
+    const double flops = 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k * op.in.c;
+    const double bytes = bytes_of(op.in) + bytes_of(op.out) + (double)op.wn * sizeof(T);
+    if (mfma()) {
+      if constexpr (sizeof(T) == 2) {
+        // rows = input pixels, columns = input channels, reduction over (r, s, k)
+        IgemmArgs g{N, op.out.h, op.out.w, op.d.c_out, op.in.h, op.in.w, op.cin_p, op.d.k, op.d.k,
+                    op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out};
+        ProfScope ps(c, "conv_dgrad_mfma", bytes, flops, net, blk, opi);
+        launch_igemm<1>(g, (const bf16_t*)dy, (const bf16_t*)wt, (bf16_t*)dx, nullptr, nullptr, 0,
+                        accumulate ? EPI_ACCUM : EPI_STORE);
+      }
+    } else {
+      ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
+      ProfScope ps(c, "conv_dgrad_direct", bytes, flops, net, blk, opi);
+      conv_direct_dgrad_kernel<T, T><<<grid_for((long)g.N * g.H * g.W * g.C), 256, 0, st>>>(dy, w, dx, accumulate, g);
+    }
+  }
+
+  // ---- convolution backward-weight (dense) -------------------------------
+  void conv_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
+    const int N = c->o.batch;
+    const long M = (long)N * op.out.h * op.out.w;
+    const int J = op.d.k * op.d.k * op.cin_p;
+    const double flops = 2.0 * M * op.d.c_out * op.d.k * op.d.k * op.in.c;
+    const double bytes = bytes_of(op.in) + bytes_of(op.out) + (double)op.wn * 4;
+    if (mfma()) {
+      if constexpr (sizeof(T) == 2) {
+        const WgradCfg w = wgrad_cfg(M, op.d.c_out, J);
+        WgradArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
+                    op.d.stride, op.d.pad, (int)M, J, w.pix_per_split};
+        dim3 grid(w.tiles_k, w.tiles_j, w.splits);
+        float* part = w.splits == 1 ? dw : red();
+        {
+          ProfScope ps(c, "conv_wgrad_mfma", bytes, flops, net, blk, opi);
+          if (w.T == 128) wgrad_kernel<128, 64><<<grid, 256, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, part, g);
+          else wgrad_kernel<64, 128><<<grid, 256, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, part, g);
+        }
+        if (w.splits > 1) {
+          ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
+          sum_partials_kernel<<<grid_for((long)op.wn), 256, 0, st>>>(part, dw, (long)op.wn, w.splits, (long)op.wn);
+        }
+      }
+    } else {
+      ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
+      ProfScope ps(c, "conv_wgrad_direct", bytes, flops, net, blk, opi);
+      conv_direct_wgrad_kernel<T><<<grid_for((long)op.wn, 64), 64, 0, st>>>(dy, x, dw, g);
+    }
+  }
+
+  // ---- depthwise ----------------------------------------------------------
+  void dw_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
+    const int N = c->o.batch, ncv = op.cout_p / 8;
+    const long nvec = (long)N * op.out.h * op.out.w * ncv;
+    ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+    dw_fwd_kernel<T, T><<<grid_for(nvec), 256, 0, st>>>(x, w, y, a, b, act, N, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                        ncv, op.d.k, op.d.stride, op.d.pad);
+  }
+  void dw_dgrad(const OpPlan& op, const T* dy, const T* w, T* dx, bool accumulate) {
+    const int N = c->o.batch, ncv = op.cout_p / 8;
+    const long nvec = (long)N * op.in.h * op.in.w * ncv;
+    ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+    dw_dgrad_kernel<T, T><<<grid_for(nvec), 256, 0, st>>>(dy, w, dx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
+                                                          op.d.k, op.d.stride, op.d.pad, accumulate ? 1 : 0);
+  }
+  void dw_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
+    const int N = c->o.batch;
+    const long M = (long)N * op.out.h * op.out.w;
+    const ColGrid g = col_grid(M, op.cout_p);
+    dim3 grid(g.slabs, g.chunks, op.d.k);
+    const size_t smem = 256 * 8 * sizeof(float);
+    {
+      ProfScope ps(c, "dw_wgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+      if (op.d.k <= 3)
+        dw_wgrad_kernel<T, 3><<<grid, 256, smem, st>>>(dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                       op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
+      else
+        dw_wgrad_kernel<T, 7><<<grid, 256, smem, st>>>(dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                       op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
+    }
+    ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
+    sum_partials_kernel<<<grid_for((long)op.wn), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
+  }
+
+  // ---- joins / pool -------------------------------------------------------
+  void join_fwd(const OpPlan& op, const Join& j, T* z) {
+    const long nvec = (long)c->o.batch * op.out.h * op.out.w * op.cout_p / 8;
+    ProfScope ps(c, "join_fwd", bytes_of(op.out) * (j.n + 1), 0, net, blk, opi);
+    join_fwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(j, z, nvec, op.d.act);
+  }
+  void pool_fwd(const OpPlan& op, const T* x, T* z, uint8_t* idx) {
+    const int N = c->o.batch, ncv = op.cout_p / 8;
+    const long nvec = (long)N * op.out.h * op.out.w * ncv;
+    ProfScope ps(c, "maxpool_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+    maxpool_fwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
+                                                          op.d.k, op.d.stride, op.d.pad);
+  }
+
+  // =========================================================================
+  // teacher block b: inference mode, output straight into the relay store
+  // =========================================================================
+  void teacher_block(int b) {
+    BlockPlan& bp = c->net[0][b];
+    net = PBD_TEACHER; blk = b;
+    auto value = [&](int v) -> T* {
+      if (v == 0) return relay(b);
+      if (v + 1 == (int)bp.shapes.size()) return relay(b + 1);
+      return ws(c->r_tscr + bp.val[v]);
+    };
+    for (size_t j = 0; j < bp.ops.size(); ++j) {
+      const OpPlan& op = bp.ops[j];
+      opi = (int)j;
+      T* out = value((int)j + 1);
+      const T* x = value(op.d.in[0]);
+      if (op.d.type == OP_CBA) {
+        const T* w = ws(op.t_w);
+        if (op.dw) dw_fwd(op, x, w, out, wsf(op.t_a), wsf(op.t_b), op.d.act);
+        else conv_fwd(op, x, w, out, wsf(op.t_a), wsf(op.t_b), op.d.act);
+      } else if (op.d.type == OP_POOL) {
+        pool_fwd(op, x, out, nullptr);
+      } else {
+        Join jn{};
+        jn.n = op.d.nin;
+        for (int k = 0; k < op.d.nin; ++k) {
+          jn.src[k] = value(op.d.in[k]);
+          jn.p[k] = op.d.type == OP_MIX ? (float)c->pool[op.d.pofs + k] : 1.f;
+        }
+        join_fwd(op, jn, out);
+      }
+    }
+  }
+
+  void fold_teacher_bn() {
+    for (BlockPlan& bp : c->net[0])
+      for (OpPlan& op : bp.ops)
+        if (op.d.type == OP_CBA)
+          bn_fold_kernel<<<(op.cout_p + 255) / 256, 256, 0, st>>>(wsf(op.t_gamma), wsf(op.t_beta), wsf(op.t_rmean),
+                                                                  wsf(op.t_rvar), wsf(op.t_a), wsf(op.t_b), op.cout_p,
+                                                                  c->o.bn_eps);
+    c->fold_dirty = false;
+  }
+
+  void relay_all(const float* x_dev) {
+    if (c->fold_dirty) fold_teacher_bn();
+    {
+      const Shape s = c->act[0];
+      const long nvec = (long)c->o.batch * s.h * s.w * round8(s.c) / 8;
+      net = PBD_TEACHER; blk = -1; opi = -1;
+      ProfScope ps(c, "cast_input", (double)c->o.batch * s.c * s.h * s.w * 4 + bytes_of(s), 0, net, blk, opi);
+      cast_input_kernel<T><<<grid_for(nvec), 256, 0, st>>>(x_dev, relay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
+    }
+    for (int b = 0; b < c->B; ++b) teacher_block(b);
+    c->relayed = true;
+  }
+
+  // =========================================================================
+  // student block b = i-1: forward, loss, backward, update
+  // =========================================================================
+  void refresh_compute_copies(BlockPlan& bp) {
+    if constexpr (sizeof(T) == 2) {
+      cast_params_kernel<<<grid_for((long)bp.arena_elems / 4), 256, 0, st>>>(wsf(bp.master), (bf16_t*)ws(bp.wc),
+                                                                             (long)bp.arena_elems / 4);
+    }
+    transpose_weights(bp);
+    bp.dirty = false;
+  }
+  void transpose_weights(BlockPlan& bp) {
+    if (bp.ttable.empty()) return;
+    ProfScope ps(c, "transpose_weights", 2.0 * bp.wt_elems * sizeof(T), 0, net, blk, -1);
+    dim3 grid(64, (unsigned)bp.ttable.size());
+    transpose_weights_kernel<T><<<grid, 256, 0, st>>>(ws(bp.wc), ws(bp.wt),
+                                                      reinterpret_cast<const TransposeEntry*>(c->ws + bp.table));
+  }
+
+  void student_block(int b, float lr, float* loss_dev) {
+    BlockPlan& bp = c->net[1][b];
+    net = PBD_STUDENT; blk = b;
+    if (bp.dirty) refresh_compute_copies(bp);
+    const int N = c->o.batch;
+    const size_t scr = c->r_sscr;
+    auto value = [&](int v) -> T* { return v == 0 ? relay(b) : ws(scr + bp.val[v]); };
+    auto dvalue = [&](int v) -> T* { return ws(scr + bp.dval[v]); };
+    T* wc = ws(bp.wc);
+    float* grad = wsf(bp.grad);
+    const float* master = wsf(bp.master);
+    const int nval = (int)bp.shapes.size();
+
+    // ---- forward ----------------------------------------------------------
+    for (size_t j = 0; j < bp.ops.size(); ++j) {
+      const OpPlan& op = bp.ops[j];
+      opi = (int)j;
+      T* z = value((int)j + 1);
+      const T* x = value(op.d.in[0]);
+      if (op.d.type == OP_CBA) {
+        T* y = ws(scr + op.y);
+        if (op.dw) dw_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0);
+        else conv_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0);
+        const long M = (long)N * op.out.h * op.out.w;
+        const ColGrid g = col_grid(M, op.cout_p);
+        {
+          ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
+          bn_stats_kernel<T><<<dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st>>>(y, red(), M, op.cout_p, g);
+        }
+        bn_finalize_kernel<T><<<(op.cout_p + 127) / 128, 128, 0, st>>>(
+            red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
+            wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
+        {
+          const long nvec = M * op.cout_p / 8;
+          ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
+          bn_apply_kernel<T><<<grid_for(nvec), 256, 0, st>>>(y, z, wsf(op.s_mean), wsf(op.s_invstd), master + op.e_gamma,
+                                                          master + op.e_beta, nvec, op.cout_p / 8, op.d.act);
+        }
+      } else if (op.d.type == OP_POOL) {
+        pool_fwd(op, x, z, reinterpret_cast<uint8_t*>(c->ws + scr + op.idx));
+      } else {
+        Join jn{};
+        jn.n = op.d.nin;
+        for (int k = 0; k < op.d.nin; ++k) {
+          jn.src[k] = value(op.d.in[k]);
+          jn.p[k] = op.d.type == OP_MIX ? (float)c->pool[op.d.pofs + k] : 1.f;
+        }
+        join_fwd(op, jn, z);
+      }
+    }
+
+    // ---- loss and its gradient (fused) -----------------------------------
+    {
+      const Shape s = bp.shapes.back();
+      const long numel = (long)N * s.h * s.w * s.c;   // outputs have no padded channels
+      const long nvec = (long)N * s.h * s.w * round8(s.c) / 8;
+      const int nb = (int)std::min<long>(kMseBlocks, (nvec + 255) / 256);
+      opi = -1;
+      ProfScope ps(c, "mse_loss_grad", 3 * bytes_of(s), 0, net, blk, opi);
+      mse_kernel<T><<<nb, 256, 0, st>>>(value(nval - 1), relay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
+      mse_final_kernel<<<1, 64, 0, st>>>(red(), nb, 1.0 / (double)numel, loss_dev);
+    }
+
+    // ---- backward ---------------------------------------------------------
+    std::vector<char> have(nval, 0);
+    have[nval - 1] = 1;
+    for (int j = (int)bp.ops.size() - 1; j >= 0; --j) {
+      const OpPlan& op = bp.ops[j];
+      opi = j;
+      if (!have[j + 1]) continue;
+      T* dz = dvalue(j + 1);
+      const int iv = op.d.in[0];
+      if (op.d.type == OP_CBA) {
+        const T* y = ws(scr + op.y);
+        const long M = (long)N * op.out.h * op.out.w;
+        const ColGrid g = col_grid(M, op.cout_p);
+        {
+          ProfScope ps(c, "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
+          bn_bwd_reduce_kernel<T><<<dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st>>>(
+              dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
+              op.d.act, g);
+        }
+        bn_bwd_finalize_kernel<<<(op.cout_p + 127) / 128, 128, 0, st>>>(red(), g.chunks, op.cout_p, (double)M,
+                                                                         grad + op.e_gamma, grad + op.e_beta,
+                                                                         wsf(op.s_k2), wsf(op.s_k3));
+        {
+          const long nvec = M * op.cout_p / 8;
+          ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
+          bn_bwd_apply_kernel<T><<<grid_for(nvec), 256, 0, st>>>(dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean),
+                                                                 wsf(op.s_invstd), wsf(op.s_k2), wsf(op.s_k3), nvec,
+                                                                 op.cout_p / 8, op.d.act);
+        }
+        const T* x = value(iv);
+        if (op.dw) dw_wgrad(op, dz, x, grad + op.e_w);
+        else conv_wgrad(op, dz, x, grad + op.e_w);
+        if (iv != 0) {  // A_{i-1} is a constant: no backward-data for the block's first layer
+          if (op.dw) dw_dgrad(op, dz, wc + op.e_w, dvalue(iv), have[iv]);
+          else conv_dgrad(op, dz, wc + op.e_w, op.e_wt >= 0 ? ws(bp.wt) + op.e_wt : nullptr, dvalue(iv), have[iv]);
+          have[iv] = 1;
+        }
+      } else if (op.d.type == OP_POOL) {
+        if (iv != 0) {
+          const int ncv = op.cout_p / 8;
+          const long nvec = (long)N * op.in.h * op.in.w * ncv;
+          ProfScope ps(c, "maxpool_bwd", bytes_of(op.in) + 1.5 * bytes_of(op.out), 0, net, blk, opi);
+          maxpool_bwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(dz, reinterpret_cast<const uint8_t*>(c->ws + scr + op.idx),
+                                                                dvalue(iv), N, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                                ncv, op.d.k, op.d.stride, op.d.pad, have[iv] ? 1 : 0);
+          have[iv] = 1;
+        }
+      } else {
+        Join jn{};
+        jn.n = op.d.nin;
+        int live = 0;
+        for (int k = 0; k < op.d.nin; ++k) {
+          const int v = op.d.in[k];
+          jn.p[k] = op.d.type == OP_MIX ? (float)c->pool[op.d.pofs + k] : 1.f;
+          jn.dst[k] = v == 0 ? nullptr : dvalue(v);
+          jn.accumulate[k] = v != 0 && have[v];
+          if (v != 0) { have[v] = 1; ++live; }
+        }
+        if (live) {
+          const long nvec = (long)N * op.out.h * op.out.w * op.cout_p / 8;
+          ProfScope ps(c, "join_bwd", bytes_of(op.out) * (live + 1 + (op.d.act ? 1 : 0)), 0, net, blk, opi);
+          join_bwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(jn, dz, value(j + 1), nvec, op.d.act);
+        }
+      }
+    }
+
+    // ---- decoupled update of this block only -----------------------------
+    {
+      opi = -1;
+      const long n4 = (long)bp.arena_elems / 4;
+      ProfScope ps(c, "sgd_momentum", (double)bp.arena_elems * (20 + (sizeof(T) == 2 ? 2 : 0)), 0, net, blk, opi);
+      if constexpr (sizeof(T) == 2)
+        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, (bf16_t*)wc, n4, lr, c->o.momentum);
+      else
+        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, nullptr, n4, lr, c->o.momentum);
+    }
+    transpose_weights(bp);
+    c->last_block = b;
+  }
+};
+
+// ---------------------------------------------------------------------------
+// host <-> device tensor marshalling (textbook layouts on the host side)
+// ---------------------------------------------------------------------------
+inline uint16_t f2bf(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+inline float bf2f(uint16_t h) {
+  const uint32_t u = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+// textbook index of physical weight element e (or -1 for a padded channel)
+long weight_host_index(const OpPlan& op, size_t e) {
+  const int k = op.d.k;
+  if (op.dw) {
+    const int c = (int)(e % op.cout_p);
+    const int rs = (int)(e / op.cout_p);
+    if (c >= op.d.c_out) return -1;
+    return (long)c * k * k + rs;
+  }
+  const int c = (int)(e % op.cin_p);
+  size_t t = e / op.cin_p;
+  const int rs = (int)(t % (k * k));
+  const int ko = (int)(t / (k * k));
+  if (c >= op.in.c) return -1;
+  return ((long)ko * op.in.c + c) * k * k + rs;
+}
+
+int check_ready(pbd_ctx* c) {
+  if (!c) return PBD_EINVAL;
+  if (!c->bound) return fail(c, PBD_ESTATE, "no workspace bound (call pbd_bind first)");
+  return PBD_OK;
+}
+
+int after_launches(pbd_ctx* c) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(c, PBD_EHIP, "kernel launch failed: %s", hipGetErrorString(e));
+  return PBD_OK;
+}
+
+OpPlan* find_cba(pbd_ctx* c, int net, int b, int op) {
+  if (net < 0 || net > 1 || b < 0 || b >= c->B) return nullptr;
+  if (op < 0 || op >= (int)c->net[net][b].ops.size()) return nullptr;
+  OpPlan* p = &c->net[net][b].ops[op];
+  return p->d.type == OP_CBA ? p : nullptr;
+}
+
+// device address, element type (0 f32, 1 bf16) and sizes of one addressed tensor
+struct TensorRef { char* ptr; bool bf; bool weight; size_t phys; size_t logical; };
+int locate(pbd_ctx* c, int kind, int net, int b, int opi, int slot, TensorRef& t) {
+  OpPlan* op = find_cba(c, net, b, opi);
+  if (!op) return fail(c, PBD_EINVAL, "no conv+BN operation at net %d block %d op %d", net, b, opi);
+  if (slot < PBD_WEIGHT || slot > PBD_RVAR) return fail(c, PBD_EINVAL, "slot %d out of range", slot);
+  if (kind < PBD_PARAM || kind > PBD_MOMENTUM) return fail(c, PBD_EINVAL, "kind %d out of range", kind);
+  if (kind != PBD_PARAM && (net != PBD_STUDENT || slot > PBD_BETA))
+    return fail(c, PBD_EINVAL, "gradients and momentum exist for student weight/gamma/beta only");
+  t.weight = slot == PBD_WEIGHT;
+  t.phys = t.weight ? op->wn : (size_t)op->cout_p;
+  t.logical = t.weight ? (size_t)op->d.c_out * (op->in.c / op->d.groups) * op->d.k * op->d.k : (size_t)op->d.c_out;
+  t.bf = false;
+  if (net == PBD_TEACHER) {
+    const size_t off[5] = {op->t_w, op->t_gamma, op->t_beta, op->t_rmean, op->t_rvar};
+    t.ptr = c->ws + off[slot];
+    t.bf = t.weight && c->o.precision == PBD_BF16;
+  } else {
+    BlockPlan& bp = c->net[1][b];
+    if (slot <= PBD_BETA) {
+      const size_t base = kind == PBD_PARAM ? bp.master : (kind == PBD_GRAD ? bp.grad : bp.mom);
+      const size_t e = slot == PBD_WEIGHT ? op->e_w : (slot == PBD_GAMMA ? op->e_gamma : op->e_beta);
+      t.ptr = c->ws + base + e * 4;
+    } else {
+      t.ptr = c->ws + (slot == PBD_RMEAN ? op->s_rmean : op->s_rvar);
+    }
+  }
+  return PBD_OK;
+}
+
+int upload(pbd_ctx* c, const TensorRef& t, const OpPlan& op, const float* host) {
+  std::vector<float> phys(t.phys, 0.f);
+  for (size_t e = 0; e < t.phys; ++e) {
+    const long h = t.weight ? weight_host_index(op, e) : ((long)e < (long)t.logical ? (long)e : -1);
+    if (h >= 0) phys[e] = host[h];
+  }
+  if (t.bf) {
+    std::vector<uint16_t> h16(t.phys);
+    for (size_t e = 0; e < t.phys; ++e) h16[e] = f2bf(phys[e]);
+    HIP_TRY(c, hipMemcpyAsync(t.ptr, h16.data(), t.phys * 2, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(t.ptr, phys.data(), t.phys * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  return PBD_OK;
+}
+
+// NHWC (Cp) device tensor -> NCHW float host
+int download_act(pbd_ctx* c, const char* dev, Shape s, float* host) {
+  const int N = c->o.batch, cp = round8(s.c);
+  const size_t n = (size_t)N * s.h * s.w * cp;
+  std::vector<float> f(n);
+  if (c->esz == 2) {
+    std::vector<uint16_t> h16(n);
+    HIP_TRY(c, hipMemcpyAsync(h16.data(), dev, n * 2, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (size_t i = 0; i < n; ++i) f[i] = bf2f(h16[i]);
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(f.data(), dev, n * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  const size_t hw = (size_t)s.h * s.w;
+  for (int nn = 0; nn < N; ++nn)
+    for (size_t p = 0; p < hw; ++p)
+      for (int ch = 0; ch < s.c; ++ch)
+        host[((size_t)nn * s.c + ch) * hw + p] = f[((size_t)nn * hw + p) * cp + ch];
+  return PBD_OK;
+}
+
+template <class F> int dispatch(pbd_ctx* c, F&& f) {
+  if (c->o.precision == PBD_BF16) { Exec<bf16_t> e(c); f(e); }
+  else { Exec<float> e(c); f(e); }
+  return after_launches(c);
+}
+
+int check_view(pbd_ctx* c, const pbd_tensor* t, int i, const char* what) {
+  if (!t) return fail(c, PBD_EINVAL, "%s is null", what);
+  const Shape s = c->act[i];
+  if (t->ptr != c->ws + c->r_relay + c->act_off[i] || t->n != c->o.batch || t->c != s.c || t->h != s.h ||
+      t->w != s.w || t->c_phys != round8(s.c) || t->dtype != c->o.precision)
+    return fail(c, PBD_ESHAPE, "%s is not the relayed activation A_%d", what, i);
+  return PBD_OK;
+}
+
+void fill_view(pbd_ctx* c, int i, pbd_tensor* t) {
+  const Shape s = c->act[i];
+  t->ptr = c->ws + c->r_relay + c->act_off[i];
+  t->n = c->o.batch; t->c = s.c; t->h = s.h; t->w = s.w;
+  t->c_phys = round8(s.c);
+  t->dtype = c->o.precision;
+}
+
+}  // namespace
+
+// ===========================================================================
+// C ABI
+// ===========================================================================
+extern "C" {
+
+int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t npool,
+               const pbd_opts* opts, pbd_ctx** out) {
+  if (!out) return fail(nullptr, PBD_EINVAL, "out is null");
+  *out = nullptr;
+  if (!words || !opts || (npool > 0 && !pool)) return fail(nullptr, PBD_EINVAL, "null argument");
+  if (nwords < 6 || words[0] != kMagic || words[1] != 1) return fail(nullptr, PBD_ESHAPE, "bad descriptor header");
+  if (opts->batch < 1 || (opts->precision != PBD_F32 && opts->precision != PBD_BF16))
+    return fail(nullptr, PBD_EINVAL, "batch must be >= 1 and precision PBD_F32 or PBD_BF16");
+  if (!(opts->momentum >= 0.f && opts->momentum < 1.f) || !(opts->bn_eps > 0.f) ||
+      !(opts->bn_momentum >= 0.f && opts->bn_momentum <= 1.f))
+    return fail(nullptr, PBD_EINVAL, "momentum, bn_eps or bn_momentum out of range");
+  pbd_ctx* c = new pbd_ctx;
+  c->o = *opts;
+  c->esz = opts->precision == PBD_BF16 ? 2 : 4;
+  c->B = words[2];
+  c->in = {words[3], words[4], words[5]};
+  if (c->B < 1 || c->B > 1024 || c->in.c < 1 || c->in.h < 1 || c->in.w < 1) {
+    delete c;
+    return fail(nullptr, PBD_ESHAPE, "block count or input shape out of range");
+  }
+  if (npool > 0) c->pool.assign(pool, pool + npool);
+  int pos = 6;
+  std::string err;
+  for (int which = 0; which < 2; ++which)
+    if (!parse_net(c, words, nwords, pos, which, err)) {
+      delete c;
+      return fail(nullptr, PBD_ESHAPE, "%s net: %s", which ? "student" : "teacher", err.c_str());
+    }
+  c->act.push_back(c->in);
+  for (int b = 0; b < c->B; ++b) {
+    const Shape t = c->net[0][b].shapes.back(), s = c->net[1][b].shapes.back();
+    // Sec. II-A: the pair (T_i, S_i) produces activations of one shape
+    if (t.c != s.c || t.h != s.h || t.w != s.w || t.c % 8) {
+      delete c;
+      return fail(nullptr, PBD_ESHAPE, "block %d: teacher and student outputs must agree in shape, channels %% 8 == 0", b + 1);
+    }
+    c->act.push_back(t);
+  }
+  if (opts->batch * (long)c->in.h * c->in.w > (1L << 30)) {
+    delete c;
+    return fail(nullptr, PBD_ESHAPE, "batch x H x W exceeds 2^30 pixels");
+  }
+  plan(c);
+  *out = c;
+  return PBD_OK;
+}
+
+void pbd_destroy(pbd_ctx* c) {
+  if (!c) return;
+  for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+const char* pbd_last_error(const pbd_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+int32_t pbd_num_blocks(const pbd_ctx* c) { return c ? c->B : 0; }
+size_t pbd_workspace_bytes(const pbd_ctx* c) { return c ? c->total : 0; }
+
+int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
+  if (!c) return PBD_EINVAL;
+  if (!dev_ws) return fail(c, PBD_ENOMEM_WS, "workspace pointer is null");
+  if (bytes < c->total) return fail(c, PBD_ENOMEM_WS, "workspace has %zu bytes, %zu needed", bytes, c->total);
+  if (reinterpret_cast<uintptr_t>(dev_ws) % kAlign) return fail(c, PBD_ENOMEM_WS, "workspace must be %zu-byte aligned", kAlign);
+  c->ws = static_cast<char*>(dev_ws);
+  c->stream = static_cast<hipStream_t>(hip_stream);
+  // parameters, optimiser state and statistics start at zero; the relay store too,
+  // so that padded channels never hold stale bits
+  HIP_TRY(c, hipMemsetAsync(c->ws, 0, c->r_tscr, c->stream));
+  c->bound = true;
+  c->relayed = false;
+  c->fold_dirty = true;
+  c->last_block = -1;
+  // BN identity: gamma = 1, running variance = 1
+  for (int net = 0; net < 2; ++net)
+    for (int b = 0; b < c->B; ++b) {
+      BlockPlan& bp = c->net[net][b];
+      for (size_t j = 0; j < bp.ops.size(); ++j) {
+        OpPlan& op = bp.ops[j];
+        if (op.d.type != OP_CBA) continue;
+        std::vector<float> ones(op.d.c_out, 1.f);
+        for (int slot : {PBD_GAMMA, PBD_RVAR}) {
+          TensorRef t;
+          int rc = locate(c, PBD_PARAM, net, b, (int)j, slot, t);
+          if (rc) return rc;
+          rc = upload(c, t, op, ones.data());
+          if (rc) return rc;
+        }
+      }
+      if (net == 1) {
+        if (!bp.ttable.empty())
+          HIP_TRY(c, hipMemcpyAsync(c->ws + bp.table, bp.ttable.data(), bp.ttable.size() * sizeof(TransposeEntry),
+                                    hipMemcpyHostToDevice, c->stream));
+        bp.dirty = true;
+      }
+    }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PBD_OK;
+}
+
+int pbd_load_param(pbd_ctx* c, int32_t net, int32_t b, int32_t op, int32_t slot, const float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  TensorRef t;
+  rc = locate(c, PBD_PARAM, net, b, op, slot, t);
+  if (rc) return rc;
+  if (n != t.logical) return fail(c, PBD_ESHAPE, "tensor has %zu elements, %zu given", t.logical, n);
+  rc = upload(c, t, *find_cba(c, net, b, op), host);
+  if (rc) return rc;
+  if (net == PBD_TEACHER) c->fold_dirty = true;
+  else c->net[1][b].dirty = true;
+  return PBD_OK;
+}
+
+int pbd_read_tensor(pbd_ctx* c, int32_t kind, int32_t net, int32_t b, int32_t opi, int32_t slot, float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  TensorRef t;
+  rc = locate(c, kind, net, b, opi, slot, t);
+  if (rc) return rc;
+  if (n != t.logical) return fail(c, PBD_ESHAPE, "tensor has %zu elements, %zu asked", t.logical, n);
+  const OpPlan& op = *find_cba(c, net, b, opi);
+  std::vector<float> phys(t.phys);
+  if (t.bf) {
+    std::vector<uint16_t> h16(t.phys);
+    HIP_TRY(c, hipMemcpyAsync(h16.data(), t.ptr, t.phys * 2, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (size_t e = 0; e < t.phys; ++e) phys[e] = bf2f(h16[e]);
+  } else {
+    HIP_TRY(c, hipMemcpyAsync(phys.data(), t.ptr, t.phys * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+  }
+  for (size_t e = 0; e < t.phys; ++e) {
+    const long h = t.weight ? weight_host_index(op, e) : ((long)e < (long)t.logical ? (long)e : -1);
+    if (h >= 0) host[h] = phys[e];
+  }
+  return PBD_OK;
+}
+
+int pbd_read_act(pbd_ctx* c, int32_t i, float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  if (i < 0 || i > c->B) return fail(c, PBD_EINVAL, "activation index %d outside 0..%d", i, c->B);
+  if (!c->relayed) return fail(c, PBD_ESTATE, "no teacher relay has run yet");
+  const Shape s = c->act[i];
+  if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "A_%d has %zu elements, %zu asked", i, (size_t)c->o.batch * s.c * s.h * s.w, n);
+  return download_act(c, c->ws + c->r_relay + c->act_off[i], s, host);
+}
+
+int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  if (b < 0 || b >= c->B) return fail(c, PBD_EINVAL, "block %d outside 0..%d", b, c->B - 1);
+  BlockPlan& bp = c->net[1][b];
+  if (v < 0 || v >= (int)bp.shapes.size()) return fail(c, PBD_EINVAL, "value %d outside 0..%zu", v, bp.shapes.size() - 1);
+  if (c->last_block != b) return fail(c, PBD_ESTATE, "block %d is not the block stepped last", b);
+  const Shape s = bp.shapes[v];
+  if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
+  const char* dev = v == 0 ? c->ws + c->r_relay + c->act_off[b] : c->ws + c->r_sscr + bp.val[v];
+  return download_act(c, dev, s, host);
+}
+
+int pbd_teacher_relay(pbd_ctx* c, const float* x_dev, pbd_tensor* A) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
+  rc = dispatch(c, [&](auto& e) { e.relay_all(x_dev); });
+  if (rc) return rc;
+  if (A) for (int i = 0; i <= c->B; ++i) fill_view(c, i, &A[i]);
+  return PBD_OK;
+}
+
+int pbd_student_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr, float* loss_dev) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (i < 1 || i > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", i, c->B);
+  if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
+  if (!loss_dev) return fail(c, PBD_EINVAL, "loss_dev is null");
+  if (!c->relayed) return fail(c, PBD_ESTATE, "no teacher relay has run yet");
+  if ((rc = check_view(c, A_prev, i - 1, "A_prev"))) return rc;
+  if ((rc = check_view(c, A_i, i, "A_i"))) return rc;
+  return dispatch(c, [&](auto& e) { e.student_block(i - 1, lr, loss_dev); });
+}
+
+int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
+  if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
+  if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
+  return dispatch(c, [&](auto& e) {
+    e.relay_all(x_dev);                                   // every T_i exactly once
+    for (int b = 0; b < c->B; ++b) e.student_block(b, lr, losses_dev + b);
+  });
+}
+
+int pbd_sync(pbd_ctx* c) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return after_launches(c);
+}
+
+int pbd_set_profile(pbd_ctx* c, int32_t on) {
+  if (!c) return PBD_EINVAL;
+  c->prof_on = on != 0;
+  return PBD_OK;
+}
+int pbd_reset_profile(pbd_ctx* c) {
+  if (!c) return PBD_EINVAL;
+  if (c->bound) HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->prof.clear();
+  return PBD_OK;
+}
+int pbd_get_profile(pbd_ctx* c, pbd_prof_entry* out, int32_t max) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  const int n = (int)c->prof.size();
+  for (int i = 0; i < n; ++i) {
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, c->ev[2 * i], c->ev[2 * i + 1]));
+    c->prof[i].ms = ms;
+    if (out && i < max) out[i] = c->prof[i];
+  }
+  return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,194 @@
+"""ctypes binding over libpbd.so: same names as include/pbd.h, argument
+marshalling only.  PyTorch supplies device memory and the stream; every step of
+the path runs in the library's HIP kernels.  There is no fallback: if the
+library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import workloads as W
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpbd.so")
+
+PBD_F32, PBD_BF16 = 0, 1
+PBD_TEACHER, PBD_STUDENT = 0, 1
+PBD_PARAM, PBD_GRAD, PBD_MOMENTUM = 0, 1, 2
+STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
+          -4: "PBD_ESTATE", -5: "PBD_EHIP"}
+
+SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
+           "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
+           "pbd_teacher_relay", "pbd_student_step", "pbd_distill_step", "pbd_sync",
+           "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
+
+
+class pbd_opts(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("precision", C.c_int32), ("momentum", C.c_float),
+                ("bn_eps", C.c_float), ("bn_momentum", C.c_float), ("force_direct", C.c_int32)]
+
+
+class pbd_tensor(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("n", C.c_int32), ("c", C.c_int32), ("h", C.c_int32),
+                ("w", C.c_int32), ("c_phys", C.c_int32), ("dtype", C.c_int32)]
+
+
+class pbd_prof_entry(C.Structure):
+    _fields_ = [("name", C.c_char * 32), ("ms", C.c_float), ("bytes", C.c_double),
+                ("flops", C.c_double), ("net", C.c_int32), ("block", C.c_int32), ("op", C.c_int32)]
+
+
+class PbdError(RuntimeError):
+    def __init__(self, code, msg=""):
+        super().__init__(f"{STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load libpbd.so; raises if it has not been built (python -m paper_2301_12443_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with "
+                                    "`python -m paper_2301_12443_amd.build`; there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        fp, ip, dp = C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)
+        L.pbd_create.argtypes = [ip, C.c_int32, dp, C.c_int32, C.POINTER(pbd_opts), C.POINTER(C.c_void_p)]
+        L.pbd_destroy.argtypes = [C.c_void_p]
+        L.pbd_destroy.restype = None
+        L.pbd_last_error.argtypes = [C.c_void_p]
+        L.pbd_last_error.restype = C.c_char_p
+        L.pbd_num_blocks.argtypes = [C.c_void_p]
+        L.pbd_workspace_bytes.argtypes = [C.c_void_p]
+        L.pbd_workspace_bytes.restype = C.c_size_t
+        L.pbd_bind.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.pbd_load_param.argtypes = [C.c_void_p] + [C.c_int32] * 4 + [fp, C.c_size_t]
+        L.pbd_read_tensor.argtypes = [C.c_void_p] + [C.c_int32] * 5 + [fp, C.c_size_t]
+        L.pbd_read_act.argtypes = [C.c_void_p, C.c_int32, fp, C.c_size_t]
+        L.pbd_read_value.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
+        L.pbd_teacher_relay.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pbd_tensor)]
+        L.pbd_student_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(pbd_tensor), C.POINTER(pbd_tensor),
+                                       C.c_float, C.c_void_p]
+        L.pbd_distill_step.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+        L.pbd_sync.argtypes = [C.c_void_p]
+        L.pbd_set_profile.argtypes = [C.c_void_p, C.c_int32]
+        L.pbd_reset_profile.argtypes = [C.c_void_p]
+        L.pbd_get_profile.argtypes = [C.c_void_p, C.POINTER(pbd_prof_entry), C.c_int32]
+        _lib = L
+    return _lib
+
+
+def _fp(a):
+    return a.ctypes.data_as(C.POINTER(C.c_float))
+
+
+class Distiller:
+    """A context for one workload.  `create` needs no GPU; `bind` and everything after do."""
+
+    def __init__(self, wl: W.Workload, batch: int | None = None, precision: str | None = None,
+                 force_direct: bool = False, bn_eps: float = 1e-5, bn_momentum: float = 0.1):
+        self.wl = wl
+        self.batch = wl.batch if batch is None else batch
+        self.precision = PBD_BF16 if (precision or wl.precision) == "bf16" else PBD_F32
+        self.B = wl.B
+        words, pool = W.pack(wl)
+        self._words, self._pool = words, pool
+        opts = pbd_opts(self.batch, self.precision, wl.momentum, bn_eps, bn_momentum, int(force_direct))
+        h = C.c_void_p()
+        rc = lib().pbd_create(words.ctypes.data_as(C.POINTER(C.c_int32)), words.size,
+                              pool.ctypes.data_as(C.POINTER(C.c_double)), pool.size, C.byref(opts), C.byref(h))
+        if rc != 0:
+            raise PbdError(rc, lib().pbd_last_error(None).decode())
+        self.h = h
+        self._ws = None
+        self.views = None
+        self.act_shapes = W.activation_shapes(wl)
+
+    def __del__(self):
+        if getattr(self, "h", None):
+            lib().pbd_destroy(self.h)
+            self.h = None
+
+    def _check(self, rc):
+        if rc < 0:
+            raise PbdError(rc, lib().pbd_last_error(self.h).decode())
+        return rc
+
+    def workspace_bytes(self) -> int:
+        return lib().pbd_workspace_bytes(self.h)
+
+    def bind(self, device="cuda:0", stream=None):
+        import torch
+        self.device = torch.device(device)
+        self._ws = torch.empty(self.workspace_bytes() + 256, dtype=torch.uint8, device=self.device)
+        base = (self._ws.data_ptr() + 255) // 256 * 256
+        self._stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        self._check(lib().pbd_bind(self.h, base, self.workspace_bytes(), self._stream.cuda_stream))
+        self.losses = torch.zeros(self.B, dtype=torch.float32, device=self.device)
+        return self
+
+    def load_params(self):
+        """Seeded parameters of both nets (He-normal weights, frozen teacher BN, identity student BN)."""
+        for net, b, j, slot, arr in W.iter_params(self.wl):
+            self.load_param(net, b, j, slot, arr)
+
+    def load_param(self, net, b, j, slot, arr):
+        a = np.ascontiguousarray(arr, dtype=np.float32).ravel()
+        self._check(lib().pbd_load_param(self.h, net, b, j, slot, _fp(a), a.size))
+
+    def read_tensor(self, kind, net, b, j, slot, shape):
+        out = np.empty(int(np.prod(shape)), dtype=np.float32)
+        self._check(lib().pbd_read_tensor(self.h, kind, net, b, j, slot, _fp(out), out.size))
+        return out.reshape(shape)
+
+    def read_act(self, i):
+        shape = (self.batch, *self.act_shapes[i])
+        out = np.empty(int(np.prod(shape)), dtype=np.float32)
+        self._check(lib().pbd_read_act(self.h, i, _fp(out), out.size))
+        return out.reshape(shape)
+
+    def read_value(self, b, v):
+        shape = (self.batch, *W.block_shapes(self.wl.student[b], self.act_shapes[b])[v])
+        out = np.empty(int(np.prod(shape)), dtype=np.float32)
+        self._check(lib().pbd_read_value(self.h, b, v, _fp(out), out.size))
+        return out.reshape(shape)
+
+    def teacher_relay(self, x_dev):
+        """x_dev: float32 NCHW CUDA tensor.  Returns the B+1 borrowed views A_0..A_B."""
+        assert x_dev.is_cuda and x_dev.dtype.is_floating_point and x_dev.is_contiguous()
+        views = (pbd_tensor * (self.B + 1))()
+        self._check(lib().pbd_teacher_relay(self.h, x_dev.data_ptr(), views))
+        self.views = views
+        return views
+
+    def student_step(self, i, lr, a_prev=None, a_i=None):
+        """Block i (1-based).  The loss lands in self.losses[i-1] on the device."""
+        a_prev = self.views[i - 1] if a_prev is None else a_prev
+        a_i = self.views[i] if a_i is None else a_i
+        self._check(lib().pbd_student_step(self.h, i, C.byref(a_prev), C.byref(a_i), lr,
+                                           self.losses.data_ptr() + 4 * (i - 1)))
+
+    def distill_step(self, x_dev, lr):
+        self._check(lib().pbd_distill_step(self.h, x_dev.data_ptr(), lr, self.losses.data_ptr()))
+
+    def sync(self):
+        self._check(lib().pbd_sync(self.h))
+
+    def set_profile(self, on: bool):
+        self._check(lib().pbd_set_profile(self.h, int(on)))
+
+    def reset_profile(self):
+        self._check(lib().pbd_reset_profile(self.h))
+
+    def get_profile(self):
+        n = self._check(lib().pbd_get_profile(self.h, None, 0))
+        buf = (pbd_prof_entry * max(n, 1))()
+        self._check(lib().pbd_get_profile(self.h, buf, n))
+        return [dict(name=e.name.decode(), ms=e.ms, bytes=e.bytes, flops=e.flops,
+                     net=e.net, block=e.block, op=e.op) for e in buf[:n]]

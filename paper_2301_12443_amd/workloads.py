@@ -216,24 +216,50 @@ def make_input(wl: Workload, batch: int | None = None, step: int = 0) -> np.ndar
     return _rng(wl, 7, step).standard_normal((n, *wl.in_shape), dtype=np.float32)
 
 
+def _is_linear_value(wl: Workload, net: int, b: int, v: int) -> bool:
+    """True when value v of block b comes out of a layer without a rectifier."""
+    if v == 0:
+        if b == 0:
+            return False                      # the image: plain He-normal first layer
+        last = wl.teacher[b - 1].ops[-1]      # A_{i-1} is the teacher's output for both nets
+        return last.type in (OP_ADD, OP_CBA) and last.act == ACT_NONE or last.type == OP_MIX
+    op = wl.net(net)[b].ops[v - 1]
+    if op.type == OP_POOL:
+        return _is_linear_value(wl, net, b, op.inputs[0])
+    return op.type == OP_MIX or op.act == ACT_NONE
+
+
+def _feeds_add(block: Block, j: int) -> bool:
+    return any(o.type == OP_ADD and (j + 1) in o.inputs for o in block.ops)
+
+
 def make_param(wl: Workload, net: int, b: int, j: int, slot: int,
                shape: Tuple[int, ...]) -> np.ndarray:
     """One parameter tensor (float32), regenerable on its own from the seed.
 
-    Conv weights: He-normal, std = sqrt(2 / fan_in).  Student BN starts at the
-    identity (gamma 1, beta 0, running mean 0, running var 1).  The frozen
-    teacher BN gets non-trivial values so that a wrong fold cannot hide:
-    gamma ~ U(0.5,1.5), beta ~ N(0,0.1^2), mean ~ N(0,0.1^2), var ~ U(0.5,1.5).
+    Conv weights: He-normal, std = sqrt(gain / fan_in) with gain 2 behind a rectifier and
+    gain 1 behind a linear output (linear bottleneck, residual sum, mix), which keeps
+    activations at unit scale through deep inverted-residual stacks the way a trained
+    network's statistics do.  Student BN starts at the identity (gamma 1, beta 0, running
+    mean 0, running var 1).  The frozen teacher BN gets non-trivial values so that a wrong
+    fold cannot hide: gamma ~ U(0.5,1.5) (halved on the last BN of a residual branch, as
+    trained residual networks have small branch gains), beta ~ N(0,0.1^2),
+    mean ~ N(0,0.1^2), var ~ U(0.5,1.5).
     """
     g = _rng(wl, net, b, j, slot)
+    block = wl.net(net)[b]
     if slot == P_WEIGHT:
         fan_in = shape[1] * shape[2] * shape[3]
+        gain = 1.0 if _is_linear_value(wl, net, b, block.ops[j].inputs[0]) else 2.0
         w = g.standard_normal(shape, dtype=np.float32)
-        return (w * np.float32(np.sqrt(2.0 / fan_in))).astype(np.float32)
+        return (w * np.float32(np.sqrt(gain / fan_in))).astype(np.float32)
     if net == NET_STUDENT:
         fill = {P_GAMMA: 1.0, P_BETA: 0.0, P_RMEAN: 0.0, P_RVAR: 1.0}[slot]
         return np.full(shape, fill, dtype=np.float32)
-    if slot in (P_GAMMA, P_RVAR):
+    if slot == P_GAMMA:
+        scale = 0.5 if (block.ops[j].act == ACT_NONE and _feeds_add(block, j)) else 1.0
+        return (scale * g.uniform(0.5, 1.5, shape)).astype(np.float32)
+    if slot == P_RVAR:
         return g.uniform(0.5, 1.5, shape).astype(np.float32)
     return (0.1 * g.standard_normal(shape)).astype(np.float32)
 

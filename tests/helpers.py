@@ -6,10 +6,10 @@ from oracle import pbd_oracle as orc
 from paper_2301_12443_amd import workloads as W
 
 
-def make_oracle(wl, batch=None, precision=64):
+def make_oracle(wl, batch=None, precision=64, storage=None):
     words, pool = W.pack(wl)
     o = orc.Oracle(words, pool, wl.batch if batch is None else batch, precision=precision,
-                   momentum=wl.momentum)
+                   momentum=wl.momentum, storage=storage)
     for net, b, j, slot, arr in W.iter_params(wl):
         o.set_param(net, b, j, slot, arr)
     return o
@@ -26,34 +26,87 @@ def max_rel(a, b):
 
 
 def pattern_workloads():
-    """Tiny instances of every op pattern the five configurations use."""
+    """Tiny instances of every op pattern the five configurations use (channel counts are
+    multiples of 8 past the input, as the device layout wants)."""
     out = []
-    # depthwise-separable + pool (VGG student), dense 3x3 + pool teacher
+    # depthwise-separable + pool (VGG student) on a 3-channel input, dense 3x3 + pool teacher
     t, s = W.Block(), W.Block()
-    v = t.cba(0, 6, 3); v = t.cba(v, 6, 3); t.pool(v, 2, 2)
-    v = s.cba(0, 4, 3, groups=4); v = s.cba(v, 6, 1)
-    v = s.cba(v, 6, 3, groups=6); v = s.cba(v, 6, 1); s.pool(v, 2, 2)
-    out.append(W.Workload("p_dsconv", 3, (4, 8, 8), [t], [s], "f32", lr=0.05))
+    v = t.cba(0, 8, 3); v = t.cba(v, 8, 3); t.pool(v, 2, 2)
+    v = s.cba(0, 3, 3, groups=3); v = s.cba(v, 8, 1)
+    v = s.cba(v, 8, 3, groups=8); v = s.cba(v, 8, 1); s.pool(v, 2, 2)
+    out.append(W.Workload("p_dsconv", 3, (3, 8, 8), [t], [s], "f32", lr=0.05))
     # MBConv k3 teacher with residual, MBConv k5/k7 stride 2 + stride-1 residual student
     t, s = W.Block(), W.Block()
-    v = W._mbconv(t, 0, 4, 6, 3, 6, 2); W._mbconv(t, v, 6, 6, 3, 6, 1)
-    v = W._mbconv(s, 0, 4, 6, 5, 4, 2); W._mbconv(s, v, 6, 6, 7, 3, 1)
-    out.append(W.Workload("p_mbconv", 3, (4, 9, 9), [t], [s], "f32", lr=0.05))
+    v = W._mbconv(t, 0, 8, 16, 3, 6, 2); W._mbconv(t, v, 16, 16, 3, 6, 1)
+    v = W._mbconv(s, 0, 8, 16, 5, 4, 2); W._mbconv(s, v, 16, 16, 7, 3, 1)
+    out.append(W.Workload("p_mbconv", 3, (8, 9, 9), [t], [s], "f32", lr=0.05))
     # 7x7 stem + 3x3 s2 p1 pool + bottlenecks with and without projection
     t, s = W.Block(), W.Block()
-    for blk, inner in ((t, 4), (s, 6)):
+    for blk, inner in ((t, 8), (s, 16)):
         v = blk.cba(0, 8, 7, 2); v = blk.pool(v, 3, 2, 1)
         v = W._bottleneck(blk, v, 8, inner, 16, 2)
         W._bottleneck(blk, v, 16, inner, 16, 1)
     out.append(W.Workload("p_bottleneck", 2, (3, 20, 20), [t], [s], "f32", lr=0.05))
     # supernet layer: mix of candidates, then a mixed layer with identity skip
     t, s = W.Block(), W.Block()
-    v = W._mbconv(t, 0, 4, 6, 3, 6, 2); W._mbconv(t, v, 6, 6, 3, 6, 1)
+    v = W._mbconv(t, 0, 8, 16, 3, 6, 2); W._mbconv(t, v, 16, 16, 3, 6, 1)
     cands = ((3, 3), (5, 6), (7, 3))
     p = (0.5, 0.3, 0.2)
-    outs = [W._mbconv(s, 0, 4, 6, k, e, 2, residual=False) for k, e in cands]
+    outs = [W._mbconv(s, 0, 8, 16, k, e, 2, residual=False) for k, e in cands]
     v = s.mix(outs, p)
-    outs = [W._mbconv(s, v, 6, 6, k, e, 1, residual=False) for k, e in cands]
+    outs = [W._mbconv(s, v, 16, 16, k, e, 1, residual=False) for k, e in cands]
     m = s.mix(outs, p); s.add(v, m)
-    out.append(W.Workload("p_supernet", 2, (4, 8, 8), [t], [s], "f32", lr=0.05))
+    out.append(W.Workload("p_supernet", 2, (8, 8, 8), [t], [s], "f32", lr=0.05))
+    return out
+
+
+def layer_workloads():
+    """Two-to-four-op student blocks at the layer shapes of the five configurations
+    (channel counts, kernel sizes, strides, ragged row and column counts), shallow enough that
+    bf16 storage noise is not amplified by depth.  Returned as (workload, batch) pairs."""
+    out = []
+
+    def wl(name, in_shape, t, s, batch):
+        out.append((W.Workload(name, batch, in_shape, [t], [s], "bf16", lr=0.05), batch))
+
+    # dense 3x3, K = 576, 128 full row tiles (VGG teacher shape as a student layer)
+    t, s = W.Block(), W.Block()
+    t.cba(0, 64, 3)
+    v = s.cba(0, 64, 1); s.cba(v, 64, 3)
+    wl("l_dense3x3", (64, 16, 16), t, s, 64)
+    # ragged rows (980) and columns (40, 72), stride-2 3x3 with backward-data
+    t, s = W.Block(), W.Block()
+    t.cba(0, 72, 3, 2)
+    v = s.cba(0, 40, 1); s.cba(v, 72, 3, 2)
+    wl("l_ragged_s2", (24, 14, 14), t, s, 5)
+    # depthwise-separable chain with pooling (VGG student)
+    t, s = W.Block(), W.Block()
+    v = t.cba(0, 128, 3); t.pool(v, 2, 2)
+    v = s.cba(0, 64, 3, groups=64); v = s.cba(v, 128, 1)
+    v = s.cba(v, 128, 3, groups=128); v = s.cba(v, 128, 1); s.pool(v, 2, 2)
+    wl("l_dsconv", (64, 16, 16), t, s, 64)
+    # 3-channel input: 7x7 stride-2 stem, 3x3 s2 p1 pool, 1x1 (ResNet stem)
+    t, s = W.Block(), W.Block()
+    v = t.cba(0, 64, 7, 2); t.pool(v, 3, 2, 1)
+    v = s.cba(0, 64, 7, 2); v = s.pool(v, 3, 2, 1); s.cba(v, 64, 1)
+    wl("l_stem7x7", (3, 64, 64), t, s, 8)
+    # MBConv k5 stride 2 (MobileNet student) and k7 stride 1 with residual (supernet candidate)
+    t, s = W.Block(), W.Block()
+    W._mbconv(t, 0, 24, 32, 3, 6, 2)
+    W._mbconv(s, 0, 24, 32, 5, 4, 2)
+    wl("l_mbconv_k5s2", (24, 28, 28), t, s, 16)
+    t, s = W.Block(), W.Block()
+    W._mbconv(t, 0, 32, 32, 3, 6, 1)
+    W._mbconv(s, 0, 32, 32, 7, 3, 1)
+    wl("l_mbconv_k7res", (32, 14, 14), t, s, 16)
+    # wide 1x1 layers, small row count (ResNet stage 4 shape)
+    t, s = W.Block(), W.Block()
+    t.cba(0, 1024, 1)
+    v = s.cba(0, 384, 1); s.cba(v, 1024, 1, act=W.ACT_NONE)
+    wl("l_wide1x1", (512, 7, 7), t, s, 32)
+    # deep reduction: 3x3 over 384 channels (K = 3456) with backward-data
+    t, s = W.Block(), W.Block()
+    t.cba(0, 384, 3)
+    v = s.cba(0, 384, 1); s.cba(v, 384, 3)
+    wl("l_deepK3x3", (256, 7, 7), t, s, 32)
     return out

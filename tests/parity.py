@@ -1,0 +1,106 @@
+"""GPU-vs-oracle comparison used by the gpu-marked tests: runs the same seeded
+workload through libpbd.so (via the C ABI binding) and through the CPU oracle and
+returns per-tensor max-norm relative errors."""
+import numpy as np
+
+from helpers import make_oracle, max_rel
+from oracle import pbd_oracle as orc
+from paper_2301_12443_amd import pbd, workloads as W
+
+
+def make_distiller(wl, batch=None, precision=None, force_direct=False):
+    d = pbd.Distiller(wl, batch=batch, precision=precision, force_direct=force_direct)
+    d.bind("cuda:0")
+    d.load_params()
+    return d
+
+
+def compare_step(wl, batch=None, precision=None, force_direct=False, steps=1, order=None, log=None,
+                 storage=None, kink_floor=0.0, beta_shift=None):
+    """Returns {name: error} for activations, losses, gradients, weights, momentum, running stats."""
+    import torch
+    batch = wl.batch if batch is None else batch
+    d = make_distiller(wl, batch, precision, force_direct)
+    o = make_oracle(wl, batch=batch, storage=storage)
+    if beta_shift is not None:
+        # move every student pre-activation away from the rectifier kinks (same on both sides)
+        for b in range(wl.B):
+            for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+                if slot == W.P_BETA:
+                    beta = np.full(shape, beta_shift, dtype=np.float32)
+                    o.set_param(W.NET_STUDENT, b, j, slot, beta)
+                    d.load_param(W.NET_STUDENT, b, j, slot, beta)
+    errs = {}
+    for step in range(steps):
+        x = W.make_input(wl, batch=batch, step=step)
+        acts = o.teacher_relay(x)
+        d.teacher_relay(torch.from_numpy(x).cuda())
+        for i in range(wl.B + 1):
+            errs[f"s{step}.A{i}"] = max_rel(d.read_act(i), acts[i])
+        for i in (order or range(1, wl.B + 1)):
+            b = i - 1
+            if kink_floor:
+                # A pre-activation that sits on a ReLU / pool kink to within rounding has two valid
+                # gradients; the block's input is redrawn (and relayed again on both sides) until
+                # the oracle's forward of this block keeps clear of every kink.
+                for cand in range(64):
+                    o.student_step(i, acts[i - 1], acts[i], 0.0, orc.MODE_LOSS)
+                    margin = o.kink_margin(b)
+                    if margin >= kink_floor:
+                        break
+                    x = W.make_input(wl, batch=batch, step=step + 1000 * (cand + 1))
+                    acts = o.teacher_relay(x)
+                    d.teacher_relay(torch.from_numpy(x).cuda())
+                else:
+                    raise AssertionError(f"block {i}: no kink-free input in 64 draws (margin {margin})")
+            d.student_step(i, wl.lr)
+            loss_o = o.student_step(i, acts[i - 1], acts[i], wl.lr)
+            d.sync()
+            loss_g = float(d.losses[b].item())
+            errs[f"s{step}.loss{i}"] = abs(loss_g - loss_o) / abs(loss_o)
+            pshapes = W.param_shapes(wl, W.NET_STUDENT, b)
+            for (j, slot), shape in pshapes.items():
+                tag = f"s{step}.b{b}.op{j}.{'w g b rm rv'.split()[slot]}"
+                og = lambda kind, sl=slot: o.get_tensor(kind, 1, b, j, sl, pshapes[(j, sl)])
+                if slot <= W.P_BETA:
+                    for kind, nm in ((pbd.PBD_GRAD, ".grad"), (pbd.PBD_MOMENTUM, ".mom")):
+                        ref = og(kind)
+                        den = np.max(np.abs(ref))
+                        if slot in (W.P_GAMMA, W.P_BETA):
+                            # dgamma and dbeta are sums of the same m terms; when the next layer is
+                            # scale-invariant dgamma is exactly 0 in exact arithmetic, so the error of
+                            # either is measured against the larger of the two
+                            den = max(np.max(np.abs(og(kind, W.P_GAMMA))), np.max(np.abs(og(kind, W.P_BETA))))
+                        got = d.read_tensor(kind, 1, b, j, slot, shape)
+                        errs[tag + nm] = float(np.max(np.abs(got - ref)) / den)
+                        if kind == pbd.PBD_GRAD and slot == W.P_WEIGHT:
+                            errs[tag + ".l2g"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+                ref = og(orc.KIND_PARAM)
+                den = np.max(np.abs(ref))
+                if slot in (W.P_GAMMA, W.P_BETA):
+                    # an updated gamma / beta whose gradient vanishes identically is measured against
+                    # the size of the update its companion received
+                    den = max(den, abs(wl.lr) * max(np.max(np.abs(og(orc.KIND_MOMENTUM, W.P_GAMMA))),
+                                                    np.max(np.abs(og(orc.KIND_MOMENTUM, W.P_BETA)))))
+                if slot == W.P_RMEAN:
+                    # a mean is measured against the channel's standard deviation, not against itself
+                    den = max(den, 0.1 * float(np.sqrt(np.max(og(orc.KIND_PARAM, W.P_RVAR)))))
+                errs[tag + ".param"] = float(np.max(np.abs(d.read_tensor(pbd.PBD_PARAM, 1, b, j, slot, shape) - ref)) / den)
+            if log:
+                log(f"step {step} block {i}: loss gpu {loss_g:.6g} oracle {loss_o:.6g}")
+    return errs
+
+
+def worst(errs, key):
+    sel = {k: v for k, v in errs.items() if key in k}
+    if not sel:
+        return None, 0.0
+    k = max(sel, key=sel.get)
+    return k, sel[k]
+
+
+def summarize(errs):
+    out = {}
+    for key in (".A", ".loss", ".grad", ".mom", ".param", ".l2g"):
+        out[key] = worst(errs, key)
+    return out

@@ -1,0 +1,139 @@
+"""GPU parity: libpbd.so (through the C ABI binding) against the CPU oracle on the same
+seeded inputs.
+
+Tolerances (max-norm relative error per tensor, max|a-b| / max|b|):
+  * float32 path vs the fp64 oracle: 1e-4 on activations, losses, gradients, momentum,
+    updated parameters and running statistics;
+  * bf16 path: 2e-2.  Losses and relayed activations are compared with the plain fp64
+    oracle.  Gradients are compared with the oracle run with bfloat16 storage rounding, so
+    that ReLU masks, pool winners and bf16 codes are decided in the kernel's precision on both
+    sides: a gradient summed over a kinked network is discontinuous in those decisions and
+    the plain fp64 value is several percent away from ANY bf16-storage evaluation (see
+    test_bf16_storage_conditioning in test_oracle_step.py for the oracle-only measurement).
+"""
+import numpy as np
+import pytest
+
+import parity
+from helpers import layer_workloads, make_oracle, max_rel, pattern_workloads
+from paper_2301_12443_amd import pbd, workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+
+
+KINK_FLOOR = 2e-6   # float32 runs: a pre-activation closer than this to a kink may fall either side
+
+
+def _assert_all(errs, tol, keys=None):
+    bad = {k: v for k, v in errs.items() if not (v < tol) and (keys is None or any(t in k for t in keys))}
+    assert not bad, dict(list(sorted(bad.items(), key=lambda kv: -kv[1]))[:8])
+
+
+SMALL = [W.tiny_cnn()] + pattern_workloads()
+
+
+@pytest.mark.parametrize("wl", SMALL, ids=[w.name for w in SMALL])
+def test_f32_path_matches_fp64_oracle(wl):
+    """Three consecutive steps (momentum and running statistics in play), every tensor."""
+    errs = parity.compare_step(wl, precision="f32", steps=3, kink_floor=KINK_FLOOR)
+    _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
+
+
+def test_f32_block_order_is_irrelevant():
+    wl = W.tiny_cnn()
+    a = parity.compare_step(wl, precision="f32", steps=1, order=(3, 1, 4, 2), kink_floor=KINK_FLOOR)
+    _assert_all({k: v for k, v in a.items() if not k.endswith(".l2g")}, TOL_F32)
+
+
+BF16_CASES = [(W.tiny_cnn(), None)] + [(w, None) for w in pattern_workloads()[:3]] + layer_workloads()
+
+
+@pytest.mark.parametrize("wl,batch", BF16_CASES, ids=[w.name for w, _ in BF16_CASES])
+@pytest.mark.parametrize("direct", [False, True], ids=["mfma", "direct"])
+def test_bf16_path_matches_oracle(wl, batch, direct):
+    plain = parity.compare_step(wl, batch=batch, precision="bf16", force_direct=direct, steps=1)
+    _assert_all(plain, TOL_BF16, keys=(".A", ".loss"))
+    rounded = parity.compare_step(wl, batch=batch, precision="bf16", force_direct=direct, steps=1, storage="bf16")
+    _assert_all(rounded, TOL_BF16, keys=(".loss", ".grad", ".mom", ".param", ".l2g"))
+
+
+def _gradient_deviation(wl, batch, get_a, get_b):
+    """Per block: median relative L2 deviation of the weight gradients of two evaluations."""
+    out = []
+    for b in range(wl.B):
+        devs = []
+        for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+            if slot == W.P_WEIGHT:
+                ga, gb = get_a(b, j, shape), get_b(b, j, shape)
+                devs.append(np.linalg.norm(ga - gb) / np.linalg.norm(gb))
+        out.append(float(np.median(devs)))
+    return out
+
+
+def _full_config_check(wl, batch):
+    """bf16 MFMA path at a configuration's real graph: activations and losses against the plain
+    fp64 oracle (losses 2e-2, activations 4e-2) and the bf16-storage oracle (2e-2); weight gradients against the bf16-storage oracle, bounded by the larger of
+    2e-2 and 1.5x the deviation the storage rounding itself causes (oracle bf16 vs oracle fp64)."""
+    import torch
+    d = parity.make_distiller(wl, batch, "bf16")
+    o64, o16 = make_oracle(wl, batch), make_oracle(wl, batch, storage="bf16")
+    x = W.make_input(wl, batch=batch)
+    d.distill_step(torch.from_numpy(x).cuda(), wl.lr)
+    d.sync()
+    print(f"[{wl.name} N={batch}] gpu step done, oracle fp64 ...", flush=True)
+    l64 = o64.relay_step(x, wl.lr)
+    print(f"[{wl.name}] oracle bf16-storage ...", flush=True)
+    l16 = o16.relay_step(x, wl.lr)
+    print(f"[{wl.name}] oracle teacher ...", flush=True)
+    acts, acts16 = o64.teacher_relay(x), o16.teacher_relay(x)
+    for i in range(wl.B + 1):
+        got = d.read_act(i)
+        assert max_rel(got, acts16[i]) < TOL_BF16, f"A_{i} vs bf16-storage oracle"
+        # plain fp64: half-ulp bf16 storage noise (2^-9 per stored layer) grows like sqrt(depth);
+        # the 52-layer MobileNetV2 teacher reaches ~2.5e-2 at its last blocks
+        assert max_rel(got, acts[i]) < 2 * TOL_BF16, f"A_{i} vs fp64 oracle"
+    lg = d.losses.cpu().numpy()
+    assert np.all(np.abs(lg - l64) / l64 < TOL_BF16), (lg, l64)
+    gpu = lambda b, j, s: d.read_tensor(pbd.PBD_GRAD, 1, b, j, W.P_WEIGHT, s)
+    g64 = lambda b, j, s: o64.get_tensor(1, 1, b, j, W.P_WEIGHT, s)
+    g16 = lambda b, j, s: o16.get_tensor(1, 1, b, j, W.P_WEIGHT, s)
+    noise = _gradient_deviation(wl, batch, g16, g64)
+    dev = _gradient_deviation(wl, batch, gpu, g16)
+    print(f"[{wl.name}] gradient deviation gpu-vs-oracle(bf16) {np.round(dev, 4)}; storage noise {np.round(noise, 4)}", flush=True)
+    for b in range(wl.B):
+        assert dev[b] < max(TOL_BF16, 1.5 * noise[b]), (b, dev, noise)
+    return dev, noise
+
+
+def test_config2_vgg16_full_batch():
+    _full_config_check(W.vgg16_dsconv(), 256)
+
+
+@pytest.mark.parametrize("name,batch,hw", [("mbv2_mbconv_k5e4", 4, 224), ("mbv2_supernet", 2, 160),
+                                            ("resnet50_x1.5", 2, 160)])
+def test_configs_3_to_5_reduced_batch_bf16(name, batch, hw):
+    """Same graphs as the full configurations, smaller batch (and image) so that the direct-loop
+    oracle finishes; BN statistics depend on the batch, so both sides use the reduced one."""
+    _full_config_check(W.CONFIGS[name](batch=batch, hw=hw), batch)
+
+
+@pytest.mark.parametrize("name,batch,hw,shift", [("vgg16_dsconv", 4, 32, 6.0), ("mbv2_mbconv_k5e4", 4, 96, 3.0),
+                                                  ("mbv2_supernet", 2, 64, 3.0), ("resnet50_x1.5", 4, 64, 6.0)])
+def test_configs_2_to_5_graphs_in_f32(name, batch, hw, shift):
+    """Every op of every block of the real graphs, float32 kernels against the fp64 oracle: pins the
+    executor (joins, gradient accumulation, skipped backward-data, update) on the full DAGs.
+
+    A block of these graphs holds ~10^6 rectified elements, so at the default beta = 0 some element
+    always sits within float32 rounding of a ReLU kink, where the gradient has two valid values and
+    one flip moves every gradient upstream by percents.  The student's beta is therefore set to
+    `shift` on both sides (pre-activations ~ N(shift, 1), inside the linear part of ReLU / ReLU6),
+    which keeps the comparison elementwise; the kinks themselves are covered at beta = 0 by the
+    small workloads above, whose inputs are drawn clear of every kink."""
+    wl = W.CONFIGS[name](batch=batch, hw=hw, precision="f32")
+    errs = parity.compare_step(wl, batch=batch, precision="f32", steps=1, beta_shift=shift)
+    # the last blocks normalise over as few as 16 samples per channel at these batch sizes and
+    # BN backward amplifies float32 rounding accordingly: 5e-4 here, 1e-4 on the tiny config above
+    _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, 5 * TOL_F32)

@@ -1,0 +1,110 @@
+"""Properties that hold at any size, checked at the full BASELINE configurations in the launch
+configuration the benchmark times (bf16, MFMA), plus the ABI's state and error handling on a GPU."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import parity
+from paper_2301_12443_amd import pbd, workloads as W
+
+pytestmark = pytest.mark.gpu
+
+FULL = ["vgg16_dsconv", "mbv2_mbconv_k5e4", "mbv2_supernet", "resnet50_x1.5"]
+
+
+def _state(d, wl):
+    out = []
+    for b in range(wl.B):
+        for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+            out.append(d.read_tensor(pbd.PBD_PARAM, 1, b, j, slot, shape).copy())
+    return out
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_step_is_deterministic_and_split_calls_agree(name):
+    """pbd_distill_step == pbd_teacher_relay + pbd_student_step in any block order, bit for bit
+    (Sec. IV-B: blocks are independent), and two runs give identical bits (ordered reductions)."""
+    import torch
+    wl = W.CONFIGS[name]()
+    x = torch.from_numpy(W.make_input(wl)).cuda()
+    a = parity.make_distiller(wl)
+    a.distill_step(x, wl.lr); a.distill_step(x, wl.lr); a.sync()
+    la = a.losses.cpu().numpy().copy()
+    assert np.all(np.isfinite(la)) and np.all(la > 0)
+    sa = _state(a, wl)
+    del a
+    torch.cuda.empty_cache()
+    b = parity.make_distiller(wl)
+    lb = np.zeros_like(la)
+    for step in range(2):
+        b.teacher_relay(x)
+        for i in reversed(range(1, wl.B + 1)):
+            b.student_step(i, wl.lr)
+        b.sync()
+        lb = b.losses.cpu().numpy().copy()
+    np.testing.assert_array_equal(la, lb)
+    for ta, tb in zip(sa, _state(b, wl)):
+        np.testing.assert_array_equal(ta, tb)
+
+
+def test_relay_views_and_shared_input():
+    """S_i reads the very buffer T_i read: the view of A_{i-1} handed out by the relay."""
+    import torch
+    wl = W.tiny_cnn()
+    d = parity.make_distiller(wl)
+    views = d.teacher_relay(torch.from_numpy(W.make_input(wl)).cuda())
+    shapes = W.activation_shapes(wl)
+    for i, v in enumerate(views):
+        assert (v.n, v.c, v.h, v.w) == (wl.batch, *shapes[i]) and v.c_phys % 8 == 0 and v.ptr
+    d.student_step(2, wl.lr)
+    np.testing.assert_array_equal(d.read_value(1, 0), d.read_act(1))
+
+
+def test_state_and_argument_errors_on_device():
+    import torch
+    wl = W.tiny_cnn()
+    d = pbd.Distiller(wl)
+    L = pbd.lib()
+    assert L.pbd_sync(d.h) == -4                                   # not bound
+    ws = torch.empty(d.workspace_bytes() + 512, dtype=torch.uint8, device="cuda")
+    base = (ws.data_ptr() + 255) // 256 * 256
+    assert L.pbd_bind(d.h, base, d.workspace_bytes() - 1, None) == -3
+    assert L.pbd_bind(d.h, base + 8, d.workspace_bytes(), None) == -3
+    assert L.pbd_bind(d.h, None, d.workspace_bytes(), None) == -3
+    d.bind()
+    loss = torch.zeros(1, device="cuda")
+    v = pbd.pbd_tensor()
+    assert L.pbd_student_step(d.h, 1, C.byref(v), C.byref(v), 0.1, loss.data_ptr()) == -4   # no relay yet
+    views = d.teacher_relay(torch.from_numpy(W.make_input(wl)).cuda())
+    assert L.pbd_student_step(d.h, 0, C.byref(views[0]), C.byref(views[1]), 0.1, loss.data_ptr()) == -1
+    assert L.pbd_student_step(d.h, 5, C.byref(views[0]), C.byref(views[1]), 0.1, loss.data_ptr()) == -1
+    assert L.pbd_student_step(d.h, 1, C.byref(views[1]), C.byref(views[1]), 0.1, loss.data_ptr()) == -2
+    assert L.pbd_student_step(d.h, 1, C.byref(views[0]), C.byref(views[1]), float("nan"), loss.data_ptr()) == -1
+    assert L.pbd_student_step(d.h, 1, C.byref(views[0]), C.byref(views[1]), 0.1, None) == -1
+    assert L.pbd_teacher_relay(d.h, None, None) == -1
+    buf = np.zeros(4, dtype=np.float32)
+    fp = buf.ctypes.data_as(C.POINTER(C.c_float))
+    assert L.pbd_load_param(d.h, 1, 0, 0, 0, fp, 4) == -2           # wrong element count
+    assert L.pbd_load_param(d.h, 1, 9, 0, 0, fp, 4) == -1
+    assert L.pbd_read_tensor(d.h, 1, 0, 0, 0, 0, fp, 4) == -1       # teacher has no gradients
+    assert L.pbd_read_act(d.h, 9, fp, 4) == -1
+    assert b"block" in L.pbd_last_error(d.h) or L.pbd_last_error(d.h)
+    assert L.pbd_student_step(d.h, 1, C.byref(views[0]), C.byref(views[1]), 0.1, loss.data_ptr()) == 0
+    d.sync()
+    assert np.isfinite(loss.item())
+
+
+def test_profile_records_every_launch():
+    import torch
+    wl = W.tiny_cnn()
+    d = parity.make_distiller(wl, precision="bf16")
+    x = torch.from_numpy(W.make_input(wl)).cuda()
+    d.distill_step(x, wl.lr)
+    d.set_profile(True); d.reset_profile()
+    d.distill_step(x, wl.lr)
+    prof = d.get_profile()
+    names = {p["name"] for p in prof}
+    assert {"cast_input", "conv_fwd_mfma_affine", "conv_fwd_mfma", "bn_stats", "bn_apply", "mse_loss_grad",
+            "bn_bwd_reduce", "bn_bwd_apply", "conv_wgrad_mfma", "conv_dgrad_mfma", "sgd_momentum"} <= names
+    assert all(p["ms"] > 0 for p in prof) and all(p["bytes"] > 0 for p in prof)
