@@ -133,9 +133,11 @@ struct IgemmArgs {
   int R, S, stride, pad;
   int M;      // N*HO*WO
   int Kred;   // R*S*CA
+  int ksteps_per_split;  // reduction steps of IG_BK handled by one blockIdx.z (split-K)
 };
 
-enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2 };
+// EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
+enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 
 constexpr int IG_BM = 128, IG_BK = 32, IG_PITCH = IG_BK + 8;
 
@@ -171,8 +173,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     rn[i] = t / g.HO;
   }
   // reduction position of this thread's chunk: kk = rs*CA + c
-  int c = chunk * 8, rs = 0;
-  while (c >= g.CA) { c -= g.CA; ++rs; }
+  const int kt0 = blockIdx.z * g.ksteps_per_split;
+  int rs = (kt0 * IG_BK + chunk * 8) / g.CA;
+  int c = kt0 * IG_BK + chunk * 8 - rs * g.CA;
 
   uint4 areg[2], breg[B_LOADS];
   auto load_tile = [&](int kt) {
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk = (g.Kred + IG_BK - 1) / IG_BK;
+  const int nk = min(g.ksteps_per_split, (g.Kred + IG_BK - 1) / IG_BK - kt0);
   load_tile(0);
   store_tile(0);
   __syncthreads();
@@ -268,11 +271,43 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
         const int row = m0 + wm * TM * 32 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         if (row >= g.M) continue;
         float o = acc[i][j][v];
+        if (EPI == EPI_PARTIAL) {
+          reinterpret_cast<float*>(Out)[((long)blockIdx.z * g.M + row) * g.NC + col] = o;
+          continue;
+        }
         bf16_t* dst = Out + (long)row * g.NC + col;
         if (EPI == EPI_AFFINE_ACT) o = apply_act(fmaf(o, ea, eb), act);
         if (EPI == EPI_ACCUM) o += (float)*dst;
         *dst = (bf16_t)o;
       }
+  }
+}
+
+// Second stage of a split-K launch: out = epilogue(sum_s part[s]) in split order.
+__global__ void splitk_epilogue_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
+                                       const float* __restrict__ ep_a, const float* __restrict__ ep_b,
+                                       int act, int epi, long nvec, int ncv, int splits) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int c0 = (int)(i % ncv) * 8;
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int s = 0; s < splits; ++s) {
+      float v[8];
+      IO<float>::ld(part + ((long)s * nvec + i) * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+    if (epi == EPI_AFFINE_ACT) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = apply_act(fmaf(acc[e], ep_a[c0 + e], ep_b[c0 + e]), act);
+    } else if (epi == EPI_ACCUM) {
+      float v[8];
+      IO<bf16_t>::ld(out + i * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] += v[e];
+    }
+    IO<bf16_t>::st(out + i * 8, acc);
   }
 }
 

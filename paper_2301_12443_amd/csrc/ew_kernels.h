@@ -99,23 +99,6 @@ __global__ void bn_fold_kernel(const float* gamma, const float* beta, const floa
   b[c] = beta[c] - rmean[c] * s;
 }
 
-// training-mode BN + activation:  z = act(gamma * ((y - mean) * invstd) + beta)
-template <class T>
-__global__ void bn_apply_kernel(const T* __restrict__ y, T* __restrict__ z,
-                                const float* __restrict__ mean, const float* __restrict__ invstd,
-                                const float* __restrict__ gamma, const float* __restrict__ beta,
-                                long nvec, int ncv, int act) {
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
-    const int c0 = (int)(i % ncv) * 8;
-    float v[8];
-    IO<T>::ld(y + i * 8, v);
-#pragma unroll
-    for (int k = 0; k < 8; ++k)
-      v[k] = apply_act(fmaf(gamma[c0 + k], (v[k] - mean[c0 + k]) * invstd[c0 + k], beta[c0 + k]), act);
-    IO<T>::st(z + i * 8, v);
-  }
-}
-
 // ---------------------------------------------------------------------------
 // per-channel column reductions over the M = N*H*W rows of an NHWC matrix.
 // Block = 256 threads = cvl channel-vector lanes x (256/cvl) row lanes; grid =
@@ -148,6 +131,48 @@ __device__ __forceinline__ void block_col_reduce(float (&acc)[NV], float* smem, 
     }
   }
   __syncthreads();
+}
+
+// training-mode BN + activation:  z = act((y - mean) * (gamma*invstd) + beta).
+// Column-grid launch: a thread keeps its 8 channels' coefficients in registers and streams rows.
+template <class T>
+__global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, T* __restrict__ z,
+                                                       const float* __restrict__ mean,
+                                                       const float* __restrict__ invstd,
+                                                       const float* __restrict__ gamma,
+                                                       const float* __restrict__ beta, long M, int Cp,
+                                                       int act, ColGrid g) {
+  const int ncv = Cp / 8;
+  const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
+  const int cv = blockIdx.x * g.cvl + cv_lane;
+  if (cv >= ncv) return;
+  const long r0 = blockIdx.y * g.rows_per_chunk;
+  const long r1 = min(M, r0 + g.rows_per_chunk);
+  float mu[8], a[8], b[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int c = cv * 8 + k;
+    mu[k] = mean[c]; a[k] = gamma[c] * invstd[c]; b[k] = beta[c];
+  }
+  long r = r0 + row_lane;
+  for (; r + 3 * rl < r1; r += 4 * rl) {
+    float v[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[u][k] = apply_act(fmaf(v[u][k] - mu[k], a[k], b[k]), act);
+      IO<T>::st(z + ((r + u * rl) * ncv + cv) * 8, v[u]);
+    }
+  }
+  for (; r < r1; r += rl) {
+    float v[8];
+    IO<T>::ld(y + (r * ncv + cv) * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = apply_act(fmaf(v[k] - mu[k], a[k], b[k]), act);
+    IO<T>::st(z + (r * ncv + cv) * 8, v);
+  }
 }
 
 // part[chunk][0][c] = sum (y - piv), part[chunk][1][c] = sum (y - piv)^2 with the pivot
@@ -241,7 +266,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         const float xh = (v[k] - mv[k]) * iv[k];
-        const float dp = act_pass(fmaf(av[k], xh, bv[k]), act) ? d[k] : 0.f;
+        const float dp = act_pass(fmaf(v[k] - mv[k], av[k] * iv[k], bv[k]), act) ? d[k] : 0.f;
         acc[k] += dp;
         acc[8 + k] = fmaf(dp, xh, acc[8 + k]);
       }
@@ -274,26 +299,55 @@ __global__ void bn_bwd_finalize_kernel(const float* __restrict__ part, int chunk
   k3[c] = (float)(sg / m);
 }
 
-// stage 3: gradient w.r.t. the convolution output, written over dz in place
+// stage 3: gradient w.r.t. the convolution output, written over dz in place (column-grid launch)
 template <class T>
-__global__ void bn_bwd_apply_kernel(T* __restrict__ dz, const T* __restrict__ y,
-                                    const float* __restrict__ gamma, const float* __restrict__ beta,
-                                    const float* __restrict__ mean, const float* __restrict__ invstd,
-                                    const float* __restrict__ k2, const float* __restrict__ k3,
-                                    long nvec, int ncv, int act) {
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
-    const int c0 = (int)(i % ncv) * 8;
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
+    T* __restrict__ dz, const T* __restrict__ y, const float* __restrict__ gamma,
+    const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
+    const float* __restrict__ k2, const float* __restrict__ k3, long M, int Cp, int act, ColGrid g) {
+  const int ncv = Cp / 8;
+  const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
+  const int cv = blockIdx.x * g.cvl + cv_lane;
+  if (cv >= ncv) return;
+  const long r0 = blockIdx.y * g.rows_per_chunk;
+  const long r1 = min(M, r0 + g.rows_per_chunk);
+  float mu[8], a[8], b[8], is[8], c2[8], c3[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int c = cv * 8 + k;
+    mu[k] = mean[c]; is[k] = invstd[c]; a[k] = gamma[c] * is[k]; b[k] = beta[c];
+    c2[k] = k2[c]; c3[k] = k3[c];
+  }
+  long r = r0 + row_lane;
+  for (; r + rl < r1; r += 2 * rl) {
+    float d[2][8], v[2][8];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      IO<T>::ld(dz + ((r + u * rl) * ncv + cv) * 8, d[u]);
+      IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float yc = v[u][k] - mu[k];
+        const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[u][k] : 0.f;
+        d[u][k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
+      }
+      IO<T>::st(dz + ((r + u * rl) * ncv + cv) * 8, d[u]);
+    }
+  }
+  for (; r < r1; r += rl) {
     float d[8], v[8];
-    IO<T>::ld(dz + i * 8, d);
-    IO<T>::ld(y + i * 8, v);
+    IO<T>::ld(dz + (r * ncv + cv) * 8, d);
+    IO<T>::ld(y + (r * ncv + cv) * 8, v);
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      const int c = c0 + k;
-      const float xh = (v[k] - mean[c]) * invstd[c];
-      const float dp = act_pass(fmaf(gamma[c], xh, beta[c]), act) ? d[k] : 0.f;
-      d[k] = gamma[c] * invstd[c] * (dp - k2[c] - xh * k3[c]);
+      const float yc = v[k] - mu[k];
+      const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
+      d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
     }
-    IO<T>::st(dz + i * 8, d);
+    IO<T>::st(dz + (r * ncv + cv) * 8, d);
   }
 }
 
@@ -471,12 +525,18 @@ __global__ __launch_bounds__(256) void mse_kernel(const T* __restrict__ s, const
   if (threadIdx.x == 0) part[blockIdx.x] = red[0];
 }
 
-__global__ void mse_final_kernel(const float* __restrict__ part, int n, double inv_m, float* loss) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    double s = 0.0;
-    for (int i = 0; i < n; ++i) s += (double)part[i];
-    *loss = (float)(s * inv_m);
+__global__ __launch_bounds__(256) void mse_final_kernel(const float* __restrict__ part, int n, double inv_m,
+                                                        float* loss) {
+  __shared__ double red[256];
+  double s = 0.0;
+  for (int i = threadIdx.x; i < n; i += 256) s += (double)part[i];
+  red[threadIdx.x] = s;
+  __syncthreads();
+  for (int h = 128; h > 0; h >>= 1) {
+    if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+    __syncthreads();
   }
+  if (threadIdx.x == 0) *loss = (float)(red[0] * inv_m);
 }
 
 // ---------------------------------------------------------------------------
@@ -532,13 +592,28 @@ __global__ void transpose_weights_kernel(const T* __restrict__ wc, T* __restrict
   }
 }
 
-// out[j] = sum_s part[s*stride + j]   (ordered second stage of split reductions)
-__global__ void sum_partials_kernel(const float* __restrict__ part, float* __restrict__ out, long n,
-                                    int splits, long stride) {
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+// out[j] = sum_s part[s*stride + j]   (ordered second stage of split reductions).
+// Block = 32 outputs x 8 split lanes: lane l adds splits l, l+8, ... in order, then the 8 lane
+// sums are added in order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ part,
+                                                           float* __restrict__ out, long n, int splits,
+                                                           long stride) {
+  __shared__ float red[8][32];
+  const int o = threadIdx.x & 31, l = threadIdx.x >> 5;
+  for (long base = (long)blockIdx.x * 32; base < n; base += (long)gridDim.x * 32) {
+    const long i = base + o;
     float s = 0.f;
-    for (int k = 0; k < splits; ++k) s += part[(long)k * stride + i];
-    out[i] = s;
+    if (i < n)
+      for (int k = l; k < splits; k += 8) s += part[(long)k * stride + i];
+    red[l][o] = s;
+    __syncthreads();
+    if (l == 0 && i < n) {
+      float t = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) t += red[k][o];
+      out[i] = t;
+    }
+    __syncthreads();
   }
 }
 

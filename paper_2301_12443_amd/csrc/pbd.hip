@@ -172,7 +172,8 @@ size_t tensor_bytes(const pbd_ctx* c, Shape s) {
   return align_up((size_t)c->o.batch * s.h * s.w * round8(s.c) * c->esz);
 }
 
-ColGrid col_grid(long M, int Cp) {
+// rows_per_thread: how many rows a thread should stream at least; max_blocks caps the grid
+ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 2048) {
   ColGrid g;
   const int ncv = Cp / 8;
   int cvl = 1;
@@ -180,8 +181,8 @@ ColGrid col_grid(long M, int Cp) {
   g.cvl = cvl;
   g.slabs = (ncv + cvl - 1) / cvl;
   const int rl = 256 / cvl;
-  long chunks = (M + (long)rl * 8 - 1) / ((long)rl * 8);
-  const long cap = std::max(1, 2048 / g.slabs);
+  long chunks = (M + (long)rl * rows_per_thread - 1) / ((long)rl * rows_per_thread);
+  const long cap = std::max(1, max_blocks / g.slabs);
   chunks = std::max(1L, std::min(chunks, cap));
   g.rows_per_chunk = (M + chunks - 1) / chunks;
   g.chunks = (int)((M + g.rows_per_chunk - 1) / g.rows_per_chunk);
@@ -195,7 +196,7 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
   w.tiles_k = (K + w.T - 1) / w.T;
   w.tiles_j = (J + w.T - 1) / w.T;
   const long tiles = (long)w.tiles_k * w.tiles_j;
-  long splits = std::max(1L, 1024 / tiles);
+  long splits = std::max(1L, 512 / tiles);
   const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
   splits = std::min(splits, max_by_mem);
   splits = std::min(splits, (M + w.BKP - 1) / w.BKP);
@@ -204,6 +205,17 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
   w.pix_per_split = (int)pps;
   w.splits = (int)((M + pps - 1) / pps);
   return w;
+}
+
+// split-K factor of an implicit-GEMM launch: small-M layers (late VGG / ResNet stages) have too few
+// output tiles to fill 256 CUs, so their reduction is cut into slices that run side by side
+int igemm_splits(long M, int NC, int Kred) {
+  const int BN = NC >= 128 ? 128 : (NC > 32 ? 64 : 32);
+  const long tiles = ((M + IG_BM - 1) / IG_BM) * ((NC + BN - 1) / BN);
+  const int nk = (Kred + IG_BK - 1) / IG_BK;
+  if (tiles >= 256 || nk < 16) return 1;
+  long splits = std::min<long>((512 + tiles - 1) / tiles, nk / 8);
+  return (int)std::max(1L, std::min(splits, 32L));
 }
 
 constexpr int kMseBlocks = 1024;
@@ -221,6 +233,10 @@ int plan(pbd_ctx* c) {
   for (BlockPlan& bp : c->net[0])
     for (OpPlan& op : bp.ops) {
       if (op.d.type != OP_CBA) continue;
+      if (!op.dw && bf) {
+        const long M = (long)c->o.batch * op.out.h * op.out.w;
+        need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p) * M * op.d.c_out * 4);
+      }
       op.t_w = take(op.wn * es);
       op.t_gamma = take(op.cout_p * 4); op.t_beta = take(op.cout_p * 4);
       op.t_rmean = take(op.cout_p * 4); op.t_rvar = take(op.cout_p * 4);
@@ -284,10 +300,14 @@ int plan(pbd_ctx* c) {
         const ColGrid g = col_grid(M, op.cout_p);
         need_red((size_t)g.chunks * 2 * op.cout_p * 4);
         if (op.dw) {
-          need_red((size_t)g.chunks * op.d.k * op.d.k * op.cout_p * 4);
+          const ColGrid gw = col_grid(M, op.cout_p, 8, 1024 / op.d.k);
+          need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
           need_red((size_t)w.splits * op.wn * 4);
+          const long Min = (long)c->o.batch * op.in.h * op.in.w;
+          need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p) * M * op.d.c_out * 4);
+          need_red((size_t)igemm_splits(Min, op.cin_p, op.d.k * op.d.k * op.d.c_out) * Min * op.cin_p * 4);
         }
       } else if (op.d.type == OP_POOL) {
         op.idx = s; s += align_up((size_t)M * op.cout_p);
@@ -346,7 +366,7 @@ template <class T> struct Exec {
     if (mfma()) {
       if constexpr (sizeof(T) == 2) {
         IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
-                    op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p};
+                    op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0};
         ProfScope ps(c, a ? "conv_fwd_mfma_affine" : "conv_fwd_mfma", bytes, flops, net, blk, opi);
         launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE);
       }
@@ -358,15 +378,22 @@ template <class T> struct Exec {
   }
 
   template <int MODE>
-  void launch_igemm(const IgemmArgs& g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
+  void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi) {
     const int BN = g.NC >= 128 ? 128 : (g.NC > 32 ? 64 : 32);
-    dim3 grid((g.M + IG_BM - 1) / IG_BM, (g.NC + BN - 1) / BN);
-#define PBD_IG(BN_, EPI_) igemm_kernel<MODE, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, out, a, b, act, g)
-#define PBD_IG_BN(EPI_) do { if (BN == 128) PBD_IG(128, EPI_); else if (BN == 64) PBD_IG(64, EPI_); else PBD_IG(32, EPI_); } while (0)
-    if (epi == EPI_AFFINE_ACT) PBD_IG_BN(EPI_AFFINE_ACT);
-    else if (epi == EPI_ACCUM) PBD_IG_BN(EPI_ACCUM);
-    else PBD_IG_BN(EPI_STORE);
+    const int splits = igemm_splits(g.M, g.NC, g.Kred);
+    const int nk = (g.Kred + IG_BK - 1) / IG_BK;
+    g.ksteps_per_split = (nk + splits - 1) / splits;
+    dim3 grid((g.M + IG_BM - 1) / IG_BM, (g.NC + BN - 1) / BN, (nk + g.ksteps_per_split - 1) / g.ksteps_per_split);
+#define PBD_IG(BN_, EPI_, OUT_) igemm_kernel<MODE, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, OUT_, a, b, act, g)
+#define PBD_IG_BN(EPI_, OUT_) do { if (BN == 128) PBD_IG(128, EPI_, OUT_); else if (BN == 64) PBD_IG(64, EPI_, OUT_); else PBD_IG(32, EPI_, OUT_); } while (0)
+    if (grid.z > 1) {
+      PBD_IG_BN(EPI_PARTIAL, reinterpret_cast<bf16_t*>(red()));
+      const long nvec = (long)g.M * g.NC / 8;
+      splitk_epilogue_kernel<<<grid_for(nvec), 256, 0, st>>>(red(), out, a, b, act, epi, nvec, g.NC / 8, (int)grid.z);
+    } else if (epi == EPI_AFFINE_ACT) PBD_IG_BN(EPI_AFFINE_ACT, out);
+    else if (epi == EPI_ACCUM) PBD_IG_BN(EPI_ACCUM, out);
+    else PBD_IG_BN(EPI_STORE, out);
 #undef PBD_IG_BN
 #undef PBD_IG
   }
@@ -380,7 +407,7 @@ template <class T> struct Exec {
       if constexpr (sizeof(T) == 2) {
         // rows = input pixels, columns = input channels, reduction over (r, s, k)
         IgemmArgs g{N, op.out.h, op.out.w, op.d.c_out, op.in.h, op.in.w, op.cin_p, op.d.k, op.d.k,
-                    op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out};
+                    op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out, 0};
         ProfScope ps(c, "conv_dgrad_mfma", bytes, flops, net, blk, opi);
         launch_igemm<1>(g, (const bf16_t*)dy, (const bf16_t*)wt, (bf16_t*)dx, nullptr, nullptr, 0,
                         accumulate ? EPI_ACCUM : EPI_STORE);
@@ -413,7 +440,7 @@ template <class T> struct Exec {
         }
         if (w.splits > 1) {
           ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
-          sum_partials_kernel<<<grid_for((long)op.wn), 256, 0, st>>>(part, dw, (long)op.wn, w.splits, (long)op.wn);
+          sum_partials_kernel<<<grid_for((long)op.wn, 32), 256, 0, st>>>(part, dw, (long)op.wn, w.splits, (long)op.wn);
         }
       }
     } else {
@@ -441,7 +468,7 @@ template <class T> struct Exec {
   void dw_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
     const int N = c->o.batch;
     const long M = (long)N * op.out.h * op.out.w;
-    const ColGrid g = col_grid(M, op.cout_p);
+    const ColGrid g = col_grid(M, op.cout_p, 8, 1024 / op.d.k);
     dim3 grid(g.slabs, g.chunks, op.d.k);
     const size_t smem = 256 * 8 * sizeof(float);
     {
@@ -454,7 +481,7 @@ template <class T> struct Exec {
                                                        op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
     }
     ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
-    sum_partials_kernel<<<grid_for((long)op.wn), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
+    sum_partials_kernel<<<grid_for((long)op.wn, 32), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
   }
 
   // ---- joins / pool -------------------------------------------------------
@@ -580,10 +607,11 @@ template <class T> struct Exec {
             red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
             wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
         {
-          const long nvec = M * op.cout_p / 8;
+          const ColGrid ga = col_grid(M, op.cout_p, 32);
           ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
-          bn_apply_kernel<T><<<grid_for(nvec), 256, 0, st>>>(y, z, wsf(op.s_mean), wsf(op.s_invstd), master + op.e_gamma,
-                                                          master + op.e_beta, nvec, op.cout_p / 8, op.d.act);
+          bn_apply_kernel<T><<<dim3(ga.slabs, ga.chunks), 256, 0, st>>>(y, z, wsf(op.s_mean), wsf(op.s_invstd),
+                                                                     master + op.e_gamma, master + op.e_beta, M,
+                                                                     op.cout_p, op.d.act, ga);
         }
       } else if (op.d.type == OP_POOL) {
         pool_fwd(op, x, z, reinterpret_cast<uint8_t*>(c->ws + scr + op.idx));
@@ -607,7 +635,7 @@ template <class T> struct Exec {
       opi = -1;
       ProfScope ps(c, "mse_loss_grad", 3 * bytes_of(s), 0, net, blk, opi);
       mse_kernel<T><<<nb, 256, 0, st>>>(value(nval - 1), relay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
-      mse_final_kernel<<<1, 64, 0, st>>>(red(), nb, 1.0 / (double)numel, loss_dev);
+      mse_final_kernel<<<1, 256, 0, st>>>(red(), nb, 1.0 / (double)numel, loss_dev);
     }
 
     // ---- backward ---------------------------------------------------------
@@ -633,11 +661,11 @@ template <class T> struct Exec {
                                                                          grad + op.e_gamma, grad + op.e_beta,
                                                                          wsf(op.s_k2), wsf(op.s_k3));
         {
-          const long nvec = M * op.cout_p / 8;
+          const ColGrid ga = col_grid(M, op.cout_p, 16);
           ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
-          bn_bwd_apply_kernel<T><<<grid_for(nvec), 256, 0, st>>>(dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean),
-                                                                 wsf(op.s_invstd), wsf(op.s_k2), wsf(op.s_k3), nvec,
-                                                                 op.cout_p / 8, op.d.act);
+          bn_bwd_apply_kernel<T><<<dim3(ga.slabs, ga.chunks), 256, 0, st>>>(
+              dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
+              wsf(op.s_k3), M, op.cout_p, op.d.act, ga);
         }
         const T* x = value(iv);
         if (op.dw) dw_wgrad(op, dz, x, grad + op.e_w);
