@@ -117,8 +117,9 @@ int pbd_read_tensor(pbd_ctx* ctx, int32_t kind, int32_t net, int32_t b, int32_t 
 /* Copy A_i (i = 0..B) of the last relay to host as float32 NCHW; waits. */
 int pbd_read_act(pbd_ctx* ctx, int32_t i, float* host, size_t n);
 /* Copy value v of student block b (0 = its input, j+1 = output of op j) as saved by
- * the last pbd_student_step on that block, float32 NCHW; valid until another block
- * is stepped (blocks share scratch).  Testing aid; waits. */
+ * the last step of that block, float32 NCHW.  When the blocks' scratch does not fit side by
+ * side in the workspace they share one region and the values are valid only until another
+ * block is stepped (PBD_ESTATE afterwards).  Testing aid; waits. */
 int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
 
 /* Teacher relay (Algorithm 1, load + T.forward; Sec. IV-A, Sec. VII-A).  x_dev:
@@ -138,8 +139,14 @@ int pbd_student_step(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pb
                      float lr, float* loss_dev);
 
 /* The whole step: relay, then every student block; no teacher block runs twice.
- * losses_dev: device float32[B].  Same results as the two calls above. */
+ * losses_dev: device float32[B].  Same results as the two calls above.  When the bound
+ * stream is a real (non-null) stream and profiling is off, the body of the step is
+ * captured once into a HIP graph and replayed on later calls (it only touches
+ * workspace addresses; x_dev, lr and losses_dev stay outside the graph). */
 int pbd_distill_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
+
+/* 1 if pbd_distill_step currently replays a captured HIP graph, 0 if it launches directly. */
+int pbd_uses_graph(const pbd_ctx* ctx);
 
 /* Wait for the bound stream; reports asynchronous failures. */
 int pbd_sync(pbd_ctx* ctx);

@@ -546,7 +546,8 @@ __global__ __launch_bounds__(256) void mse_final_kernel(const float* __restrict_
 template <class T>
 __global__ void sgd_momentum_kernel(float* __restrict__ w, float* __restrict__ v,
                                     const float* __restrict__ g, T* __restrict__ wc, long n4,
-                                    float lr, float mu) {
+                                    const float* __restrict__ lr_ptr, float mu) {
+  const float lr = *lr_ptr;  // device scalar: a captured graph stays valid when the rate changes
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n4; i += (long)gridDim.x * blockDim.x) {
     float4 wv = reinterpret_cast<float4*>(w)[i], vv = reinterpret_cast<float4*>(v)[i];
     const float4 gv = reinterpret_cast<const float4*>(g)[i];
@@ -563,6 +564,8 @@ __global__ void sgd_momentum_kernel(float* __restrict__ w, float* __restrict__ v
     }
   }
 }
+
+__global__ void set_scalar_kernel(float* p, float v) { *p = v; }
 
 // compute copy <- rne(master) without an update (after parameters were loaded)
 __global__ void cast_params_kernel(const float* __restrict__ w, bf16_t* __restrict__ wc, long n4) {

@@ -62,7 +62,9 @@ struct BlockPlan {
   size_t master = 0, mom = 0, grad = 0, wc = 0, wt = 0, table = 0;  // byte offsets (param region)
   size_t wt_elems = 0;
   std::vector<TransposeEntry> ttable;
-  size_t scratch_bytes = 0;
+  size_t scratch_bytes = 0, red_bytes = 0;
+  size_t scr_off = 0, red_off = 0;   // absolute workspace offsets of this block's scratch regions
+  bool stepped = false;          // student: saved values in scratch belong to a finished step
   bool dirty = true;             // compute copies stale w.r.t. master weights
 };
 
@@ -78,14 +80,18 @@ struct pbd_ctx {
   std::vector<size_t> act_off;          // byte offsets (relay region)
   size_t esz = 4;                       // bytes per tensor element
   // regions (byte offsets from the workspace base)
-  size_t r_param = 0, r_relay = 0, r_tscr = 0, r_sscr = 0, r_red = 0, total = 0;
-  size_t red_bytes = 0;
+  size_t r_param = 0, r_relay = 0, r_tscr = 0, r_tred = 0, total = 0;
+  bool concurrent = false;              // student blocks own disjoint scratch and may overlap
+  std::vector<hipStream_t> side;        // one stream per student block (graph capture branches)
+  std::vector<hipEvent_t> ev_fork, ev_join;
   char* ws = nullptr;
   hipStream_t stream = nullptr;
   bool bound = false, relayed = false, fold_dirty = true;
-  int last_block = -1;                  // student block whose saved values are in scratch
   std::string err;
   // profiling
+  size_t lr_off = 0, loss_off = 0;      // device scalars: learning rate, per-block losses
+  hipGraphExec_t gexec = nullptr;       // the captured step (teacher blocks + student blocks)
+  bool graph_tried = false;
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
   std::vector<pbd_prof_entry> prof;
@@ -225,9 +231,8 @@ int plan(pbd_ctx* c) {
   const bool bf = c->o.precision == PBD_BF16;
   size_t p = 0;  // parameter region cursor
   auto take = [&](size_t bytes) { size_t o = p; p += align_up(bytes); return o; };
-  size_t red = 0;
+  size_t red = kMseBlocks * sizeof(float);  // reduction scratch of the block being planned
   auto need_red = [&](size_t bytes) { red = std::max(red, bytes); };
-  need_red(kMseBlocks * sizeof(float));
 
   // teacher parameters
   for (BlockPlan& bp : c->net[0])
@@ -266,7 +271,10 @@ int plan(pbd_ctx* c) {
     bp.wt = take(std::max<size_t>(et, 1) * es);
     bp.table = take(std::max<size_t>(bp.ttable.size(), 1) * sizeof(TransposeEntry));
   }
+  c->lr_off = take(256);
+  c->loss_off = take((size_t)c->B * 4);
   c->r_param = 0;
+  const size_t teacher_red = align_up(red);
   size_t cur = align_up(p);
   // relay store A_0..A_B
   c->r_relay = cur;
@@ -286,8 +294,10 @@ int plan(pbd_ctx* c) {
   c->r_tscr = cur; cur += align_up(tmax);
   // student scratch per block: values, conv outputs, pool indices, value gradients
   size_t smax = 0;
+  size_t ssum = 0;
   for (BlockPlan& bp : c->net[1]) {
     size_t s = 0;
+    red = kMseBlocks * sizeof(float);
     bp.val.assign(bp.shapes.size(), 0);
     bp.dval.assign(bp.shapes.size(), 0);
     for (size_t v = 1; v < bp.shapes.size(); ++v) {
@@ -313,11 +323,22 @@ int plan(pbd_ctx* c) {
         op.idx = s; s += align_up((size_t)M * op.cout_p);
       }
     }
-    bp.scratch_bytes = s;
-    smax = std::max(smax, s);
+    bp.scratch_bytes = align_up(s);
+    bp.red_bytes = align_up(red);
+    smax = std::max(smax, bp.scratch_bytes + bp.red_bytes);
+    ssum += bp.scratch_bytes + bp.red_bytes;
   }
-  c->r_sscr = cur; cur += align_up(smax);
-  c->r_red = cur; c->red_bytes = align_up(red); cur += c->red_bytes;
+  c->r_tred = cur; cur += teacher_red;
+  // Blocks are independent (Sec. IV-B): when the sum of their scratch fits comfortably in HBM each
+  // block gets its own region, so that their kernels can overlap; otherwise they share one region.
+  c->concurrent = c->B > 1 && cur + ssum <= ((size_t)160 << 30);
+  size_t at = cur;
+  for (BlockPlan& bp : c->net[1]) {
+    bp.scr_off = at;
+    bp.red_off = at + bp.scratch_bytes;
+    if (c->concurrent) at += bp.scratch_bytes + bp.red_bytes;
+  }
+  cur = c->concurrent ? at : cur + smax;
   c->total = cur;
   return PBD_OK;
 }
@@ -349,12 +370,13 @@ template <class T> struct Exec {
   pbd_ctx* c;
   hipStream_t st;
   int net = 0, blk = 0, opi = 0;
-  explicit Exec(pbd_ctx* ctx) : c(ctx), st(ctx->stream) {}
+  size_t red_off;
+  explicit Exec(pbd_ctx* ctx) : c(ctx), st(ctx->stream), red_off(ctx->r_tred) {}
 
   T* ws(size_t off) const { return reinterpret_cast<T*>(c->ws + off); }
   float* wsf(size_t off) const { return reinterpret_cast<float*>(c->ws + off); }
   T* relay(int i) const { return ws(c->r_relay + c->act_off[i]); }
-  float* red() const { return wsf(c->r_red); }
+  float* red() const { return wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
 
@@ -542,8 +564,18 @@ template <class T> struct Exec {
     c->fold_dirty = false;
   }
 
-  void relay_all(const float* x_dev) {
+  void set_lr(float lr) { set_scalar_kernel<<<1, 1, 0, st>>>(wsf(c->lr_off), lr); }
+
+  // everything a step needs that depends on the caller's pointers or on freshly loaded parameters
+  void prepare(const float* x_dev) {
     if (c->fold_dirty) fold_teacher_bn();
+    for (int b = 0; b < c->B; ++b) {
+      net = PBD_STUDENT; blk = b;
+      if (c->net[1][b].dirty) refresh_compute_copies(c->net[1][b]);
+    }
+    cast_input(x_dev);
+  }
+  void cast_input(const float* x_dev) {
     {
       const Shape s = c->act[0];
       const long nvec = (long)c->o.batch * s.h * s.w * round8(s.c) / 8;
@@ -551,7 +583,33 @@ template <class T> struct Exec {
       ProfScope ps(c, "cast_input", (double)c->o.batch * s.c * s.h * s.w * 4 + bytes_of(s), 0, net, blk, opi);
       cast_input_kernel<T><<<grid_for(nvec), 256, 0, st>>>(x_dev, relay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
     }
+  }
+  void relay_all(const float* x_dev) {
+    if (c->fold_dirty) fold_teacher_bn();
+    cast_input(x_dev);
     for (int b = 0; b < c->B; ++b) teacher_block(b);
+    c->relayed = true;
+  }
+  // the pointer-independent body of a step: T_1..T_B once each, then every student block
+  // With `fork` (graph capture, disjoint scratch) student block b runs on its own stream as soon as
+  // T_b has produced its target, next to T_{b+1}: the one-device form of the overlap of Sec. IV-A.
+  void step_body(bool fork) {
+    hipStream_t main = st;
+    for (int b = 0; b < c->B; ++b) {
+      teacher_block(b);
+      if (fork) {
+        (void)hipEventRecord(c->ev_fork[b], main);
+        (void)hipStreamWaitEvent(c->side[b], c->ev_fork[b], 0);
+        st = c->side[b];
+        student_block(b, wsf(c->loss_off) + b);
+        (void)hipEventRecord(c->ev_join[b], st);
+        st = main;
+      }
+    }
+    for (int b = 0; b < c->B; ++b) {
+      if (fork) (void)hipStreamWaitEvent(main, c->ev_join[b], 0);
+      else student_block(b, wsf(c->loss_off) + b);
+    }
     c->relayed = true;
   }
 
@@ -574,12 +632,13 @@ template <class T> struct Exec {
                                                       reinterpret_cast<const TransposeEntry*>(c->ws + bp.table));
   }
 
-  void student_block(int b, float lr, float* loss_dev) {
+  void student_block(int b, float* loss_dev) {
     BlockPlan& bp = c->net[1][b];
     net = PBD_STUDENT; blk = b;
     if (bp.dirty) refresh_compute_copies(bp);
     const int N = c->o.batch;
-    const size_t scr = c->r_sscr;
+    const size_t scr = bp.scr_off;
+    red_off = bp.red_off;
     auto value = [&](int v) -> T* { return v == 0 ? relay(b) : ws(scr + bp.val[v]); };
     auto dvalue = [&](int v) -> T* { return ws(scr + bp.dval[v]); };
     T* wc = ws(bp.wc);
@@ -710,12 +769,15 @@ template <class T> struct Exec {
       const long n4 = (long)bp.arena_elems / 4;
       ProfScope ps(c, "sgd_momentum", (double)bp.arena_elems * (20 + (sizeof(T) == 2 ? 2 : 0)), 0, net, blk, opi);
       if constexpr (sizeof(T) == 2)
-        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, (bf16_t*)wc, n4, lr, c->o.momentum);
+        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, (bf16_t*)wc, n4, wsf(c->lr_off), c->o.momentum);
       else
-        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, nullptr, n4, lr, c->o.momentum);
+        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, nullptr, n4, wsf(c->lr_off), c->o.momentum);
     }
     transpose_weights(bp);
-    c->last_block = b;
+    red_off = c->r_tred;
+    if (!c->concurrent)
+      for (BlockPlan& other : c->net[1]) other.stepped = false;   // shared scratch was overwritten
+    bp.stepped = true;
   }
 };
 
@@ -921,6 +983,10 @@ int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t
 
 void pbd_destroy(pbd_ctx* c) {
   if (!c) return;
+  if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
+  for (hipStream_t s2 : c->side) (void)hipStreamDestroy(s2);
+  for (hipEvent_t e : c->ev_fork) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_join) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
   delete c;
 }
@@ -939,10 +1005,12 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
   // parameters, optimiser state and statistics start at zero; the relay store too,
   // so that padded channels never hold stale bits
   HIP_TRY(c, hipMemsetAsync(c->ws, 0, c->r_tscr, c->stream));
+  if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
+  c->graph_tried = false;
   c->bound = true;
   c->relayed = false;
   c->fold_dirty = true;
-  c->last_block = -1;
+  for (BlockPlan& bp : c->net[1]) bp.stepped = false;
   // BN identity: gamma = 1, running variance = 1
   for (int net = 0; net < 2; ++net)
     for (int b = 0; b < c->B; ++b) {
@@ -1029,10 +1097,10 @@ int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
   if (b < 0 || b >= c->B) return fail(c, PBD_EINVAL, "block %d outside 0..%d", b, c->B - 1);
   BlockPlan& bp = c->net[1][b];
   if (v < 0 || v >= (int)bp.shapes.size()) return fail(c, PBD_EINVAL, "value %d outside 0..%zu", v, bp.shapes.size() - 1);
-  if (c->last_block != b) return fail(c, PBD_ESTATE, "block %d is not the block stepped last", b);
+  if (!bp.stepped) return fail(c, PBD_ESTATE, "block %d holds no saved values (not stepped, or scratch reused)", b);
   const Shape s = bp.shapes[v];
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
-  const char* dev = v == 0 ? c->ws + c->r_relay + c->act_off[b] : c->ws + c->r_sscr + bp.val[v];
+  const char* dev = v == 0 ? c->ws + c->r_relay + c->act_off[b] : c->ws + bp.scr_off + bp.val[v];
   return download_act(c, dev, s, host);
 }
 
@@ -1055,7 +1123,7 @@ int pbd_student_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_
   if (!c->relayed) return fail(c, PBD_ESTATE, "no teacher relay has run yet");
   if ((rc = check_view(c, A_prev, i - 1, "A_prev"))) return rc;
   if ((rc = check_view(c, A_i, i, "A_i"))) return rc;
-  return dispatch(c, [&](auto& e) { e.student_block(i - 1, lr, loss_dev); });
+  return dispatch(c, [&](auto& e) { e.set_lr(lr); e.student_block(i - 1, loss_dev); });
 }
 
 int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev) {
@@ -1064,11 +1132,49 @@ int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev
   if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
   if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
   if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
-  return dispatch(c, [&](auto& e) {
-    e.relay_all(x_dev);                                   // every T_i exactly once
-    for (int b = 0; b < c->B; ++b) e.student_block(b, lr, losses_dev + b);
-  });
+  // The body of the step touches only workspace addresses, so it is captured once into a HIP
+  // graph and replayed: ~300 small launches per step would otherwise be bound by launch cost.
+  // Capture needs a real stream and no profiling events; otherwise the kernels are launched directly.
+  const bool want_graph = c->stream != nullptr && !c->prof_on;
+  rc = dispatch(c, [&](auto& e) { e.set_lr(lr); e.prepare(x_dev); });
+  if (rc) return rc;
+  if (want_graph && !c->gexec && !c->graph_tried) {
+    c->graph_tried = true;
+    hipGraph_t graph = nullptr;
+    bool fork = c->concurrent;
+    if (fork && c->side.empty()) {
+      for (int b = 0; b < c->B && fork; ++b) {
+        hipStream_t s2; hipEvent_t e1, e2;
+        fork = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&e1, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&e2, hipEventDisableTiming) == hipSuccess;
+        if (fork) { c->side.push_back(s2); c->ev_fork.push_back(e1); c->ev_join.push_back(e2); }
+      }
+    }
+    fork = fork && (int)c->side.size() == c->B;
+    if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
+      dispatch(c, [&](auto& e) { e.step_body(fork); });
+      hipError_t ee = hipStreamEndCapture(c->stream, &graph);
+      if (ee == hipSuccess && graph && hipGraphInstantiate(&c->gexec, graph, nullptr, nullptr, 0) != hipSuccess)
+        c->gexec = nullptr;
+      if (graph) (void)hipGraphDestroy(graph);
+    }
+    (void)hipGetLastError();
+  }
+  if (want_graph && c->gexec) {
+    HIP_TRY(c, hipGraphLaunch(c->gexec, c->stream));
+    c->relayed = true;
+    for (BlockPlan& bp : c->net[1]) bp.stepped = c->concurrent;
+    c->net[1].back().stepped = true;
+  } else {
+    rc = dispatch(c, [&](auto& e) { e.step_body(false); });
+    if (rc) return rc;
+  }
+  HIP_TRY(c, hipMemcpyAsync(losses_dev, c->ws + c->loss_off, (size_t)c->B * 4, hipMemcpyDeviceToDevice, c->stream));
+  return after_launches(c);
 }
+
+int pbd_uses_graph(const pbd_ctx* c) { return c && c->gexec ? 1 : 0; }
 
 int pbd_sync(pbd_ctx* c) {
   int rc = check_ready(c);

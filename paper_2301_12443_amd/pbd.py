@@ -22,7 +22,7 @@ STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
 
 SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
            "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
-           "pbd_teacher_relay", "pbd_student_step", "pbd_distill_step", "pbd_sync",
+           "pbd_teacher_relay", "pbd_student_step", "pbd_distill_step", "pbd_uses_graph", "pbd_sync",
            "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
 
 
@@ -76,6 +76,7 @@ def lib():
         L.pbd_student_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(pbd_tensor), C.POINTER(pbd_tensor),
                                        C.c_float, C.c_void_p]
         L.pbd_distill_step.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+        L.pbd_uses_graph.argtypes = [C.c_void_p]
         L.pbd_sync.argtypes = [C.c_void_p]
         L.pbd_set_profile.argtypes = [C.c_void_p, C.c_int32]
         L.pbd_reset_profile.argtypes = [C.c_void_p]
@@ -128,9 +129,12 @@ class Distiller:
         self.device = torch.device(device)
         self._ws = torch.empty(self.workspace_bytes() + 256, dtype=torch.uint8, device=self.device)
         base = (self._ws.data_ptr() + 255) // 256 * 256
-        self._stream = stream if stream is not None else torch.cuda.current_stream(self.device)
-        self._check(lib().pbd_bind(self.h, base, self.workspace_bytes(), self._stream.cuda_stream))
+        # a stream of its own (not the legacy default stream) so that the library can capture the
+        # step into a HIP graph; callers order against it with sync() or stream events
+        self._stream = stream if stream is not None else torch.cuda.Stream(self.device)
         self.losses = torch.zeros(self.B, dtype=torch.float32, device=self.device)
+        torch.cuda.synchronize(self.device)
+        self._check(lib().pbd_bind(self.h, base, self.workspace_bytes(), self._stream.cuda_stream))
         return self
 
     def load_params(self):
@@ -176,6 +180,9 @@ class Distiller:
 
     def distill_step(self, x_dev, lr):
         self._check(lib().pbd_distill_step(self.h, x_dev.data_ptr(), lr, self.losses.data_ptr()))
+
+    def uses_graph(self) -> bool:
+        return bool(lib().pbd_uses_graph(self.h))
 
     def sync(self):
         self._check(lib().pbd_sync(self.h))
