@@ -214,19 +214,36 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, 
   }
 }
 
+// Finalize kernels run 16 channels x 16 lanes per block: lane l adds chunks l, l+16, ... in order
+// and the 16 lane sums are then added in order (fixed association, independent of scheduling).
+__device__ __forceinline__ void finalize_sums(const float* __restrict__ part, int chunks, int Cp, int c,
+                                              int lane, double& s1, double& s2) {
+  __shared__ double red1[16][17], red2[16][17];
+  const int cl = threadIdx.x & 15;
+  double a = 0.0, b = 0.0;
+  if (c < Cp)
+    for (int k = lane; k < chunks; k += 16) {
+      a += (double)part[(long)k * 2 * Cp + c];
+      b += (double)part[(long)k * 2 * Cp + Cp + c];
+    }
+  red1[lane][cl] = a;
+  red2[lane][cl] = b;
+  __syncthreads();
+  s1 = 0.0; s2 = 0.0;
+#pragma unroll
+  for (int l = 0; l < 16; ++l) { s1 += red1[l][cl]; s2 += red2[l][cl]; }
+}
+
 // mean, biased variance -> inv std; running statistics
 //   rm <- (1-rho) rm + rho mean,  rv <- (1-rho) rv + rho var m/(m-1)
 template <class T>
 __global__ void bn_finalize_kernel(const float* __restrict__ part, const T* __restrict__ y, int chunks,
                                    int Cp, double m, float* mean, float* invstd, float* rmean,
                                    float* rvar, float eps, float rho) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= Cp) return;
-  double s1 = 0.0, s2 = 0.0;
-  for (int k = 0; k < chunks; ++k) {
-    s1 += (double)part[(long)k * 2 * Cp + c];
-    s2 += (double)part[(long)k * 2 * Cp + Cp + c];
-  }
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15), lane = threadIdx.x >> 4;
+  double s1, s2;
+  finalize_sums(part, chunks, Cp, c, lane, s1, s2);
+  if (c >= Cp || lane != 0) return;
   const double shift = s1 / m;
   const double mu = (double)(float)y[c] + shift;
   double var = s2 / m - shift * shift;
@@ -286,13 +303,10 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 // k2 = dbeta/m, k3 = dgamma/m of  dy = gamma*invstd*(dpre - k2 - xhat*k3)
 __global__ void bn_bwd_finalize_kernel(const float* __restrict__ part, int chunks, int Cp, double m,
                                        float* g_gamma, float* g_beta, float* k2, float* k3) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= Cp) return;
-  double sb = 0.0, sg = 0.0;
-  for (int k = 0; k < chunks; ++k) {
-    sb += (double)part[(long)k * 2 * Cp + c];
-    sg += (double)part[(long)k * 2 * Cp + Cp + c];
-  }
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15), lane = threadIdx.x >> 4;
+  double sb, sg;
+  finalize_sums(part, chunks, Cp, c, lane, sb, sg);
+  if (c >= Cp || lane != 0) return;
   g_beta[c] = (float)sb;
   g_gamma[c] = (float)sg;
   k2[c] = (float)(sb / m);

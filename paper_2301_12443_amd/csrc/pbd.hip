@@ -179,7 +179,7 @@ size_t tensor_bytes(const pbd_ctx* c, Shape s) {
 }
 
 // rows_per_thread: how many rows a thread should stream at least; max_blocks caps the grid
-ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 2048) {
+ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 512) {
   ColGrid g;
   const int ncv = Cp / 8;
   int cvl = 1;
@@ -310,7 +310,7 @@ int plan(pbd_ctx* c) {
         const ColGrid g = col_grid(M, op.cout_p);
         need_red((size_t)g.chunks * 2 * op.cout_p * 4);
         if (op.dw) {
-          const ColGrid gw = col_grid(M, op.cout_p, 8, 1024 / op.d.k);
+          const ColGrid gw = col_grid(M, op.cout_p, 8, 768 / op.d.k);
           need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
@@ -490,7 +490,7 @@ template <class T> struct Exec {
   void dw_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
     const int N = c->o.batch;
     const long M = (long)N * op.out.h * op.out.w;
-    const ColGrid g = col_grid(M, op.cout_p, 8, 1024 / op.d.k);
+    const ColGrid g = col_grid(M, op.cout_p, 8, 768 / op.d.k);
     dim3 grid(g.slabs, g.chunks, op.d.k);
     const size_t smem = 256 * 8 * sizeof(float);
     {
@@ -662,11 +662,11 @@ template <class T> struct Exec {
           ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
           bn_stats_kernel<T><<<dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st>>>(y, red(), M, op.cout_p, g);
         }
-        bn_finalize_kernel<T><<<(op.cout_p + 127) / 128, 128, 0, st>>>(
+        bn_finalize_kernel<T><<<(op.cout_p + 15) / 16, 256, 0, st>>>(
             red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
             wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
         {
-          const ColGrid ga = col_grid(M, op.cout_p, 32);
+          const ColGrid ga = col_grid(M, op.cout_p, 32, 2048);
           ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
           bn_apply_kernel<T><<<dim3(ga.slabs, ga.chunks), 256, 0, st>>>(y, z, wsf(op.s_mean), wsf(op.s_invstd),
                                                                      master + op.e_gamma, master + op.e_beta, M,
@@ -716,11 +716,11 @@ template <class T> struct Exec {
               dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
               op.d.act, g);
         }
-        bn_bwd_finalize_kernel<<<(op.cout_p + 127) / 128, 128, 0, st>>>(red(), g.chunks, op.cout_p, (double)M,
+        bn_bwd_finalize_kernel<<<(op.cout_p + 15) / 16, 256, 0, st>>>(red(), g.chunks, op.cout_p, (double)M,
                                                                          grad + op.e_gamma, grad + op.e_beta,
                                                                          wsf(op.s_k2), wsf(op.s_k3));
         {
-          const ColGrid ga = col_grid(M, op.cout_p, 16);
+          const ColGrid ga = col_grid(M, op.cout_p, 16, 2048);
           ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
           bn_bwd_apply_kernel<T><<<dim3(ga.slabs, ga.chunks), 256, 0, st>>>(
               dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
