@@ -17,6 +17,8 @@
 //  * direct kernels: plain one-thread-per-output loops in fp32, used for the
 //    float32 precision and as a cross-check of the MFMA kernels.
 #pragma once
+#include <type_traits>
+
 #include "ew_kernels.h"
 
 namespace pbd {
@@ -121,6 +123,19 @@ __global__ void conv_direct_wgrad_kernel(const T* __restrict__ dy, const T* __re
 // MFMA implicit GEMM: forward (MODE 0) and backward-data (MODE 1)
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over a whole tensor: a load whose byte offset lies outside [0, bytes) returns
+// zeros in hardware, which turns padding, ragged tiles and the reduction tail into plain offsets
+// (no branches, no selects).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tensor_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+constexpr unsigned kOutOfRange = 0x80000000u;   // byte offset beyond any tensor (they are < 2^31 elements)
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // Generic view: Out[m][j] = sum_kk Agather(m, kk) * Bw[j][kk]
@@ -134,93 +149,127 @@ struct IgemmArgs {
   int M;      // N*HO*WO
   int Kred;   // R*S*CA
   int ksteps_per_split;  // reduction steps of IG_BK handled by one blockIdx.z (split-K)
+  unsigned a_bytes, b_bytes;  // sizes of the A tensor and of the weight matrix
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
 enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 
-constexpr int IG_BM = 128, IG_BK = 32, IG_PITCH = IG_BK + 8;
+constexpr int IG_BK = 32, IG_PITCH = IG_BK + 8;
 
-template <int MODE, int BN, int EPI>
+template <int MODE, int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A,
                                                     const bf16_t* __restrict__ Bw,
                                                     bf16_t* __restrict__ Out,
                                                     const float* __restrict__ ep_a,
                                                     const float* __restrict__ ep_b, int act,
                                                     IgemmArgs g) {
-  constexpr int WAVES_M = (BN == 128) ? 2 : 4, WAVES_N = 4 / WAVES_M;
-  constexpr int TM = IG_BM / (WAVES_M * 32), TN = BN / (WAVES_N * 32);
+  // wave grid: 128-row tiles 2x2 (BN 128) or 4x1; 64-row tiles 2x2 (BN >= 64) or 2x1 over 32 columns
+  constexpr int WAVES_M = BM == 128 ? (BN == 128 ? 2 : 4) : 2, WAVES_N = 4 / WAVES_M;
+  constexpr int TM = BM / (WAVES_M * 32);
+  constexpr int TN = (BN / (WAVES_N * 32)) > 0 ? BN / (WAVES_N * 32) : 1;
+  constexpr bool kIdleWaves = BN / (WAVES_N * 32) == 0;      // BM 64, BN 32: waves with wn = 1 only stage tiles
+  constexpr int A_LOADS = BM / 64;
   constexpr int B_LOADS = (BN * 4 + 255) / 256;  // 16-byte chunks of the weight tile per thread
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][IG_BM * IG_PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * IG_PITCH];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * IG_PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int m0 = blockIdx.x * IG_BM, n0 = blockIdx.y * BN;
+  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
   const int chunk = tid & 3;
+  const int sh = g.stride == 2 ? 1 : 0, smask = g.stride - 1;
 
-  // the two A rows this thread stages, decoded once
-  int rn[2], ra[2], rb[2];
-  bool rvalid[2];
+  // The A rows this thread stages, decoded once.  All offsets are 32-bit element indices
+  // (create rejects tensors of 2^31 elements or more), and the per-step work is a handful of adds.
+  int rbase[A_LOADS], rh[A_LOADS], rw[A_LOADS];
+  bool rvalid[A_LOADS];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < A_LOADS; ++i) {
     const int m = m0 + (tid >> 2) + 64 * i;
     rvalid[i] = m < g.M;
     const int mm = rvalid[i] ? m : 0;
-    rb[i] = mm % g.WO;
+    const int b_ = mm % g.WO;
     const int t = mm / g.WO;
-    ra[i] = t % g.HO;
-    rn[i] = t / g.HO;
+    const int a_ = t % g.HO;
+    rbase[i] = (t / g.HO) * g.HA * g.WA;                          // first pixel of image n
+    rh[i] = MODE == 0 ? a_ * g.stride - g.pad : a_ + g.pad;       // row of tap (0,0) / of the output pixel
+    rw[i] = MODE == 0 ? b_ * g.stride - g.pad : b_ + g.pad;
   }
-  // reduction position of this thread's chunk: kk = rs*CA + c
-  const int kt0 = blockIdx.z * g.ksteps_per_split;
-  int rs = (kt0 * IG_BK + chunk * 8) / g.CA;
-  int c = kt0 * IG_BK + chunk * 8 - rs * g.CA;
-
-  uint4 areg[2], breg[B_LOADS];
-  auto load_tile = [&](int kt) {
-    (void)kt;
-    const int r = rs / g.S, s = rs - r * g.S;
-    const bool kvalid = rs < g.R * g.S;
+  int brow[B_LOADS];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < B_LOADS; ++i) {
+    const int row = (tid >> 2) + 64 * i;
+    brow[i] = (row < BN && n0 + row < g.NC) ? (n0 + row) * g.Kred : -1;
+  }
+  // reduction position of this thread's chunk: kk = (r*S + s)*CA + c
+  const int kt0 = blockIdx.z * g.ksteps_per_split;
+  int kk = kt0 * IG_BK + chunk * 8;
+  int r, s, c;
+  {
+    const int rs = kk / g.CA;
+    c = kk - rs * g.CA;
+    r = rs / g.S;
+    s = rs - r * g.S;
+  }
+
+  // two register stages: tile kt+2 is requested while tile kt is multiplied and tile kt+1 moves to LDS
+  uint4 areg[2][A_LOADS], breg[2][B_LOADS];
+  const __amdgpu_buffer_rsrc_t a_rsrc = tensor_rsrc(A, g.a_bytes), b_rsrc = tensor_rsrc(Bw, g.b_bytes);
+  auto load_tile = [&](auto stage) {
+    constexpr int S_ = decltype(stage)::value;
+    const bool kvalid = r < g.R;
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
       int h, w;
       bool ok = rvalid[i] && kvalid;
       if (MODE == 0) {
-        h = ra[i] * g.stride + r - g.pad;
-        w = rb[i] * g.stride + s - g.pad;
+        h = rh[i] + r;
+        w = rw[i] + s;
       } else {
-        const int th = ra[i] + g.pad - r, tw = rb[i] + g.pad - s;
-        ok = ok && th >= 0 && tw >= 0 && (th % g.stride) == 0 && (tw % g.stride) == 0;
-        h = th / g.stride;
-        w = tw / g.stride;
+        const int th = rh[i] - r, tw = rw[i] - s;
+        ok = ok && ((th | tw) & smask) == 0;
+        h = th >> sh;
+        w = tw >> sh;
       }
-      ok = ok && h >= 0 && h < g.HA && w >= 0 && w < g.WA;
-      areg[i] = ok ? *reinterpret_cast<const uint4*>(A + (((long)rn[i] * g.HA + h) * g.WA + w) * g.CA + c)
-                   : make_uint4(0, 0, 0, 0);
+      ok = ok && (unsigned)h < (unsigned)g.HA && (unsigned)w < (unsigned)g.WA;
+      const unsigned off = (unsigned)((rbase[i] + h * g.WA + w) * g.CA + c) * 2u;
+      areg[S_][i] = buffer_load16(a_rsrc, ok ? off : kOutOfRange);
     }
-    const int kk = rs * g.CA + c;
 #pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) {
-      const int row = (tid >> 2) + 64 * i;
-      const bool ok = row < BN && (n0 + row) < g.NC && kvalid;
-      breg[i] = ok ? *reinterpret_cast<const uint4*>(Bw + (long)(n0 + row) * g.Kred + kk)
-                   : make_uint4(0, 0, 0, 0);
-    }
+    for (int i = 0; i < B_LOADS; ++i)
+      breg[S_][i] = buffer_load16(b_rsrc, (brow[i] >= 0 && kvalid) ? (unsigned)(brow[i] + kk) * 2u : kOutOfRange);
+    kk += IG_BK;
     c += IG_BK;
-    while (c >= g.CA) { c -= g.CA; ++rs; }
+    if (g.CA >= IG_BK) {          // at most one wrap per step
+      const bool wrap = c >= g.CA;
+      c -= wrap ? g.CA : 0;
+      s += wrap ? 1 : 0;
+      const bool wrap2 = s == g.S;
+      s = wrap2 ? 0 : s;
+      r += wrap2 ? 1 : 0;
+    } else {
+      while (c >= g.CA) {
+        c -= g.CA;
+        if (++s == g.S) { s = 0; ++r; }
+      }
+    }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](auto stage, int buf) {
+    constexpr int S_ = decltype(stage)::value;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      *reinterpret_cast<uint4*>(&As[buf][((tid >> 2) + 64 * i) * IG_PITCH + chunk * 8]) = areg[i];
+    for (int i = 0; i < A_LOADS; ++i)
+      *reinterpret_cast<uint4*>(&As[buf][((tid >> 2) + 64 * i) * IG_PITCH + chunk * 8]) = areg[S_][i];
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
       const int row = (tid >> 2) + 64 * i;
-      if (row < BN) *reinterpret_cast<uint4*>(&Bs[buf][row * IG_PITCH + chunk * 8]) = breg[i];
+      if (row < BN) *reinterpret_cast<uint4*>(&Bs[buf][row * IG_PITCH + chunk * 8]) = breg[S_][i];
     }
   };
 
+  // acc[i][j]: 32 channels (rows of the MFMA result) x 32 pixels (columns): the weight fragment is
+  // the first operand, so that a lane ends up with 4 consecutive channels of one pixel per register
+  // group and the epilogue stores 8 bytes (bf16) or 16 bytes (fp32 partial) at a time.
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -230,55 +279,80 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nk = min(g.ksteps_per_split, (g.Kred + IG_BK - 1) / IG_BK - kt0);
-  load_tile(0);
-  store_tile(0);
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  load_tile(S0{});
+  if (nk > 1) load_tile(S1{});
+  store_tile(S0{}, 0);
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) load_tile(kt + 1);
+  auto iteration = [&](int kt, auto cur) {
+    constexpr int C_ = decltype(cur)::value;
+    using Cur = std::integral_constant<int, C_>;
+    using Nxt = std::integral_constant<int, 1 - C_>;
+    if (kt + 2 < nk) load_tile(Cur{});          // stage C_ went to LDS one iteration ago
+    if (!(kIdleWaves && wn > 0)) {
 #pragma unroll
-    for (int ks = 0; ks < IG_BK / 16; ++ks) {
-      bf16x8 af[TM], bfr[TN];
+      for (int ks = 0; ks < IG_BK / 16; ++ks) {
+        bf16x8 af[TM], bfr[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = *reinterpret_cast<const bf16x8*>(
-            &As[buf][(wm * TM * 32 + i * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8*>(
-            &Bs[buf][(wn * TN * 32 + j * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
+          af[i] = *reinterpret_cast<const bf16x8*>(
+              &As[C_][(wm * TM * 32 + i * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          bfr[j] = *reinterpret_cast<const bf16x8*>(
+              &Bs[C_][(wn * TN * 32 + j * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+      }
     }
-    if (kt + 1 < nk) store_tile(buf ^ 1);
+    if (kt + 1 < nk) store_tile(Nxt{}, 1 - C_);
     __syncthreads();
+  };
+  for (int kt = 0; kt < nk; kt += 2) {
+    iteration(kt, S0{});
+    if (kt + 1 < nk) iteration(kt + 1, S1{});
   }
+  if (kIdleWaves && wn > 0) return;
 
-  // epilogue: lane holds column j = lane%32, rows 8*(v/4) + 4*(lane/32) + v%4
+  // epilogue: lane holds pixel (lane%32) and channels 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 tile
+  const bool full = m0 + BM <= g.M && n0 + BN <= g.NC;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
-    if (col >= g.NC) continue;
-    float ea = 1.f, eb = 0.f;
-    if (EPI == EPI_AFFINE_ACT) { ea = ep_a[col]; eb = ep_b[col]; }
+  for (int i = 0; i < TM; ++i) {
+    const int row = m0 + wm * TM * 32 + i * 32 + (lane & 31);
+    if (!full && row >= g.M) continue;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * TM * 32 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row >= g.M) continue;
-        float o = acc[i][j][v];
+      for (int q = 0; q < 4; ++q) {
+        const int col = n0 + wn * TN * 32 + j * 32 + 8 * q + 4 * (lane >> 5);
+        if (!full && col >= g.NC) continue;   // NC % 8 == 0 and col % 4 == 0: a group is in or out as a whole
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
         if (EPI == EPI_PARTIAL) {
-          reinterpret_cast<float*>(Out)[((long)blockIdx.z * g.M + row) * g.NC + col] = o;
+          float* dst = reinterpret_cast<float*>(Out) + ((size_t)blockIdx.z * g.M + row) * g.NC + col;
+          *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
           continue;
         }
-        bf16_t* dst = Out + (long)row * g.NC + col;
-        if (EPI == EPI_AFFINE_ACT) o = apply_act(fmaf(o, ea, eb), act);
-        if (EPI == EPI_ACCUM) o += (float)*dst;
-        *dst = (bf16_t)o;
+        bf16_t* dst = Out + (size_t)row * g.NC + col;
+        if (EPI == EPI_AFFINE_ACT) {
+          const float4 ea = *reinterpret_cast<const float4*>(ep_a + col);
+          const float4 eb = *reinterpret_cast<const float4*>(ep_b + col);
+          o[0] = apply_act(fmaf(o[0], ea.x, eb.x), act); o[1] = apply_act(fmaf(o[1], ea.y, eb.y), act);
+          o[2] = apply_act(fmaf(o[2], ea.z, eb.z), act); o[3] = apply_act(fmaf(o[3], ea.w, eb.w), act);
+        }
+        if (EPI == EPI_ACCUM) {
+          const uint2 old = *reinterpret_cast<const uint2*>(dst);
+          o[0] += bf_lo(old.x); o[1] += bf_hi(old.x); o[2] += bf_lo(old.y); o[3] += bf_hi(old.y);
+        }
+        uint2 pk;
+        pk.x = pack_bf2(o[0], o[1]);
+        pk.y = pack_bf2(o[2], o[3]);
+        *reinterpret_cast<uint2*>(dst) = pk;
       }
   }
 }

@@ -213,16 +213,22 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
   return w;
 }
 
-// split-K factor of an implicit-GEMM launch: small-M layers (late VGG / ResNet stages) have too few
-// output tiles to fill 256 CUs, so their reduction is cut into slices that run side by side
-int igemm_splits(long M, int NC, int Kred) {
-  const int BN = NC >= 128 ? 128 : (NC > 32 ? 64 : 32);
-  const long tiles = ((M + IG_BM - 1) / IG_BM) * ((NC + BN - 1) / BN);
+// Tile shape and split-K factor of an implicit-GEMM launch.  256 CUs want >= 512 workgroups: layers
+// with few output tiles (late VGG / ResNet stages at small batch x image) first drop to 64-row tiles
+// and then cut their reduction into slices that run side by side.
+struct IgemmCfg { int BM, BN, splits; };
+IgemmCfg igemm_cfg(long M, int NC, int Kred) {
+  IgemmCfg c;
+  c.BN = NC >= 128 ? 128 : (NC > 32 ? 64 : 32);
+  const long tn = (NC + c.BN - 1) / c.BN;
+  c.BM = ((M + 127) / 128) * tn >= 512 ? 128 : 64;
+  const long tiles = ((M + c.BM - 1) / c.BM) * tn;
   const int nk = (Kred + IG_BK - 1) / IG_BK;
-  if (tiles >= 256 || nk < 16) return 1;
-  long splits = std::min<long>((512 + tiles - 1) / tiles, nk / 8);
-  return (int)std::max(1L, std::min(splits, 32L));
+  c.splits = 1;
+  if (tiles < 512 && nk >= 32) c.splits = (int)std::max(1L, std::min<long>(std::min<long>((1024 + tiles - 1) / tiles, nk / 16), 32L));
+  return c;
 }
+int igemm_splits(long M, int NC, int Kred) { return igemm_cfg(M, NC, Kred).splits; }
 
 constexpr int kMseBlocks = 1024;
 
@@ -388,7 +394,8 @@ template <class T> struct Exec {
     if (mfma()) {
       if constexpr (sizeof(T) == 2) {
         IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
-                    op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0};
+                    op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0,
+                    (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2), (unsigned)(op.wn * 2)};
         ProfScope ps(c, a ? "conv_fwd_mfma_affine" : "conv_fwd_mfma", bytes, flops, net, blk, opi);
         launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE);
       }
@@ -402,20 +409,22 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi) {
-    const int BN = g.NC >= 128 ? 128 : (g.NC > 32 ? 64 : 32);
-    const int splits = igemm_splits(g.M, g.NC, g.Kred);
+    const IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred);
     const int nk = (g.Kred + IG_BK - 1) / IG_BK;
-    g.ksteps_per_split = (nk + splits - 1) / splits;
-    dim3 grid((g.M + IG_BM - 1) / IG_BM, (g.NC + BN - 1) / BN, (nk + g.ksteps_per_split - 1) / g.ksteps_per_split);
-#define PBD_IG(BN_, EPI_, OUT_) igemm_kernel<MODE, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, OUT_, a, b, act, g)
-#define PBD_IG_BN(EPI_, OUT_) do { if (BN == 128) PBD_IG(128, EPI_, OUT_); else if (BN == 64) PBD_IG(64, EPI_, OUT_); else PBD_IG(32, EPI_, OUT_); } while (0)
+    g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
+    dim3 grid((g.M + cfg.BM - 1) / cfg.BM, (g.NC + cfg.BN - 1) / cfg.BN,
+              (nk + g.ksteps_per_split - 1) / g.ksteps_per_split);
+#define PBD_IG(BM_, BN_, EPI_, OUT_) igemm_kernel<MODE, BM_, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, OUT_, a, b, act, g)
+#define PBD_IG_BN(BM_, EPI_, OUT_) do { if (cfg.BN == 128) PBD_IG(BM_, 128, EPI_, OUT_); else if (cfg.BN == 64) PBD_IG(BM_, 64, EPI_, OUT_); else PBD_IG(BM_, 32, EPI_, OUT_); } while (0)
+#define PBD_IG_BM(EPI_, OUT_) do { if (cfg.BM == 128) PBD_IG_BN(128, EPI_, OUT_); else PBD_IG_BN(64, EPI_, OUT_); } while (0)
     if (grid.z > 1) {
-      PBD_IG_BN(EPI_PARTIAL, reinterpret_cast<bf16_t*>(red()));
+      PBD_IG_BM(EPI_PARTIAL, reinterpret_cast<bf16_t*>(red()));
       const long nvec = (long)g.M * g.NC / 8;
       splitk_epilogue_kernel<<<grid_for(nvec), 256, 0, st>>>(red(), out, a, b, act, epi, nvec, g.NC / 8, (int)grid.z);
-    } else if (epi == EPI_AFFINE_ACT) PBD_IG_BN(EPI_AFFINE_ACT, out);
-    else if (epi == EPI_ACCUM) PBD_IG_BN(EPI_ACCUM, out);
-    else PBD_IG_BN(EPI_STORE, out);
+    } else if (epi == EPI_AFFINE_ACT) PBD_IG_BM(EPI_AFFINE_ACT, out);
+    else if (epi == EPI_ACCUM) PBD_IG_BM(EPI_ACCUM, out);
+    else PBD_IG_BM(EPI_STORE, out);
+#undef PBD_IG_BM
 #undef PBD_IG_BN
 #undef PBD_IG
   }
@@ -429,7 +438,8 @@ template <class T> struct Exec {
       if constexpr (sizeof(T) == 2) {
         // rows = input pixels, columns = input channels, reduction over (r, s, k)
         IgemmArgs g{N, op.out.h, op.out.w, op.d.c_out, op.in.h, op.in.w, op.cin_p, op.d.k, op.d.k,
-                    op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out, 0};
+                    op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out, 0,
+                    (unsigned)((size_t)N * op.out.h * op.out.w * op.d.c_out * 2), (unsigned)(op.wn * 2)};
         ProfScope ps(c, "conv_dgrad_mfma", bytes, flops, net, blk, opi);
         launch_igemm<1>(g, (const bf16_t*)dy, (const bf16_t*)wt, (bf16_t*)dx, nullptr, nullptr, 0,
                         accumulate ? EPI_ACCUM : EPI_STORE);
@@ -972,10 +982,14 @@ int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t
     }
     c->act.push_back(t);
   }
-  if (opts->batch * (long)c->in.h * c->in.w > (1L << 30)) {
-    delete c;
-    return fail(nullptr, PBD_ESHAPE, "batch x H x W exceeds 2^30 pixels");
-  }
+  // kernels index tensors with 32-bit element offsets
+  for (int which = 0; which < 2; ++which)
+    for (const BlockPlan& bp : c->net[which])
+      for (const Shape& s : bp.shapes)
+        if ((long)opts->batch * s.h * s.w * round8(s.c) >= (1L << 31) - 64) {
+          delete c;
+          return fail(nullptr, PBD_ESHAPE, "a tensor of batch x %d x %d x %d has 2^31 elements or more", s.h, s.w, s.c);
+        }
   plan(c);
   *out = c;
   return PBD_OK;
