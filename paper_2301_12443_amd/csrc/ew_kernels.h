@@ -111,24 +111,29 @@ struct ColGrid {
   long rows_per_chunk;
 };
 
-// in-block ordered reduction of NV floats per thread over the row lanes
+// in-block reduction of NV floats per thread over the row lanes: a fixed binary tree (lane r adds
+// lane r + stride for stride = rl/2, rl/4, ... 1), so the association never depends on scheduling
 template <int NV>
 __device__ __forceinline__ void block_col_reduce(float (&acc)[NV], float* smem, int cvl, int cv_lane,
                                                  int row_lane, float* out /*[NV]*/, bool& owner) {
   const int rl = 256 / cvl;
-  owner = false;
+  owner = row_lane == 0;
   // smem layout [row_lane][cv_lane][NV]
+  float* mine = smem + (row_lane * cvl + cv_lane) * NV;
 #pragma unroll
-  for (int k = 0; k < NV; ++k) smem[(row_lane * cvl + cv_lane) * NV + k] = acc[k];
+  for (int k = 0; k < NV; ++k) mine[k] = acc[k];
   __syncthreads();
-  if (row_lane == 0) {
-    owner = true;
+  for (int stride = rl >> 1; stride > 0; stride >>= 1) {
+    if (row_lane < stride) {
+      const float* other = smem + ((row_lane + stride) * cvl + cv_lane) * NV;
 #pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      float s = 0.f;
-      for (int r = 0; r < rl; ++r) s += smem[(r * cvl + cv_lane) * NV + k];
-      out[k] = s;
+      for (int k = 0; k < NV; ++k) mine[k] += other[k];
     }
+    __syncthreads();
+  }
+  if (owner) {
+#pragma unroll
+    for (int k = 0; k < NV; ++k) out[k] = mine[k];
   }
   __syncthreads();
 }
@@ -609,26 +614,30 @@ __global__ void transpose_weights_kernel(const T* __restrict__ wc, T* __restrict
   }
 }
 
-// out[j] = sum_s part[s*stride + j]   (ordered second stage of split reductions).
-// Block = 32 outputs x 8 split lanes: lane l adds splits l, l+8, ... in order, then the 8 lane
+// out[j] = sum_s part[s*stride + j]   (ordered second stage of split reductions); n % 4 == 0.
+// Block = 32 float4 outputs x 8 split lanes: lane l adds splits l, l+8, ... in order, then the 8 lane
 // sums are added in order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ part,
                                                            float* __restrict__ out, long n, int splits,
                                                            long stride) {
-  __shared__ float red[8][32];
+  __shared__ float4 red[8][32];
   const int o = threadIdx.x & 31, l = threadIdx.x >> 5;
-  for (long base = (long)blockIdx.x * 32; base < n; base += (long)gridDim.x * 32) {
+  const long n4 = n / 4;
+  for (long base = (long)blockIdx.x * 32; base < n4; base += (long)gridDim.x * 32) {
     const long i = base + o;
-    float s = 0.f;
-    if (i < n)
-      for (int k = l; k < splits; k += 8) s += part[(long)k * stride + i];
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < n4)
+      for (int k = l; k < splits; k += 8) {
+        const float4 v = *reinterpret_cast<const float4*>(part + (long)k * stride + i * 4);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+      }
     red[l][o] = s;
     __syncthreads();
-    if (l == 0 && i < n) {
-      float t = 0.f;
+    if (l == 0 && i < n4) {
+      float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int k = 0; k < 8; ++k) t += red[k][o];
-      out[i] = t;
+      for (int k = 0; k < 8; ++k) { t.x += red[k][o].x; t.y += red[k][o].y; t.z += red[k][o].z; t.w += red[k][o].w; }
+      *reinterpret_cast<float4*>(out + i * 4) = t;
     }
     __syncthreads();
   }
@@ -710,9 +719,10 @@ __global__ void dw_dgrad_kernel(const T* __restrict__ dy, const WT* __restrict__
   }
 }
 
-// dW[r][t][c] = sum over output pixels dY * X(shifted).  grid = (slabs, chunks, k):
-// blockIdx.z picks the tap row r; each thread keeps k x 8 accumulators.
-template <class T, int KMAX>
+// dW[r][t][c] = sum over output pixels dY * X(shifted).  ROWS tap rows per block: 3x3 filters keep all
+// 9 x 8 accumulators in registers and read dY / X once; larger filters take one tap row per
+// blockIdx.z (grid = (slabs, chunks, k / ROWS)).
+template <class T, int KMAX, int ROWS>
 __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                        float* __restrict__ part, int N, int H, int W,
                                                        int P, int Q, int Cp, int k, int stride, int pad,
@@ -721,49 +731,56 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy,
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
   const int cv = blockIdx.x * g.cvl + cv_lane;
-  const int r = blockIdx.z;
+  const int rbase = blockIdx.z * ROWS;
   const long M = (long)N * P * Q;
   const long r0 = blockIdx.y * g.rows_per_chunk;
   const long r1 = min(M, r0 + g.rows_per_chunk);
-  float acc[KMAX][8];
+  float acc[ROWS][KMAX][8];
 #pragma unroll
-  for (int t = 0; t < KMAX; ++t)
+  for (int a = 0; a < ROWS; ++a)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
+    for (int t = 0; t < KMAX; ++t)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[a][t][e] = 0.f;
   if (cv < ncv)
     for (long m = r0 + row_lane; m < r1; m += rl) {
       long pix = m;
       const int q = (int)(pix % Q); pix /= Q;
       const int p = (int)(pix % P);
       const int n = (int)(pix / P);
-      const int h = p * stride + r - pad;
-      if (h < 0 || h >= H) continue;
       float d[8];
       IO<T>::ld(dy + (m * ncv + cv) * 8, d);
 #pragma unroll
-      for (int t = 0; t < KMAX; ++t) {
-        const int ww = q * stride + t - pad;
-        if (t < k && ww >= 0 && ww < W) {
-          float v[8];
-          IO<T>::ld(x + ((((long)n * H + h) * W + ww) * ncv + cv) * 8, v);
+      for (int a = 0; a < ROWS; ++a) {
+        const int h = p * stride + rbase + a - pad;
+        if (rbase + a >= k || h < 0 || h >= H) continue;
 #pragma unroll
-          for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(d[e], v[e], acc[t][e]);
+        for (int t = 0; t < KMAX; ++t) {
+          const int ww = q * stride + t - pad;
+          if (t < k && ww >= 0 && ww < W) {
+            float v[8];
+            IO<T>::ld(x + ((((long)n * H + h) * W + ww) * ncv + cv) * 8, v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[a][t][e] = fmaf(d[e], v[e], acc[a][t][e]);
+          }
         }
       }
     }
-  // ordered reduction over the row lanes, one tap at a time
+  // tree reduction over the row lanes, one tap at a time
 #pragma unroll
-  for (int t = 0; t < KMAX; ++t) {
-    if (t >= k) break;
-    float out[8];
-    bool owner;
-    block_col_reduce<8>(acc[t], smem, g.cvl, cv_lane, row_lane, out, owner);
-    if (owner && cv < ncv) {
-      float* p = part + ((long)blockIdx.y * k * k + r * k + t) * Cp + cv * 8;
+  for (int a = 0; a < ROWS; ++a)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) p[e] = out[e];
+    for (int t = 0; t < KMAX; ++t) {
+      if (rbase + a >= k || t >= k) continue;   // uniform over the block
+      float out[8];
+      bool owner;
+      block_col_reduce<8>(acc[a][t], smem, g.cvl, cv_lane, row_lane, out, owner);
+      if (owner && cv < ncv) {
+        float* p = part + ((long)blockIdx.y * k * k + (rbase + a) * k + t) * Cp + cv * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p[e] = out[e];
+      }
     }
-  }
 }
 
 }  // namespace pbd

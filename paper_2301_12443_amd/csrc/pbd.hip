@@ -189,7 +189,9 @@ ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 512) 
   const int rl = 256 / cvl;
   long chunks = (M + (long)rl * rows_per_thread - 1) / ((long)rl * rows_per_thread);
   const long cap = std::max(1, max_blocks / g.slabs);
-  chunks = std::max(1L, std::min(chunks, cap));
+  // small tensors: rather fewer rows per thread than idle compute units
+  const long want = std::min<long>((M + rl - 1) / rl, (256 + g.slabs - 1) / g.slabs);
+  chunks = std::max(std::max(1L, want), std::min(chunks, cap));
   g.rows_per_chunk = (M + chunks - 1) / chunks;
   g.chunks = (int)((M + g.rows_per_chunk - 1) / g.rows_per_chunk);
   return g;
@@ -202,7 +204,7 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
   w.tiles_k = (K + w.T - 1) / w.T;
   w.tiles_j = (J + w.T - 1) / w.T;
   const long tiles = (long)w.tiles_k * w.tiles_j;
-  long splits = std::max(1L, 512 / tiles);
+  long splits = std::max(1L, 256 / tiles);
   const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
   splits = std::min(splits, max_by_mem);
   splits = std::min(splits, (M + w.BKP - 1) / w.BKP);
@@ -316,7 +318,7 @@ int plan(pbd_ctx* c) {
         const ColGrid g = col_grid(M, op.cout_p);
         need_red((size_t)g.chunks * 2 * op.cout_p * 4);
         if (op.dw) {
-          const ColGrid gw = col_grid(M, op.cout_p, 8, 768 / op.d.k);
+          const ColGrid gw = col_grid(M, op.cout_p, 8, op.d.k <= 3 ? 512 : 768 / op.d.k);
           need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
@@ -472,7 +474,7 @@ template <class T> struct Exec {
         }
         if (w.splits > 1) {
           ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
-          sum_partials_kernel<<<grid_for((long)op.wn, 32), 256, 0, st>>>(part, dw, (long)op.wn, w.splits, (long)op.wn);
+          sum_partials_kernel<<<grid_for((long)op.wn / 4, 32), 256, 0, st>>>(part, dw, (long)op.wn, w.splits, (long)op.wn);
         }
       }
     } else {
@@ -500,20 +502,19 @@ template <class T> struct Exec {
   void dw_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
     const int N = c->o.batch;
     const long M = (long)N * op.out.h * op.out.w;
-    const ColGrid g = col_grid(M, op.cout_p, 8, 768 / op.d.k);
-    dim3 grid(g.slabs, g.chunks, op.d.k);
+    const ColGrid g = col_grid(M, op.cout_p, 8, op.d.k <= 3 ? 512 : 768 / op.d.k);
     const size_t smem = 256 * 8 * sizeof(float);
     {
       ProfScope ps(c, "dw_wgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
       if (op.d.k <= 3)
-        dw_wgrad_kernel<T, 3><<<grid, 256, smem, st>>>(dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w,
-                                                       op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
+        dw_wgrad_kernel<T, 3, 3><<<dim3(g.slabs, g.chunks, 1), 256, smem, st>>>(
+            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
       else
-        dw_wgrad_kernel<T, 7><<<grid, 256, smem, st>>>(dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w,
-                                                       op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
+        dw_wgrad_kernel<T, 7, 1><<<dim3(g.slabs, g.chunks, op.d.k), 256, smem, st>>>(
+            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
     }
     ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
-    sum_partials_kernel<<<grid_for((long)op.wn, 32), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
+    sum_partials_kernel<<<grid_for((long)op.wn / 4, 32), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
   }
 
   // ---- joins / pool -------------------------------------------------------
