@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--config", default="vgg16_dsconv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--classes", action="store_true", help="also print the per-kernel-class table to stderr")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
+                    help="also run a plain device-to-device copy of this many MiB (a kernel of known "
+                         "traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU relay step only: run with --gpus 1 "
@@ -102,6 +105,13 @@ def main():
     if args.classes:
         for k, v in classes.items():
             print(f"{k:24s} {v}", file=sys.stderr)
+
+    if args.calibrate_copy:
+        src = torch.ones(args.calibrate_copy * 2**20 // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     rec = {
         "metric": "distillation samples/sec/GPU (full relay step)",

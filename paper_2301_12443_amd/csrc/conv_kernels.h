@@ -123,19 +123,6 @@ __global__ void conv_direct_wgrad_kernel(const T* __restrict__ dy, const T* __re
 // MFMA implicit GEMM: forward (MODE 0) and backward-data (MODE 1)
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-
-// Raw buffer descriptor over a whole tensor: a load whose byte offset lies outside [0, bytes) returns
-// zeros in hardware, which turns padding, ragged tiles and the reduction tail into plain offsets
-// (no branches, no selects).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t tensor_rsrc(const void* p, unsigned bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
-  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
-constexpr unsigned kOutOfRange = 0x80000000u;   // byte offset beyond any tensor (they are < 2^31 elements)
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // Generic view: Out[m][j] = sum_kk Agather(m, kk) * Bw[j][kk]

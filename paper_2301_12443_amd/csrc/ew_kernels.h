@@ -27,6 +27,20 @@ __device__ __forceinline__ uint32_t pack_bf2(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over a whole tensor: a load whose byte offset lies outside [0, bytes) returns
+// zeros in hardware, which turns padding, ragged tiles and the reduction tail into plain offsets
+// (no branches, no selects).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tensor_rsrc(const void* p, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+constexpr unsigned kOutOfRange = 0x80000000u;   // byte offset beyond any tensor (they are < 2^31 elements)
+
 template <class T> struct IO;
 template <> struct IO<float> {
   static __device__ __forceinline__ void ld(const float* p, float v[8]) {
@@ -49,6 +63,35 @@ template <> struct IO<bf16_t> {
     u.x = pack_bf2(v[0], v[1]); u.y = pack_bf2(v[2], v[3]);
     u.z = pack_bf2(v[4], v[5]); u.w = pack_bf2(v[6], v[7]);
     *reinterpret_cast<uint4*>(p) = u;
+  }
+};
+
+// Gathered 8-channel loads through a buffer descriptor: issue() only starts the load (an invalid
+// position becomes an out-of-range offset and reads as zeros), unpack() converts later, so that a
+// whole stencil of loads is in flight before the first use.
+template <class T> struct BufIO;
+template <> struct BufIO<bf16_t> {
+  typedef uint4 Raw;
+  static __device__ __forceinline__ Raw issue(__amdgpu_buffer_rsrc_t r, unsigned elem, bool ok) {
+    return buffer_load16(r, ok ? elem * 2u : kOutOfRange);
+  }
+  static __device__ __forceinline__ void unpack(const Raw& u, float v[8]) {
+    v[0] = bf_lo(u.x); v[1] = bf_hi(u.x); v[2] = bf_lo(u.y); v[3] = bf_hi(u.y);
+    v[4] = bf_lo(u.z); v[5] = bf_hi(u.z); v[6] = bf_lo(u.w); v[7] = bf_hi(u.w);
+  }
+};
+template <> struct BufIO<float> {
+  struct Raw { uint4 a, b; };
+  static __device__ __forceinline__ Raw issue(__amdgpu_buffer_rsrc_t r, unsigned elem, bool ok) {
+    Raw q;
+    q.a = buffer_load16(r, ok ? elem * 4u : kOutOfRange);
+    q.b = buffer_load16(r, ok ? elem * 4u + 16u : kOutOfRange);
+    return q;
+  }
+  static __device__ __forceinline__ void unpack(const Raw& u, float v[8]) {
+    v[0] = __uint_as_float(u.a.x); v[1] = __uint_as_float(u.a.y); v[2] = __uint_as_float(u.a.z);
+    v[3] = __uint_as_float(u.a.w); v[4] = __uint_as_float(u.b.x); v[5] = __uint_as_float(u.b.y);
+    v[6] = __uint_as_float(u.b.z); v[7] = __uint_as_float(u.b.w);
   }
 };
 
@@ -646,11 +689,16 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restri
 // ---------------------------------------------------------------------------
 // depthwise convolution, weights [k*k][Cp] (channel-last)
 // ---------------------------------------------------------------------------
-template <class T, class WT>
-__global__ void dw_fwd_kernel(const T* __restrict__ x, const WT* __restrict__ w, T* __restrict__ y,
-                              const float* __restrict__ a, const float* __restrict__ b, int act,
-                              int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad) {
+// Forward: one thread = 8 channels of one output pixel; all k*k taps are requested before the
+// first multiply.  KK = k*k.
+template <class T, int KK>
+__global__ __launch_bounds__(256) void dw_fwd_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                     T* __restrict__ y, const float* __restrict__ a,
+                                                     const float* __restrict__ b, int act, int N, int H, int W,
+                                                     int P, int Q, int ncv, int k, int stride, int pad,
+                                                     unsigned x_elems) {
   const long nvec = (long)N * P * Q * ncv;
+  const __amdgpu_buffer_rsrc_t xr = tensor_rsrc(x, x_elems * (unsigned)sizeof(T));
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
     const int cv = (int)(i % ncv);
     long pix = i / ncv;
@@ -660,15 +708,24 @@ __global__ void dw_fwd_kernel(const T* __restrict__ x, const WT* __restrict__ w,
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int r = 0; r < k; ++r) {
-      const int h = p * stride + r - pad;
-      if (h < 0 || h >= H) continue;
-      for (int t = 0; t < k; ++t) {
-        const int ww = q * stride + t - pad;
-        if (ww < 0 || ww >= W) continue;
+    constexpr int G = KK < 25 ? KK : 25;     // taps in flight at once (bounds the register footprint)
+#pragma unroll
+    for (int t0 = 0; t0 < KK; t0 += G) {
+      typename BufIO<T>::Raw raw[G];
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const int t = t0 + u;
+        const int r = t / k, s = t - r * k;    // k is uniform: scalar arithmetic after unrolling
+        const int h = p * stride + r - pad, ww = q * stride + s - pad;
+        const bool ok = t < KK && (unsigned)h < (unsigned)H && (unsigned)ww < (unsigned)W;
+        raw[u] = BufIO<T>::issue(xr, (unsigned)(((n * H + h) * W + ww) * ncv + cv) * 8u, ok);
+      }
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        if (t0 + u >= KK) continue;
         float v[8], f[8];
-        IO<T>::ld(x + ((((long)n * H + h) * W + ww) * ncv + cv) * 8, v);
-        IO<WT>::ld(w + ((long)(r * k + t) * ncv + cv) * 8, f);
+        BufIO<T>::unpack(raw[u], v);
+        IO<T>::ld(w + ((long)(t0 + u) * ncv + cv) * 8, f);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], f[e], acc[e]);
       }
@@ -681,11 +738,15 @@ __global__ void dw_fwd_kernel(const T* __restrict__ x, const WT* __restrict__ w,
   }
 }
 
-template <class T, class WT>
-__global__ void dw_dgrad_kernel(const T* __restrict__ dy, const WT* __restrict__ w, T* __restrict__ dx,
-                                int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad,
-                                int accumulate) {
+// Backward-data in gather form: dx[h,w] (+)= sum_taps dy[(h+pad-r)/st, (w+pad-s)/st] * w[r][s]
+template <class T, int KK>
+__global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dy, const T* __restrict__ w,
+                                                       T* __restrict__ dx, int N, int H, int W, int P, int Q,
+                                                       int ncv, int k, int stride, int pad, int accumulate,
+                                                       unsigned dy_elems) {
   const long nvec = (long)N * H * W * ncv;
+  const __amdgpu_buffer_rsrc_t dr = tensor_rsrc(dy, dy_elems * (unsigned)sizeof(T));
+  const int sh = stride == 2 ? 1 : 0, smask = stride - 1;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
     const int cv = (int)(i % ncv);
     long pix = i / ncv;
@@ -698,19 +759,25 @@ __global__ void dw_dgrad_kernel(const T* __restrict__ dy, const WT* __restrict__
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     }
-    for (int r = 0; r < k; ++r) {
-      const int ph = h + pad - r;
-      if (ph < 0 || ph % stride) continue;
-      const int p = ph / stride;
-      if (p >= P) continue;
-      for (int t = 0; t < k; ++t) {
-        const int qw = ww + pad - t;
-        if (qw < 0 || qw % stride) continue;
-        const int q = qw / stride;
-        if (q >= Q) continue;
+    constexpr int G = KK < 25 ? KK : 25;
+#pragma unroll
+    for (int t0 = 0; t0 < KK; t0 += G) {
+      typename BufIO<T>::Raw raw[G];
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        const int t = t0 + u;
+        const int r = t / k, s = t - r * k;
+        const int ph = h + pad - r, qw = ww + pad - s;
+        const int p = ph >> sh, q = qw >> sh;
+        const bool ok = t < KK && ((ph | qw) & smask) == 0 && (unsigned)p < (unsigned)P && (unsigned)q < (unsigned)Q;
+        raw[u] = BufIO<T>::issue(dr, (unsigned)(((n * P + p) * Q + q) * ncv + cv) * 8u, ok);
+      }
+#pragma unroll
+      for (int u = 0; u < G; ++u) {
+        if (t0 + u >= KK) continue;
         float d[8], f[8];
-        IO<T>::ld(dy + ((((long)n * P + p) * Q + q) * ncv + cv) * 8, d);
-        IO<WT>::ld(w + ((long)(r * k + t) * ncv + cv) * 8, f);
+        BufIO<T>::unpack(raw[u], d);
+        IO<T>::ld(w + ((long)(t0 + u) * ncv + cv) * 8, f);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = fmaf(d[e], f[e], acc[e]);
       }
@@ -721,12 +788,12 @@ __global__ void dw_dgrad_kernel(const T* __restrict__ dy, const WT* __restrict__
 
 // dW[r][t][c] = sum over output pixels dY * X(shifted).  ROWS tap rows per block: 3x3 filters keep all
 // 9 x 8 accumulators in registers and read dY / X once; larger filters take one tap row per
-// blockIdx.z (grid = (slabs, chunks, k / ROWS)).
+// blockIdx.z (grid = (slabs, chunks, k / ROWS)).  All taps of a pixel are requested before use.
 template <class T, int KMAX, int ROWS>
 __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                        float* __restrict__ part, int N, int H, int W,
                                                        int P, int Q, int Cp, int k, int stride, int pad,
-                                                       ColGrid g) {
+                                                       ColGrid g, unsigned x_elems) {
   extern __shared__ float smem[];
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
@@ -735,52 +802,64 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy,
   const long M = (long)N * P * Q;
   const long r0 = blockIdx.y * g.rows_per_chunk;
   const long r1 = min(M, r0 + g.rows_per_chunk);
-  float acc[ROWS][KMAX][8];
+  const __amdgpu_buffer_rsrc_t xr = tensor_rsrc(x, x_elems * (unsigned)sizeof(T));
+  float acc[ROWS][KMAX * 8];
 #pragma unroll
   for (int a = 0; a < ROWS; ++a)
 #pragma unroll
-    for (int t = 0; t < KMAX; ++t)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[a][t][e] = 0.f;
-  if (cv < ncv)
+    for (int t = 0; t < KMAX * 8; ++t) acc[a][t] = 0.f;
+  if (cv < ncv && r0 + row_lane < r1) {
+    // (n, p, q) of this thread's first row, then advanced by rl rows per step without divisions
+    long pix = r0 + row_lane;
+    int q = (int)(pix % Q); pix /= Q;
+    int p = (int)(pix % P);
+    int n = (int)(pix / P);
+    const int dq = rl % Q, dp = (rl / Q) % P, dn = rl / (Q * P);
     for (long m = r0 + row_lane; m < r1; m += rl) {
-      long pix = m;
-      const int q = (int)(pix % Q); pix /= Q;
-      const int p = (int)(pix % P);
-      const int n = (int)(pix / P);
+      typename BufIO<T>::Raw raw[ROWS][KMAX];
+#pragma unroll
+      for (int a = 0; a < ROWS; ++a)
+#pragma unroll
+        for (int t = 0; t < KMAX; ++t) {
+          const int h = p * stride + rbase + a - pad, ww = q * stride + t - pad;
+          const bool ok = rbase + a < k && t < k && (unsigned)h < (unsigned)H && (unsigned)ww < (unsigned)W;
+          raw[a][t] = BufIO<T>::issue(xr, (unsigned)(((n * H + h) * W + ww) * ncv + cv) * 8u, ok);
+        }
       float d[8];
       IO<T>::ld(dy + (m * ncv + cv) * 8, d);
 #pragma unroll
-      for (int a = 0; a < ROWS; ++a) {
-        const int h = p * stride + rbase + a - pad;
-        if (rbase + a >= k || h < 0 || h >= H) continue;
+      for (int a = 0; a < ROWS; ++a)
 #pragma unroll
         for (int t = 0; t < KMAX; ++t) {
-          const int ww = q * stride + t - pad;
-          if (t < k && ww >= 0 && ww < W) {
-            float v[8];
-            IO<T>::ld(x + ((((long)n * H + h) * W + ww) * ncv + cv) * 8, v);
+          float v[8];
+          BufIO<T>::unpack(raw[a][t], v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[a][t][e] = fmaf(d[e], v[e], acc[a][t][e]);
-          }
+          for (int e = 0; e < 8; ++e) acc[a][t * 8 + e] = fmaf(d[e], v[e], acc[a][t * 8 + e]);
         }
+      q += dq;
+      if (q >= Q) { q -= Q; ++p; }
+      p += dp;
+      if (p >= P) { p -= P; ++n; }
+      n += dn;
+    }
+  }
+  // tree reduction over the row lanes, one tap row (KMAX x 8 values) at a time
+#pragma unroll
+  for (int a = 0; a < ROWS; ++a) {
+    if (rbase + a >= k) continue;   // uniform over the block
+    float out[KMAX * 8];
+    bool owner;
+    block_col_reduce<KMAX * 8>(acc[a], smem, g.cvl, cv_lane, row_lane, out, owner);
+    if (owner && cv < ncv) {
+#pragma unroll
+      for (int t = 0; t < KMAX; ++t) {
+        if (t >= k) continue;
+        float* pp = part + ((long)blockIdx.y * k * k + (rbase + a) * k + t) * Cp + cv * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pp[e] = out[t * 8 + e];
       }
     }
-  // tree reduction over the row lanes, one tap at a time
-#pragma unroll
-  for (int a = 0; a < ROWS; ++a)
-#pragma unroll
-    for (int t = 0; t < KMAX; ++t) {
-      if (rbase + a >= k || t >= k) continue;   // uniform over the block
-      float out[8];
-      bool owner;
-      block_col_reduce<8>(acc[a][t], smem, g.cvl, cv_lane, row_lane, out, owner);
-      if (owner && cv < ncv) {
-        float* p = part + ((long)blockIdx.y * k * k + (rbase + a) * k + t) * Cp + cv * 8;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) p[e] = out[e];
-      }
-    }
+  }
 }
 
 }  // namespace pbd

@@ -146,6 +146,7 @@ bool parse_net(pbd_ctx* c, const int32_t* w, int nw, int& pos, int which, std::s
       if (o.type == OP_CBA) {
         if (o.nin != 1 || o.k < 1 || o.k > 7 || o.stride < 1 || o.stride > 2 || o.pad != o.k / 2 ||
             o.c_out < 1) { err = "unsupported convolution geometry"; return false; }
+        if (o.groups != 1 && o.k != 1 && o.k != 3 && o.k != 5 && o.k != 7) { err = "depthwise kernels are 1, 3, 5 or 7 wide"; return false; }
         if (o.groups != 1 && (o.groups != s.c || o.c_out != s.c)) { err = "groups must be 1 or C_in == C_out"; return false; }
         if (o.groups == 1 && o.c_out % 8) { err = "dense convolution needs C_out % 8 == 0"; return false; }
         out = {o.c_out, out_dim(s.h, o.k, o.stride, o.pad), out_dim(s.w, o.k, o.stride, o.pad)};
@@ -318,7 +319,7 @@ int plan(pbd_ctx* c) {
         const ColGrid g = col_grid(M, op.cout_p);
         need_red((size_t)g.chunks * 2 * op.cout_p * 4);
         if (op.dw) {
-          const ColGrid gw = col_grid(M, op.cout_p, 8, op.d.k <= 3 ? 512 : 768 / op.d.k);
+          const ColGrid gw = col_grid(M, op.cout_p, 16, op.d.k <= 3 ? 512 : 768 / op.d.k);
           need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
@@ -398,8 +399,8 @@ template <class T> struct Exec {
         IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                     op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0,
                     (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2), (unsigned)(op.wn * 2)};
-        ProfScope ps(c, a ? "conv_fwd_mfma_affine" : "conv_fwd_mfma", bytes, flops, net, blk, opi);
-        launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE);
+        launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE,
+                        bytes, flops);
       }
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
@@ -410,7 +411,7 @@ template <class T> struct Exec {
 
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
-                    const float* b, int act, int epi) {
+                    const float* b, int act, int epi, double bytes, double flops) {
     const IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred);
     const int nk = (g.Kred + IG_BK - 1) / IG_BK;
     g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
@@ -419,13 +420,25 @@ template <class T> struct Exec {
 #define PBD_IG(BM_, BN_, EPI_, OUT_) igemm_kernel<MODE, BM_, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, OUT_, a, b, act, g)
 #define PBD_IG_BN(BM_, EPI_, OUT_) do { if (cfg.BN == 128) PBD_IG(BM_, 128, EPI_, OUT_); else if (cfg.BN == 64) PBD_IG(BM_, 64, EPI_, OUT_); else PBD_IG(BM_, 32, EPI_, OUT_); } while (0)
 #define PBD_IG_BM(EPI_, OUT_) do { if (cfg.BM == 128) PBD_IG_BN(128, EPI_, OUT_); else PBD_IG_BN(64, EPI_, OUT_); } while (0)
+    // profile entries are named after the kernel instantiation, so that each maps to one symbol of
+    // a rocprofv3 kernel trace: igemm_<fwd|dgrad>_<BM>x<BN>_<epilogue>
+    static const char* const kEpi[] = {"store", "affine", "accum", "partial"};
+    char name[32];
+    snprintf(name, sizeof name, "igemm_%s_%dx%d_%s", MODE ? "dgrad" : "fwd", cfg.BM, cfg.BN, kEpi[grid.z > 1 ? 3 : epi]);
     if (grid.z > 1) {
-      PBD_IG_BM(EPI_PARTIAL, reinterpret_cast<bf16_t*>(red()));
+      {
+        ProfScope ps(c, name, bytes, flops, net, blk, opi);
+        PBD_IG_BM(EPI_PARTIAL, reinterpret_cast<bf16_t*>(red()));
+      }
       const long nvec = (long)g.M * g.NC / 8;
+      ProfScope ps(c, "splitk_epilogue", (double)nvec * 8 * (4.0 * grid.z + 2), 0, net, blk, opi);
       splitk_epilogue_kernel<<<grid_for(nvec), 256, 0, st>>>(red(), out, a, b, act, epi, nvec, g.NC / 8, (int)grid.z);
-    } else if (epi == EPI_AFFINE_ACT) PBD_IG_BM(EPI_AFFINE_ACT, out);
-    else if (epi == EPI_ACCUM) PBD_IG_BM(EPI_ACCUM, out);
-    else PBD_IG_BM(EPI_STORE, out);
+    } else {
+      ProfScope ps(c, name, bytes, flops, net, blk, opi);
+      if (epi == EPI_AFFINE_ACT) PBD_IG_BM(EPI_AFFINE_ACT, out);
+      else if (epi == EPI_ACCUM) PBD_IG_BM(EPI_ACCUM, out);
+      else PBD_IG_BM(EPI_STORE, out);
+    }
 #undef PBD_IG_BM
 #undef PBD_IG_BN
 #undef PBD_IG
@@ -442,9 +455,8 @@ template <class T> struct Exec {
         IgemmArgs g{N, op.out.h, op.out.w, op.d.c_out, op.in.h, op.in.w, op.cin_p, op.d.k, op.d.k,
                     op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out, 0,
                     (unsigned)((size_t)N * op.out.h * op.out.w * op.d.c_out * 2), (unsigned)(op.wn * 2)};
-        ProfScope ps(c, "conv_dgrad_mfma", bytes, flops, net, blk, opi);
         launch_igemm<1>(g, (const bf16_t*)dy, (const bf16_t*)wt, (bf16_t*)dx, nullptr, nullptr, 0,
-                        accumulate ? EPI_ACCUM : EPI_STORE);
+                        accumulate ? EPI_ACCUM : EPI_STORE, bytes, flops);
       }
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
@@ -468,7 +480,7 @@ template <class T> struct Exec {
         dim3 grid(w.tiles_k, w.tiles_j, w.splits);
         float* part = w.splits == 1 ? dw : red();
         {
-          ProfScope ps(c, "conv_wgrad_mfma", bytes, flops, net, blk, opi);
+          ProfScope ps(c, w.T == 128 ? "wgrad_128x64" : "wgrad_64x128", bytes, flops, net, blk, opi);
           if (w.T == 128) wgrad_kernel<128, 64><<<grid, 256, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, part, g);
           else wgrad_kernel<64, 128><<<grid, 256, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, part, g);
         }
@@ -489,29 +501,37 @@ template <class T> struct Exec {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
     ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
-    dw_fwd_kernel<T, T><<<grid_for(nvec), 256, 0, st>>>(x, w, y, a, b, act, N, op.in.h, op.in.w, op.out.h, op.out.w,
-                                                        ncv, op.d.k, op.d.stride, op.d.pad);
+    const unsigned xe = (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p);
+#define PBD_DWF(KK_) dw_fwd_kernel<T, KK_><<<grid_for(nvec), 256, 0, st>>>(x, w, y, a, b, act, N, op.in.h, op.in.w, \
+    op.out.h, op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, xe)
+    if (op.d.k == 3) PBD_DWF(9); else if (op.d.k == 5) PBD_DWF(25); else if (op.d.k == 7) PBD_DWF(49); else PBD_DWF(1);
+#undef PBD_DWF
   }
   void dw_dgrad(const OpPlan& op, const T* dy, const T* w, T* dx, bool accumulate) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.in.h * op.in.w * ncv;
     ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
-    dw_dgrad_kernel<T, T><<<grid_for(nvec), 256, 0, st>>>(dy, w, dx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
-                                                          op.d.k, op.d.stride, op.d.pad, accumulate ? 1 : 0);
+    const unsigned de = (unsigned)((size_t)N * op.out.h * op.out.w * op.cout_p);
+#define PBD_DWD(KK_) dw_dgrad_kernel<T, KK_><<<grid_for(nvec), 256, 0, st>>>(dy, w, dx, N, op.in.h, op.in.w, op.out.h, \
+    op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, accumulate ? 1 : 0, de)
+    if (op.d.k == 3) PBD_DWD(9); else if (op.d.k == 5) PBD_DWD(25); else if (op.d.k == 7) PBD_DWD(49); else PBD_DWD(1);
+#undef PBD_DWD
   }
   void dw_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
     const int N = c->o.batch;
     const long M = (long)N * op.out.h * op.out.w;
-    const ColGrid g = col_grid(M, op.cout_p, 8, op.d.k <= 3 ? 512 : 768 / op.d.k);
-    const size_t smem = 256 * 8 * sizeof(float);
+    const ColGrid g = col_grid(M, op.cout_p, 16, op.d.k <= 3 ? 512 : 768 / op.d.k);
+    const size_t smem = 256 * 8 * sizeof(float) * (op.d.k <= 3 ? 3 : 7);
     {
       ProfScope ps(c, "dw_wgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
       if (op.d.k <= 3)
         dw_wgrad_kernel<T, 3, 3><<<dim3(g.slabs, g.chunks, 1), 256, smem, st>>>(
-            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
+            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
+            (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
       else
         dw_wgrad_kernel<T, 7, 1><<<dim3(g.slabs, g.chunks, op.d.k), 256, smem, st>>>(
-            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g);
+            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
+            (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
     }
     ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
     sum_partials_kernel<<<grid_for((long)op.wn / 4, 32), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
