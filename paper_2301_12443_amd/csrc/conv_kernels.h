@@ -142,7 +142,9 @@ struct IgemmArgs {
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
 enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 
-constexpr int IG_BK = 32, IG_PITCH = IG_BK + 8;
+// LDS row pitch 96 B: both the MFMA fragment reads (row = lane%32, 16-byte chunk = lane/32) and the
+// staging writes (row = lane/4, chunk = lane%4) run at the full 128 B/clk with it (80 B makes the writes conflict)
+constexpr int IG_BK = 32, IG_PITCH = IG_BK + 16;
 
 template <int MODE, int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A,

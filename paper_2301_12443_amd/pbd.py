@@ -112,8 +112,8 @@ class Distiller:
         self.act_shapes = W.activation_shapes(wl)
 
     def __del__(self):
-        if getattr(self, "h", None):
-            lib().pbd_destroy(self.h)
+        if getattr(self, "h", None) and _lib is not None:   # (module globals are gone at interpreter exit)
+            _lib.pbd_destroy(self.h)
             self.h = None
 
     def _check(self, rc):
