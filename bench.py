@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="vgg16_dsconv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch the step's kernels one by one (for rocprofv3 --pmc runs)")
     ap.add_argument("--classes", action="store_true", help="also print the per-kernel-class table to stderr")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB (a kernel of known "
@@ -78,7 +80,7 @@ def main():
     import torch
     from paper_2301_12443_amd import pbd, workloads as W
     wl = W.CONFIGS[args.config]()
-    d = pbd.Distiller(wl)
+    d = pbd.Distiller(wl, no_graph=args.no_graph)
     d.bind("cuda:0")
     d.load_params()
     x = torch.from_numpy(W.make_input(wl)).cuda()       # resident in HBM before the timed region

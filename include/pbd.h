@@ -60,6 +60,9 @@ typedef struct {
   float bn_momentum;    /* rate of the student's running statistics */
   int32_t force_direct; /* nonzero: run every convolution with the plain direct kernels
                            (testing aid; the MFMA kernels are the default for bf16) */
+  int32_t no_graph;     /* nonzero: pbd_distill_step launches its kernels one by one instead of
+                           replaying a captured HIP graph (for callers that capture the call
+                           themselves, and for per-kernel hardware counters) */
 } pbd_opts;
 
 /* A borrowed view of an activation inside the workspace. */

@@ -414,6 +414,185 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Whole-column kernels for short matrices (M <= 4096 rows).  One block of 512 threads owns an
+// 8-channel slab over ALL rows and keeps its (at most 8) rows per thread in registers, so
+// statistics, their finalisation and the elementwise pass are one launch and one read instead of
+// three launches and two reads: at these sizes the launches, not the bytes, are the cost.
+// ---------------------------------------------------------------------------
+constexpr int kSmallThreads = 512;                   // 8 waves: up to 256 registers per thread
+constexpr int kSmallRows = 8;                        // rows per thread
+
+// consecutive slabs go to the same XCD (blocks are dealt round-robin over 8 XCDs), so each cache
+// line of a row is pulled into one L2 only
+__device__ __forceinline__ int xcd_slab(int b, int nslab) {
+  return (nslab & 7) == 0 ? (b & 7) * (nslab >> 3) + (b >> 3) : b;
+}
+
+// Sum of 16 per-thread values over the block, result in every thread.  In the wave: a
+// reduce-scatter butterfly (exchange half of the values with lane^32, a quarter with lane^16, ...:
+// 17 cross-lane moves instead of 96), float.  Across the waves: added in order, in double (BN
+// backward subtracts these means from the gradient and what is left feeds weight gradients whose
+// own sum cancels, so the totals want more than float).  A fixed association throughout.
+__device__ __forceinline__ void block_sum16(const float (&v)[16], double (&out)[16], float (*red)[16], double* tot) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float w8[8], w4[4], w2[2], w1;
+  const bool h32 = lane & 32, h16 = lane & 16, h8 = lane & 8, h4 = lane & 4;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) w8[i] = (h32 ? v[8 + i] : v[i]) + __shfl_xor(h32 ? v[i] : v[8 + i], 32, 64);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w4[i] = (h16 ? w8[4 + i] : w8[i]) + __shfl_xor(h16 ? w8[i] : w8[4 + i], 16, 64);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) w2[i] = (h8 ? w4[2 + i] : w4[i]) + __shfl_xor(h8 ? w4[i] : w4[2 + i], 8, 64);
+  w1 = (h4 ? w2[1] : w2[0]) + __shfl_xor(h4 ? w2[0] : w2[1], 4, 64);
+  w1 += __shfl_xor(w1, 2, 64);
+  w1 += __shfl_xor(w1, 1, 64);
+  if ((lane & 3) == 0) red[wave][(h32 ? 8 : 0) + (h16 ? 4 : 0) + (h8 ? 2 : 0) + (h4 ? 1 : 0)] = w1;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    double t = (double)red[0][threadIdx.x];
+#pragma unroll 1
+    for (int w = 1; w < kSmallThreads / 64; ++w) t += (double)red[w][threadIdx.x];
+    tot[threadIdx.x] = t;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 16; ++k) out[k] = tot[k];
+}
+
+// y -> batch statistics (pivot-shifted sums as in bn_stats_kernel), running statistics, then
+// z = act((y - mean) * (gamma*invstd) + beta)
+template <class T>
+__global__ __launch_bounds__(kSmallThreads) void bn_small_fwd_kernel(
+    const T* __restrict__ y, T* __restrict__ z, const float* __restrict__ gamma, const float* __restrict__ beta,
+    float* __restrict__ mean, float* __restrict__ invstd, float* __restrict__ rmean, float* __restrict__ rvar,
+    int M, int Cp, float eps, float rho, int act, unsigned bytes) {
+  __shared__ float red[kSmallThreads / 64][16];
+  __shared__ double tot[16];
+  const int ncv = Cp / 8, cv = xcd_slab(blockIdx.x, ncv), tid = threadIdx.x;
+  const __amdgpu_buffer_rsrc_t ry = tensor_rsrc(y, bytes);
+  typename BufIO<T>::Raw raw[kSmallRows];
+#pragma unroll
+  for (int u = 0; u < kSmallRows; ++u) {
+    const int r = u * kSmallThreads + tid;
+    raw[u] = BufIO<T>::issue(ry, (unsigned)(r * ncv + cv) * 8u, r < M);
+  }
+  float piv[8];
+  IO<T>::ld(y + (long)cv * 8, piv);
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+#pragma unroll
+  for (int u = 0; u < kSmallRows; ++u) {
+    const bool ok = u * kSmallThreads + tid < M;
+    float v[8];
+    BufIO<T>::unpack(raw[u], v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float d = ok ? v[k] - piv[k] : 0.f;
+      acc[k] += d;
+      acc[8 + k] = fmaf(d, d, acc[8 + k]);
+    }
+  }
+  double sum[16];
+  block_sum16(acc, sum, red, tot);
+  float mu[8], a[8], b[8];
+  const double m = (double)M;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int c = cv * 8 + k;
+    const double shift = sum[k] / m;
+    const double mean_d = (double)piv[k] + shift;
+    double var = sum[8 + k] / m - shift * shift;
+    if (var < 0.0) var = 0.0;
+    const float is = (float)(1.0 / sqrt(var + (double)eps));
+    mu[k] = (float)mean_d; a[k] = gamma[c] * is; b[k] = beta[c];
+    if (tid == 0) {
+      mean[c] = mu[k];
+      invstd[c] = is;
+      rmean[c] = (1.f - rho) * rmean[c] + rho * mu[k];
+      rvar[c] = (1.f - rho) * rvar[c] + rho * (float)(var * m / (m - 1.0));
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kSmallRows; ++u) {
+    const int r = u * kSmallThreads + tid;
+    if (r >= M) continue;
+    float v[8];
+    BufIO<T>::unpack(raw[u], v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = apply_act(fmaf(v[k] - mu[k], a[k], b[k]), act);
+    IO<T>::st(z + ((long)r * ncv + cv) * 8, v);
+  }
+}
+
+// BN backward in one launch: sums of dpre and dpre*xhat, the parameter gradients, then
+// dy = gamma*invstd*(dpre - dbeta/m - xhat*dgamma/m) over dz in place
+template <class T>
+__global__ __launch_bounds__(kSmallThreads) void bn_small_bwd_kernel(
+    T* dz, const T* __restrict__ y, const float* __restrict__ gamma, const float* __restrict__ beta,
+    const float* __restrict__ mean, const float* __restrict__ invstd, float* __restrict__ g_gamma,
+    float* __restrict__ g_beta, int M, int Cp, int act, unsigned bytes) {
+  __shared__ float red[kSmallThreads / 64][16];
+  __shared__ double tot[16];
+  const int ncv = Cp / 8, cv = xcd_slab(blockIdx.x, ncv), tid = threadIdx.x;
+  const __amdgpu_buffer_rsrc_t ry = tensor_rsrc(y, bytes), rd = tensor_rsrc(dz, bytes);
+  typename BufIO<T>::Raw rawd[kSmallRows], rawy[kSmallRows];
+#pragma unroll
+  for (int u = 0; u < kSmallRows; ++u) {
+    const int r = u * kSmallThreads + tid;
+    rawd[u] = BufIO<T>::issue(rd, (unsigned)(r * ncv + cv) * 8u, r < M);
+    rawy[u] = BufIO<T>::issue(ry, (unsigned)(r * ncv + cv) * 8u, r < M);
+  }
+  float mu[8], a[8], b[8], is[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    const int c = cv * 8 + k;
+    mu[k] = mean[c]; is[k] = invstd[c]; a[k] = gamma[c] * is[k]; b[k] = beta[c];
+  }
+  float acc[16];
+#pragma unroll
+  for (int k = 0; k < 16; ++k) acc[k] = 0.f;
+#pragma unroll
+  for (int u = 0; u < kSmallRows; ++u) {
+    float d[8], v[8];                                // rows past M read as dz = 0: they add nothing
+    BufIO<T>::unpack(rawd[u], d);
+    BufIO<T>::unpack(rawy[u], v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float yc = v[k] - mu[k];
+      const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
+      acc[k] += dp;
+      acc[8 + k] = fmaf(dp, yc * is[k], acc[8 + k]);
+    }
+  }
+  double sum[16];
+  block_sum16(acc, sum, red, tot);
+  float c2[8], c3[8];
+  const double m = (double)M;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    c2[k] = (float)(sum[k] / m);
+    c3[k] = (float)(sum[8 + k] / m);
+    if (tid == 0) { g_beta[cv * 8 + k] = (float)sum[k]; g_gamma[cv * 8 + k] = (float)sum[8 + k]; }
+  }
+#pragma unroll
+  for (int u = 0; u < kSmallRows; ++u) {
+    const int r = u * kSmallThreads + tid;
+    if (r >= M) continue;
+    float d[8], v[8];
+    BufIO<T>::unpack(rawd[u], d);
+    BufIO<T>::unpack(rawy[u], v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float yc = v[k] - mu[k];
+      const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
+      d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
+    }
+    IO<T>::st(dz + ((long)r * ncv + cv) * 8, d);
+  }
+}
+
+// ---------------------------------------------------------------------------
 // max-pool; idx keeps the window position r*k+t of the first maximum
 // ---------------------------------------------------------------------------
 template <class T>

@@ -8,6 +8,7 @@
 //             A_{i-1}), and the SGD-momentum update straight after (Sec. IV-B).
 // Everything is enqueued on the caller's stream; the library owns no device memory.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <cmath>
@@ -15,6 +16,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "../../include/pbd.h"
@@ -94,6 +96,7 @@ struct pbd_ctx {
   bool graph_tried = false;
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
+  hipEvent_t pend_start = nullptr, pend_stop = nullptr;   // events waiting for the next launch
   std::vector<pbd_prof_entry> prof;
 };
 
@@ -370,10 +373,27 @@ struct ProfScope {
     c->prof.push_back(e);
     const size_t need = c->prof.size() * 2;
     while (c->ev.size() < need) { hipEvent_t ev; (void)hipEventCreate(&ev); c->ev.push_back(ev); }
-    (void)hipEventRecord(c->ev[need - 2], c->stream);
+    c->pend_start = c->ev[need - 2]; c->pend_stop = c->ev[need - 1];   // the scope's first launch takes them
   }
-  ~ProfScope() { if (on) (void)hipEventRecord(c->ev[c->prof.size() * 2 - 1], c->stream); }
+  ~ProfScope() { if (on) c->pend_start = c->pend_stop = nullptr; }
 };
+
+// Launch through one place.  A profiled launch attaches its two events to the dispatch itself, so
+// their distance is the kernel's own run time (what a kernel trace reports), not the gap between
+// two markers in the stream.  The lambda converts every argument to the kernel's parameter type.
+template <class... KA, class... A>
+inline void launch(pbd_ctx* c, void (*kern)(KA...), dim3 grid, dim3 block, size_t smem, hipStream_t st, A&&... a) {
+  static_assert(sizeof...(KA) == sizeof...(A), "argument count differs from the kernel's");
+  [&](KA... ka) {
+    void* argv[] = {(void*)&ka...};
+    if (c->pend_start) {
+      (void)hipExtLaunchKernel((const void*)kern, grid, block, argv, smem, st, c->pend_start, c->pend_stop, 0);
+      c->pend_start = c->pend_stop = nullptr;
+    } else {
+      (void)hipLaunchKernel((const void*)kern, grid, block, argv, smem, st);
+    }
+  }(std::forward<A>(a)...);
+}
 
 template <class T> struct Exec {
   pbd_ctx* c;
@@ -388,6 +408,8 @@ template <class T> struct Exec {
   float* red() const { return wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
+  // few enough rows for the whole-column kernels (one block per 8-channel slab)
+  static bool short_column(long M) { return M <= (long)kSmallThreads * kSmallRows; }
 
   // ---- convolution forward (dense) --------------------------------------
   void conv_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
@@ -405,7 +427,7 @@ template <class T> struct Exec {
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
       ProfScope ps(c, "conv_fwd_direct", bytes, flops, net, blk, opi);
-      conv_direct_fwd_kernel<T, T><<<grid_for((long)g.N * g.P * g.Q * g.K), 256, 0, st>>>(x, w, y, a, b, act, g);
+      launch(c, conv_direct_fwd_kernel<T, T>, grid_for((long)g.N * g.P * g.Q * g.K), 256, 0, st, x, w, y, a, b, act, g);
     }
   }
 
@@ -417,7 +439,7 @@ template <class T> struct Exec {
     g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
     dim3 grid((g.M + cfg.BM - 1) / cfg.BM, (g.NC + cfg.BN - 1) / cfg.BN,
               (nk + g.ksteps_per_split - 1) / g.ksteps_per_split);
-#define PBD_IG(BM_, BN_, EPI_, OUT_) igemm_kernel<MODE, BM_, BN_, EPI_><<<grid, 256, 0, st>>>(A, Bw, OUT_, a, b, act, g)
+#define PBD_IG(BM_, BN_, EPI_, OUT_) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g)
 #define PBD_IG_BN(BM_, EPI_, OUT_) do { if (cfg.BN == 128) PBD_IG(BM_, 128, EPI_, OUT_); else if (cfg.BN == 64) PBD_IG(BM_, 64, EPI_, OUT_); else PBD_IG(BM_, 32, EPI_, OUT_); } while (0)
 #define PBD_IG_BM(EPI_, OUT_) do { if (cfg.BM == 128) PBD_IG_BN(128, EPI_, OUT_); else PBD_IG_BN(64, EPI_, OUT_); } while (0)
     // profile entries are named after the kernel instantiation, so that each maps to one symbol of
@@ -432,7 +454,7 @@ template <class T> struct Exec {
       }
       const long nvec = (long)g.M * g.NC / 8;
       ProfScope ps(c, "splitk_epilogue", (double)nvec * 8 * (4.0 * grid.z + 2), 0, net, blk, opi);
-      splitk_epilogue_kernel<<<grid_for(nvec), 256, 0, st>>>(red(), out, a, b, act, epi, nvec, g.NC / 8, (int)grid.z);
+      launch(c, splitk_epilogue_kernel, grid_for(nvec), 256, 0, st, red(), out, a, b, act, epi, nvec, g.NC / 8, (int)grid.z);
     } else {
       ProfScope ps(c, name, bytes, flops, net, blk, opi);
       if (epi == EPI_AFFINE_ACT) PBD_IG_BM(EPI_AFFINE_ACT, out);
@@ -461,7 +483,7 @@ template <class T> struct Exec {
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
       ProfScope ps(c, "conv_dgrad_direct", bytes, flops, net, blk, opi);
-      conv_direct_dgrad_kernel<T, T><<<grid_for((long)g.N * g.H * g.W * g.C), 256, 0, st>>>(dy, w, dx, accumulate, g);
+      launch(c, conv_direct_dgrad_kernel<T, T>, grid_for((long)g.N * g.H * g.W * g.C), 256, 0, st, dy, w, dx, accumulate, g);
     }
   }
 
@@ -481,18 +503,18 @@ template <class T> struct Exec {
         float* part = w.splits == 1 ? dw : red();
         {
           ProfScope ps(c, w.T == 128 ? "wgrad_128x64" : "wgrad_64x128", bytes, flops, net, blk, opi);
-          if (w.T == 128) wgrad_kernel<128, 64><<<grid, 256, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, part, g);
-          else wgrad_kernel<64, 128><<<grid, 256, 0, st>>>((const bf16_t*)dy, (const bf16_t*)x, part, g);
+          if (w.T == 128) launch(c, wgrad_kernel<128, 64>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g);
+          else launch(c, wgrad_kernel<64, 128>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g);
         }
         if (w.splits > 1) {
           ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
-          sum_partials_kernel<<<grid_for((long)op.wn / 4, 32), 256, 0, st>>>(part, dw, (long)op.wn, w.splits, (long)op.wn);
+          launch(c, sum_partials_kernel, grid_for((long)op.wn / 4, 32), 256, 0, st, part, dw, (long)op.wn, w.splits, (long)op.wn);
         }
       }
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
       ProfScope ps(c, "conv_wgrad_direct", bytes, flops, net, blk, opi);
-      conv_direct_wgrad_kernel<T><<<grid_for((long)op.wn, 64), 64, 0, st>>>(dy, x, dw, g);
+      launch(c, conv_direct_wgrad_kernel<T>, grid_for((long)op.wn, 64), 64, 0, st, dy, x, dw, g);
     }
   }
 
@@ -502,7 +524,7 @@ template <class T> struct Exec {
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
     ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
     const unsigned xe = (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p);
-#define PBD_DWF(KK_) dw_fwd_kernel<T, KK_><<<grid_for(nvec), 256, 0, st>>>(x, w, y, a, b, act, N, op.in.h, op.in.w, \
+#define PBD_DWF(KK_) launch(c, dw_fwd_kernel<T, KK_>, grid_for(nvec), 256, 0, st, x, w, y, a, b, act, N, op.in.h, op.in.w, \
     op.out.h, op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, xe)
     if (op.d.k == 3) PBD_DWF(9); else if (op.d.k == 5) PBD_DWF(25); else if (op.d.k == 7) PBD_DWF(49); else PBD_DWF(1);
 #undef PBD_DWF
@@ -512,7 +534,7 @@ template <class T> struct Exec {
     const long nvec = (long)N * op.in.h * op.in.w * ncv;
     ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
     const unsigned de = (unsigned)((size_t)N * op.out.h * op.out.w * op.cout_p);
-#define PBD_DWD(KK_) dw_dgrad_kernel<T, KK_><<<grid_for(nvec), 256, 0, st>>>(dy, w, dx, N, op.in.h, op.in.w, op.out.h, \
+#define PBD_DWD(KK_) launch(c, dw_dgrad_kernel<T, KK_>, grid_for(nvec), 256, 0, st, dy, w, dx, N, op.in.h, op.in.w, op.out.h, \
     op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, accumulate ? 1 : 0, de)
     if (op.d.k == 3) PBD_DWD(9); else if (op.d.k == 5) PBD_DWD(25); else if (op.d.k == 7) PBD_DWD(49); else PBD_DWD(1);
 #undef PBD_DWD
@@ -525,29 +547,29 @@ template <class T> struct Exec {
     {
       ProfScope ps(c, "dw_wgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
       if (op.d.k <= 3)
-        dw_wgrad_kernel<T, 3, 3><<<dim3(g.slabs, g.chunks, 1), 256, smem, st>>>(
+        launch(c, dw_wgrad_kernel<T, 3, 3>, dim3(g.slabs, g.chunks, 1), 256, smem, st, 
             dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
             (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
       else
-        dw_wgrad_kernel<T, 7, 1><<<dim3(g.slabs, g.chunks, op.d.k), 256, smem, st>>>(
+        launch(c, dw_wgrad_kernel<T, 7, 1>, dim3(g.slabs, g.chunks, op.d.k), 256, smem, st, 
             dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
             (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
     }
     ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
-    sum_partials_kernel<<<grid_for((long)op.wn / 4, 32), 256, 0, st>>>(red(), dw, (long)op.wn, g.chunks, (long)op.wn);
+    launch(c, sum_partials_kernel, grid_for((long)op.wn / 4, 32), 256, 0, st, red(), dw, (long)op.wn, g.chunks, (long)op.wn);
   }
 
   // ---- joins / pool -------------------------------------------------------
   void join_fwd(const OpPlan& op, const Join& j, T* z) {
     const long nvec = (long)c->o.batch * op.out.h * op.out.w * op.cout_p / 8;
     ProfScope ps(c, "join_fwd", bytes_of(op.out) * (j.n + 1), 0, net, blk, opi);
-    join_fwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(j, z, nvec, op.d.act);
+    launch(c, join_fwd_kernel<T>, grid_for(nvec), 256, 0, st, j, z, nvec, op.d.act);
   }
   void pool_fwd(const OpPlan& op, const T* x, T* z, uint8_t* idx) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
     ProfScope ps(c, "maxpool_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
-    maxpool_fwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
+    launch(c, maxpool_fwd_kernel<T>, grid_for(nvec), 256, 0, st, x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
                                                           op.d.k, op.d.stride, op.d.pad);
   }
 
@@ -589,13 +611,13 @@ template <class T> struct Exec {
     for (BlockPlan& bp : c->net[0])
       for (OpPlan& op : bp.ops)
         if (op.d.type == OP_CBA)
-          bn_fold_kernel<<<(op.cout_p + 255) / 256, 256, 0, st>>>(wsf(op.t_gamma), wsf(op.t_beta), wsf(op.t_rmean),
+          launch(c, bn_fold_kernel, (op.cout_p + 255) / 256, 256, 0, st, wsf(op.t_gamma), wsf(op.t_beta), wsf(op.t_rmean),
                                                                   wsf(op.t_rvar), wsf(op.t_a), wsf(op.t_b), op.cout_p,
                                                                   c->o.bn_eps);
     c->fold_dirty = false;
   }
 
-  void set_lr(float lr) { set_scalar_kernel<<<1, 1, 0, st>>>(wsf(c->lr_off), lr); }
+  void set_lr(float lr) { launch(c, set_scalar_kernel, 1, 1, 0, st, wsf(c->lr_off), lr); }
 
   // everything a step needs that depends on the caller's pointers or on freshly loaded parameters
   void prepare(const float* x_dev) {
@@ -612,7 +634,7 @@ template <class T> struct Exec {
       const long nvec = (long)c->o.batch * s.h * s.w * round8(s.c) / 8;
       net = PBD_TEACHER; blk = -1; opi = -1;
       ProfScope ps(c, "cast_input", (double)c->o.batch * s.c * s.h * s.w * 4 + bytes_of(s), 0, net, blk, opi);
-      cast_input_kernel<T><<<grid_for(nvec), 256, 0, st>>>(x_dev, relay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
+      launch(c, cast_input_kernel<T>, grid_for(nvec), 256, 0, st, x_dev, relay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
     }
   }
   void relay_all(const float* x_dev) {
@@ -649,7 +671,7 @@ template <class T> struct Exec {
   // =========================================================================
   void refresh_compute_copies(BlockPlan& bp) {
     if constexpr (sizeof(T) == 2) {
-      cast_params_kernel<<<grid_for((long)bp.arena_elems / 4), 256, 0, st>>>(wsf(bp.master), (bf16_t*)ws(bp.wc),
+      launch(c, cast_params_kernel, grid_for((long)bp.arena_elems / 4), 256, 0, st, wsf(bp.master), (bf16_t*)ws(bp.wc),
                                                                              (long)bp.arena_elems / 4);
     }
     transpose_weights(bp);
@@ -659,7 +681,7 @@ template <class T> struct Exec {
     if (bp.ttable.empty()) return;
     ProfScope ps(c, "transpose_weights", 2.0 * bp.wt_elems * sizeof(T), 0, net, blk, -1);
     dim3 grid(64, (unsigned)bp.ttable.size());
-    transpose_weights_kernel<T><<<grid, 256, 0, st>>>(ws(bp.wc), ws(bp.wt),
+    launch(c, transpose_weights_kernel<T>, grid, 256, 0, st, ws(bp.wc), ws(bp.wt),
                                                       reinterpret_cast<const TransposeEntry*>(c->ws + bp.table));
   }
 
@@ -688,20 +710,27 @@ template <class T> struct Exec {
         if (op.dw) dw_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0);
         else conv_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0);
         const long M = (long)N * op.out.h * op.out.w;
-        const ColGrid g = col_grid(M, op.cout_p);
-        {
-          ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
-          bn_stats_kernel<T><<<dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st>>>(y, red(), M, op.cout_p, g);
-        }
-        bn_finalize_kernel<T><<<(op.cout_p + 15) / 16, 256, 0, st>>>(
-            red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
-            wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
-        {
-          const ColGrid ga = col_grid(M, op.cout_p, 32, 2048);
-          ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
-          bn_apply_kernel<T><<<dim3(ga.slabs, ga.chunks), 256, 0, st>>>(y, z, wsf(op.s_mean), wsf(op.s_invstd),
-                                                                     master + op.e_gamma, master + op.e_beta, M,
-                                                                     op.cout_p, op.d.act, ga);
+        if (short_column(M)) {
+          ProfScope ps(c, "bn_small_fwd", 3 * bytes_of(op.out), 0, net, blk, opi);
+          launch(c, bn_small_fwd_kernel<T>, op.cout_p / 8, kSmallThreads, 0, st, y, z, master + op.e_gamma,
+                 master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean), wsf(op.s_rvar), (int)M,
+                 op.cout_p, c->o.bn_eps, c->o.bn_momentum, op.d.act, (unsigned)(M * op.cout_p * sizeof(T)));
+        } else {
+          const ColGrid g = col_grid(M, op.cout_p);
+          {
+            ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
+            launch(c, bn_stats_kernel<T>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st, y, red(), M, op.cout_p, g);
+          }
+          launch(c, bn_finalize_kernel<T>, (op.cout_p + 15) / 16, 256, 0, st, 
+              red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
+              wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
+          {
+            const ColGrid ga = col_grid(M, op.cout_p, 32, 2048);
+            ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
+            launch(c, bn_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st, y, z, wsf(op.s_mean), wsf(op.s_invstd),
+                                                                       master + op.e_gamma, master + op.e_beta, M,
+                                                                       op.cout_p, op.d.act, ga);
+          }
         }
       } else if (op.d.type == OP_POOL) {
         pool_fwd(op, x, z, reinterpret_cast<uint8_t*>(c->ws + scr + op.idx));
@@ -724,8 +753,8 @@ template <class T> struct Exec {
       const int nb = (int)std::min<long>(kMseBlocks, (nvec + 255) / 256);
       opi = -1;
       ProfScope ps(c, "mse_loss_grad", 3 * bytes_of(s), 0, net, blk, opi);
-      mse_kernel<T><<<nb, 256, 0, st>>>(value(nval - 1), relay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
-      mse_final_kernel<<<1, 256, 0, st>>>(red(), nb, 1.0 / (double)numel, loss_dev);
+      launch(c, mse_kernel<T>, nb, 256, 0, st, value(nval - 1), relay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
+      launch(c, mse_final_kernel, 1, 256, 0, st, red(), nb, 1.0 / (double)numel, loss_dev);
     }
 
     // ---- backward ---------------------------------------------------------
@@ -740,22 +769,29 @@ template <class T> struct Exec {
       if (op.d.type == OP_CBA) {
         const T* y = ws(scr + op.y);
         const long M = (long)N * op.out.h * op.out.w;
-        const ColGrid g = col_grid(M, op.cout_p);
-        {
-          ProfScope ps(c, "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
-          bn_bwd_reduce_kernel<T><<<dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st>>>(
-              dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
-              op.d.act, g);
-        }
-        bn_bwd_finalize_kernel<<<(op.cout_p + 15) / 16, 256, 0, st>>>(red(), g.chunks, op.cout_p, (double)M,
-                                                                         grad + op.e_gamma, grad + op.e_beta,
-                                                                         wsf(op.s_k2), wsf(op.s_k3));
-        {
-          const ColGrid ga = col_grid(M, op.cout_p, 16, 2048);
-          ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
-          bn_bwd_apply_kernel<T><<<dim3(ga.slabs, ga.chunks), 256, 0, st>>>(
-              dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
-              wsf(op.s_k3), M, op.cout_p, op.d.act, ga);
+        if (short_column(M)) {
+          ProfScope ps(c, "bn_small_bwd", 5 * bytes_of(op.out), 0, net, blk, opi);
+          launch(c, bn_small_bwd_kernel<T>, op.cout_p / 8, kSmallThreads, 0, st, dz, y, master + op.e_gamma,
+                 master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), grad + op.e_gamma, grad + op.e_beta, (int)M,
+                 op.cout_p, op.d.act, (unsigned)(M * op.cout_p * sizeof(T)));
+        } else {
+          const ColGrid g = col_grid(M, op.cout_p);
+          {
+            ProfScope ps(c, "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
+            launch(c, bn_bwd_reduce_kernel<T>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st, 
+                dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
+                op.d.act, g);
+          }
+          launch(c, bn_bwd_finalize_kernel, (op.cout_p + 15) / 16, 256, 0, st, red(), g.chunks, op.cout_p, (double)M,
+                                                                           grad + op.e_gamma, grad + op.e_beta,
+                                                                           wsf(op.s_k2), wsf(op.s_k3));
+          {
+            const ColGrid ga = col_grid(M, op.cout_p, 16, 2048);
+            ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
+            launch(c, bn_bwd_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st, 
+                dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
+                wsf(op.s_k3), M, op.cout_p, op.d.act, ga);
+          }
         }
         const T* x = value(iv);
         if (op.dw) dw_wgrad(op, dz, x, grad + op.e_w);
@@ -770,7 +806,7 @@ template <class T> struct Exec {
           const int ncv = op.cout_p / 8;
           const long nvec = (long)N * op.in.h * op.in.w * ncv;
           ProfScope ps(c, "maxpool_bwd", bytes_of(op.in) + 1.5 * bytes_of(op.out), 0, net, blk, opi);
-          maxpool_bwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(dz, reinterpret_cast<const uint8_t*>(c->ws + scr + op.idx),
+          launch(c, maxpool_bwd_kernel<T>, grid_for(nvec), 256, 0, st, dz, reinterpret_cast<const uint8_t*>(c->ws + scr + op.idx),
                                                                 dvalue(iv), N, op.in.h, op.in.w, op.out.h, op.out.w,
                                                                 ncv, op.d.k, op.d.stride, op.d.pad, have[iv] ? 1 : 0);
           have[iv] = 1;
@@ -789,7 +825,7 @@ template <class T> struct Exec {
         if (live) {
           const long nvec = (long)N * op.out.h * op.out.w * op.cout_p / 8;
           ProfScope ps(c, "join_bwd", bytes_of(op.out) * (live + 1 + (op.d.act ? 1 : 0)), 0, net, blk, opi);
-          join_bwd_kernel<T><<<grid_for(nvec), 256, 0, st>>>(jn, dz, value(j + 1), nvec, op.d.act);
+          launch(c, join_bwd_kernel<T>, grid_for(nvec), 256, 0, st, jn, dz, value(j + 1), nvec, op.d.act);
         }
       }
     }
@@ -800,9 +836,9 @@ template <class T> struct Exec {
       const long n4 = (long)bp.arena_elems / 4;
       ProfScope ps(c, "sgd_momentum", (double)bp.arena_elems * (20 + (sizeof(T) == 2 ? 2 : 0)), 0, net, blk, opi);
       if constexpr (sizeof(T) == 2)
-        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, (bf16_t*)wc, n4, wsf(c->lr_off), c->o.momentum);
+        launch(c, sgd_momentum_kernel<bf16_t>, grid_for(n4), 256, 0, st, wsf(bp.master), wsf(bp.mom), grad, (bf16_t*)wc, n4, wsf(c->lr_off), c->o.momentum);
       else
-        sgd_momentum_kernel<bf16_t><<<grid_for(n4), 256, 0, st>>>(wsf(bp.master), wsf(bp.mom), grad, nullptr, n4, wsf(c->lr_off), c->o.momentum);
+        launch(c, sgd_momentum_kernel<bf16_t>, grid_for(n4), 256, 0, st, wsf(bp.master), wsf(bp.mom), grad, nullptr, n4, wsf(c->lr_off), c->o.momentum);
     }
     transpose_weights(bp);
     red_off = c->r_tred;
@@ -1170,7 +1206,7 @@ int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev
   // The body of the step touches only workspace addresses, so it is captured once into a HIP
   // graph and replayed: ~300 small launches per step would otherwise be bound by launch cost.
   // Capture needs a real stream and no profiling events; otherwise the kernels are launched directly.
-  const bool want_graph = c->stream != nullptr && !c->prof_on;
+  const bool want_graph = c->stream != nullptr && !c->prof_on && !c->o.no_graph;
   rc = dispatch(c, [&](auto& e) { e.set_lr(lr); e.prepare(x_dev); });
   if (rc) return rc;
   if (want_graph && !c->gexec && !c->graph_tried) {

@@ -28,7 +28,7 @@ SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd
 
 class pbd_opts(C.Structure):
     _fields_ = [("batch", C.c_int32), ("precision", C.c_int32), ("momentum", C.c_float),
-                ("bn_eps", C.c_float), ("bn_momentum", C.c_float), ("force_direct", C.c_int32)]
+                ("bn_eps", C.c_float), ("bn_momentum", C.c_float), ("force_direct", C.c_int32), ("no_graph", C.c_int32)]
 
 
 class pbd_tensor(C.Structure):
@@ -93,14 +93,16 @@ class Distiller:
     """A context for one workload.  `create` needs no GPU; `bind` and everything after do."""
 
     def __init__(self, wl: W.Workload, batch: int | None = None, precision: str | None = None,
-                 force_direct: bool = False, bn_eps: float = 1e-5, bn_momentum: float = 0.1):
+                 force_direct: bool = False, bn_eps: float = 1e-5, bn_momentum: float = 0.1,
+                 no_graph: bool = False):
         self.wl = wl
         self.batch = wl.batch if batch is None else batch
         self.precision = PBD_BF16 if (precision or wl.precision) == "bf16" else PBD_F32
         self.B = wl.B
         words, pool = W.pack(wl)
         self._words, self._pool = words, pool
-        opts = pbd_opts(self.batch, self.precision, wl.momentum, bn_eps, bn_momentum, int(force_direct))
+        opts = pbd_opts(self.batch, self.precision, wl.momentum, bn_eps, bn_momentum, int(force_direct),
+                        int(no_graph))
         h = C.c_void_p()
         rc = lib().pbd_create(words.ctypes.data_as(C.POINTER(C.c_int32)), words.size,
                               pool.ctypes.data_as(C.POINTER(C.c_double)), pool.size, C.byref(opts), C.byref(h))

@@ -16,12 +16,17 @@ def make_distiller(wl, batch=None, precision=None, force_direct=False):
 
 
 def compare_step(wl, batch=None, precision=None, force_direct=False, steps=1, order=None, log=None,
-                 storage=None, kink_floor=0.0, beta_shift=None):
-    """Returns {name: error} for activations, losses, gradients, weights, momentum, running stats."""
+                 storage=None, kink_floor=0.0, beta_shift=None, noise=False):
+    """Returns {name: error} for activations, losses, gradients, weights, momentum, running stats.
+
+    noise=True (with a storage-rounded oracle): also steps a plain fp64 oracle and reports, as
+    "<tensor>.noise", how far the storage rounding alone moves each gradient (oracle vs oracle)."""
     import torch
     batch = wl.batch if batch is None else batch
     d = make_distiller(wl, batch, precision, force_direct)
     o = make_oracle(wl, batch=batch, storage=storage)
+    o64 = make_oracle(wl, batch=batch) if noise else None
+    assert not (noise and (kink_floor or beta_shift is not None))
     if beta_shift is not None:
         # move every student pre-activation away from the rectifier kinks (same on both sides)
         for b in range(wl.B):
@@ -55,6 +60,9 @@ def compare_step(wl, batch=None, precision=None, force_direct=False, steps=1, or
                     raise AssertionError(f"block {i}: no kink-free input in 64 draws (margin {margin})")
             d.student_step(i, wl.lr)
             loss_o = o.student_step(i, acts[i - 1], acts[i], wl.lr)
+            if o64 is not None:
+                acts64 = o64.teacher_relay(x)
+                o64.student_step(i, acts64[i - 1], acts64[i], wl.lr)
             d.sync()
             loss_g = float(d.losses[b].item())
             errs[f"s{step}.loss{i}"] = abs(loss_g - loss_o) / abs(loss_o)
@@ -73,6 +81,9 @@ def compare_step(wl, batch=None, precision=None, force_direct=False, steps=1, or
                             den = max(np.max(np.abs(og(kind, W.P_GAMMA))), np.max(np.abs(og(kind, W.P_BETA))))
                         got = d.read_tensor(kind, 1, b, j, slot, shape)
                         errs[tag + nm] = float(np.max(np.abs(got - ref)) / den)
+                        if o64 is not None:
+                            ref64 = o64.get_tensor(kind, 1, b, j, slot, shape)
+                            errs[tag + nm + ".noise"] = float(np.max(np.abs(ref64 - ref)) / den)
                         if kind == pbd.PBD_GRAD and slot == W.P_WEIGHT:
                             errs[tag + ".l2g"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
                 ref = og(orc.KIND_PARAM)

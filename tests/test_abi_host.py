@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_header():
-    assert C.sizeof(pbd.pbd_opts) == 24
+    assert C.sizeof(pbd.pbd_opts) == 28
     assert C.sizeof(pbd.pbd_tensor) == 32
     assert C.sizeof(pbd.pbd_prof_entry) == 72
 

@@ -10,6 +10,8 @@ Tolerances (max-norm relative error per tensor, max|a-b| / max|b|):
     sides: a gradient summed over a kinked network is discontinuous in those decisions and
     the plain fp64 value is several percent away from ANY bf16-storage evaluation (see
     test_bf16_storage_conditioning in test_oracle_step.py for the oracle-only measurement).
+    Where that oracle-vs-oracle deviation of a gradient tensor exceeds 4e-2, the bound for the
+    tensor is half of it (see _assert_bf16_step).
 """
 import numpy as np
 import pytest
@@ -32,6 +34,27 @@ def _assert_all(errs, tol, keys=None):
     assert not bad, dict(list(sorted(bad.items(), key=lambda kv: -kv[1]))[:8])
 
 
+def _assert_bf16_step(errs):
+    """Losses, gradients, momentum and updated parameters of a bf16 step against the bf16-storage
+    oracle.  Which bf16 code a stored value rounds to is decided by the last float32 bit on the
+    GPU and in double by the oracle, so a handful of stored elements differ by one bf16 ulp and the
+    gradient moves with them; the size of that sensitivity is what the storage rounding itself does
+    to the same tensor (oracle vs oracle, ".noise").  Bound: the larger of 2e-2 and half of it."""
+    bad = {}
+    for k, v in errs.items():
+        if k.endswith(".noise") or ".A" in k:
+            continue
+        tol = TOL_BF16
+        for stem in (".grad", ".mom"):
+            if k.endswith(stem):
+                tol = max(tol, 0.5 * errs.get(k + ".noise", 0.0))
+        if k.endswith(".l2g"):
+            tol = max(tol, 0.5 * errs.get(k[:-4] + ".grad.noise", 0.0))
+        if not v < tol:
+            bad[k] = (v, tol)
+    assert not bad, dict(list(sorted(bad.items(), key=lambda kv: -kv[1][0]))[:8])
+
+
 SMALL = [W.tiny_cnn()] + pattern_workloads()
 
 
@@ -40,6 +63,21 @@ def test_f32_path_matches_fp64_oracle(wl):
     """Three consecutive steps (momentum and running statistics in play), every tensor."""
     errs = parity.compare_step(wl, precision="f32", steps=3, kink_floor=KINK_FLOOR)
     _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
+
+
+@pytest.mark.parametrize("precision", ["f32", "bf16"])
+def test_long_columns_take_the_chunked_bn_kernels(precision):
+    """Batch 96 gives the first blocks M = 24576 rows: above the whole-column limit (16384), so the
+    chunked statistics / finalize / apply kernels run, while the later blocks stay below it."""
+    wl = W.tiny_cnn()
+    if precision == "f32":
+        errs = parity.compare_step(wl, batch=96, precision="f32", steps=2, kink_floor=KINK_FLOOR)
+        _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
+    else:
+        plain = parity.compare_step(wl, batch=96, precision="bf16", steps=1)
+        _assert_all(plain, TOL_BF16, keys=(".A", ".loss"))
+        rounded = parity.compare_step(wl, batch=96, precision="bf16", steps=1, storage="bf16", noise=True)
+        _assert_bf16_step(rounded)
 
 
 def test_f32_block_order_is_irrelevant():
@@ -56,8 +94,9 @@ BF16_CASES = [(W.tiny_cnn(), None)] + [(w, None) for w in pattern_workloads()[:3
 def test_bf16_path_matches_oracle(wl, batch, direct):
     plain = parity.compare_step(wl, batch=batch, precision="bf16", force_direct=direct, steps=1)
     _assert_all(plain, TOL_BF16, keys=(".A", ".loss"))
-    rounded = parity.compare_step(wl, batch=batch, precision="bf16", force_direct=direct, steps=1, storage="bf16")
-    _assert_all(rounded, TOL_BF16, keys=(".loss", ".grad", ".mom", ".param", ".l2g"))
+    rounded = parity.compare_step(wl, batch=batch, precision="bf16", force_direct=direct, steps=1, storage="bf16",
+                                  noise=True)
+    _assert_bf16_step(rounded)
 
 
 def _gradient_deviation(wl, batch, get_a, get_b):
@@ -131,9 +170,12 @@ def test_configs_2_to_5_graphs_in_f32(name, batch, hw, shift):
     one flip moves every gradient upstream by percents.  The student's beta is therefore set to
     `shift` on both sides (pre-activations ~ N(shift, 1), inside the linear part of ReLU / ReLU6),
     which keeps the comparison elementwise; the kinks themselves are covered at beta = 0 by the
-    small workloads above, whose inputs are drawn clear of every kink."""
+    small workloads above, whose inputs are drawn clear of every kink.  Max-pool ties are not moved
+    by beta (two window elements within rounding of each other send the gradient to either
+    position), so each block's input is also redrawn until the oracle sees no such near-tie: at
+    |value| ~ 10 a float32 activation carries a few 1e-6 of rounding, hence the 1e-5 floor."""
     wl = W.CONFIGS[name](batch=batch, hw=hw, precision="f32")
-    errs = parity.compare_step(wl, batch=batch, precision="f32", steps=1, beta_shift=shift)
+    errs = parity.compare_step(wl, batch=batch, precision="f32", steps=1, beta_shift=shift, kink_floor=1e-5)
     # the last blocks normalise over as few as 16 samples per channel at these batch sizes and
     # BN backward amplifies float32 rounding accordingly: 5e-4 here, 1e-4 on the tiny config above
     _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, 5 * TOL_F32)

@@ -48,6 +48,26 @@ def test_full_size_step_is_deterministic_and_split_calls_agree(name):
         np.testing.assert_array_equal(ta, tb)
 
 
+def test_no_graph_option_gives_the_same_bits():
+    """The captured graph replays exactly the launches that no_graph issues one by one."""
+    import torch
+    wl = W.CONFIGS["vgg16_dsconv"]()
+    x = torch.from_numpy(W.make_input(wl)).cuda()
+    out = []
+    for no_graph in (False, True):
+        d = pbd.Distiller(wl, no_graph=no_graph)
+        d.bind("cuda:0"); d.load_params()
+        for _ in range(3):
+            d.distill_step(x, wl.lr)
+        d.sync()
+        assert d.uses_graph() == (not no_graph)
+        out.append((d.losses.cpu().numpy().copy(), _state(d, wl)))
+        del d
+    np.testing.assert_array_equal(out[0][0], out[1][0])
+    for ta, tb in zip(out[0][1], out[1][1]):
+        np.testing.assert_array_equal(ta, tb)
+
+
 def test_relay_views_and_shared_input():
     """S_i reads the very buffer T_i read: the view of A_{i-1} handed out by the relay."""
     import torch
@@ -95,18 +115,20 @@ def test_state_and_argument_errors_on_device():
     assert np.isfinite(loss.item())
 
 
-def test_profile_records_every_launch():
+@pytest.mark.parametrize("batch,bn", [(8, {"bn_small_fwd", "bn_small_bwd"}),
+                                      (96, {"bn_stats", "bn_apply", "bn_bwd_reduce", "bn_bwd_apply",
+                                            "bn_small_fwd", "bn_small_bwd"})])
+def test_profile_records_every_launch(batch, bn):
     import torch
     wl = W.tiny_cnn()
-    d = parity.make_distiller(wl, precision="bf16")
-    x = torch.from_numpy(W.make_input(wl)).cuda()
+    d = parity.make_distiller(wl, batch=batch, precision="bf16")
+    x = torch.from_numpy(W.make_input(wl, batch=batch)).cuda()
     d.distill_step(x, wl.lr)
     d.set_profile(True); d.reset_profile()
     d.distill_step(x, wl.lr)
     prof = d.get_profile()
     names = {p["name"] for p in prof}
-    assert {"cast_input", "bn_stats", "bn_apply", "mse_loss_grad", "bn_bwd_reduce", "bn_bwd_apply",
-            "sgd_momentum"} <= names
+    assert {"cast_input", "mse_loss_grad", "sgd_momentum"} | bn <= names
     for prefix in ("igemm_fwd_", "igemm_dgrad_", "wgrad_"):
         assert any(n.startswith(prefix) for n in names), (prefix, names)
     assert any(n.startswith("igemm_fwd_") and n.endswith("_affine") for n in names)      # teacher: fused BN + ReLU
