@@ -15,6 +15,19 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 
+# HBM bytes per launch (mean over a kernel class's launches in one step) from rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by what the same counter reads for a
+# 256 MiB copy (fetch x2.000, write x1.000); commands and the full table are in
+# profiles/vgg16_dsconv_step_hbm_traffic.md.  Counters cannot be read from inside the process, so
+# the figures are carried here and apply to the workload they were measured on only.
+HBM_TRAFFIC_PER_LAUNCH = {
+    "vgg16_dsconv": {
+        "dw_wgrad": 17085429, "bn_bwd_reduce": 30422306, "bn_bwd_apply": 45063308, "bn_stats": 15411621,
+        "bn_apply": 30080577, "sum_partials": 7965464, "dw_fwd": 26760444, "dw_dgrad": 33013179,
+        "bn_small_fwd": 5312642, "bn_small_bwd": 8057364,
+    },
+}
+
 
 def roofline_from_profile(prof, steps):
     """Aggregate the library's per-launch HIP-event timings by kernel class; report the class that
@@ -104,6 +117,7 @@ def main():
     prof = d.get_profile()
     d.set_profile(False)
     roof, classes = roofline_from_profile(prof, psteps)
+    roof["traffic"] = HBM_TRAFFIC_PER_LAUNCH.get(args.config, {}).get(roof["kernel"])
     if args.classes:
         for k, v in classes.items():
             print(f"{k:24s} {v}", file=sys.stderr)
