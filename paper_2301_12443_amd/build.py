@@ -15,6 +15,9 @@ HEADERS = [os.path.join(HERE, "csrc", "ew_kernels.h"), os.path.join(HERE, "csrc"
 def build_lib(verbose: bool = False) -> str:
     cmd = ["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # keep MFMA accumulators in ordinary VGPRs: without this the register allocator parks
+           # them in AGPRs and copies all of them in and out around the MFMAs of every K step
+           "-mllvm", "-amdgpu-mfma-vgpr-form",
            "-I" + os.path.join(ROOT, "include"), *SOURCES, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
