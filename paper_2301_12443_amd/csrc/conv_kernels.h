@@ -8,12 +8,12 @@
 //    forward, [C][R][S][K] for backward-data) so both operands are read from LDS
 //    with one 128-bit load per lane.  128 x BN x 32 tiles, 4 wavefronts of 64,
 //    LDS double buffering with register prefetch.
-//  * wgrad_kernel: backward-weight.  The reduction runs over pixels, which is the
-//    strided direction of NHWC memory, so every thread loads an 8 pixel x 8 channel
-//    block, transposes it in registers and stores reduction-contiguous rows to LDS
-//    (XOR-swizzled against bank conflicts).  The pixel range is split over
-//    workgroups; partial tiles go to scratch and are summed by an ordered second
-//    stage, so the result does not depend on scheduling.
+//  * wgrad_tr_kernel: backward-weight.  The reduction runs over pixels, which is the
+//    strided direction of NHWC memory; tiles go to LDS as they lie in memory and the
+//    gfx950 transposing LDS read (ds_read_b64_tr_b16) hands each lane its 8
+//    consecutive pixels of one channel.  The pixel range is split over workgroups;
+//    partial tiles go to scratch and are summed by an ordered second stage, so the
+//    result does not depend on scheduling.
 //  * direct kernels: plain one-thread-per-output loops in fp32, used for the
 //    float32 precision and as a cross-check of the MFMA kernels.
 #pragma once
@@ -375,146 +375,173 @@ __global__ void splitk_epilogue_kernel(const float* __restrict__ part, bf16_t* _
 }
 
 // ---------------------------------------------------------------------------
-// MFMA backward-weight:  dW[k][j] = sum_m dy[m][k] * Xgather(m, j),  j = (r*S+s)*C + c
-// Tile T x T outputs, BKP pixels per step; grid = (tiles_k, tiles_j, splits).
+// Weight gradient with the LDS transpose read of gfx950.
+//   dW[k][j] = sum_m dy[m][k] * xcol[m][j],  j = (r*S + s)*C + c
+// The reduction runs over pixels, the slow dimension of both operands, while an MFMA lane wants 8
+// consecutive reduction elements of ONE channel.  ds_read_b64_tr_b16 does that exchange inside the
+// LDS read: 16 lanes read a 4 (rows) x 16 (columns) block of 16-bit elements, source lane s giving
+// the address of row s/4, columns 4*(s%4)..+3, and lane i receives column i of the 4 rows.  So
+// tiles are staged exactly as they lie in memory (rows = pixels, channels contiguous; a plain
+// 16-byte copy per thread) and no register transpose is needed.
+//   LDS row pitch = tile width + 32 elements (64 bytes): the 4 rows of one read land on banks
+//   16 apart and the two 16-lane groups of a half wave 8 apart: conflict-free.
+// Pipeline: registers hold tile t+1 while tile t is multiplied; two LDS buffers, one barrier a step.
 // ---------------------------------------------------------------------------
-struct WgradArgs {
+struct WgradTrArgs {
   int N, H, W, C;     // x  [N][H][W][C]
   int P, Q, K;        // dy [N][P][Q][K]
   int R, S, stride, pad;
   int M;              // N*P*Q
   int J;              // R*S*C
-  int pix_per_split;  // multiple of BKP
+  int pix_per_split;  // multiple of 32
+  int dn, dp, dq;     // 32 pixels = dn images + dp rows + dq columns (mixed radix P, Q)
+  unsigned dy_bytes, x_bytes;
 };
 
-__device__ __forceinline__ void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
-  // in[p] = 8 channels of pixel p (as 4 dwords); out[c] = 8 pixels of channel c
-  const uint32_t* I = reinterpret_cast<const uint32_t*>(in);
-  uint32_t* O = reinterpret_cast<uint32_t*>(out);
-#pragma unroll
-  for (int j = 0; j < 4; ++j)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t lo = I[(2 * i) * 4 + j], hi = I[(2 * i + 1) * 4 + j];
-      O[(2 * j) * 4 + i] = (lo & 0xffffu) | (hi << 16);
-      O[(2 * j + 1) * 4 + i] = (lo >> 16) | (hi & 0xffff0000u);
-    }
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ bf16x8 lds_read_tr8(const bf16_t* p, int row_pitch) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * row_pitch));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int T, int BKP>
-__global__ __launch_bounds__(256) void wgrad_kernel(const bf16_t* __restrict__ dy,
-                                                    const bf16_t* __restrict__ x,
-                                                    float* __restrict__ part, WgradArgs g) {
-  static_assert((2 * T / 8) * (BKP / 8) == 256, "one 8x8 block per thread");
-  constexpr int PITCH = BKP + 8;          // bf16 elements per LDS row
-  constexpr int UNITS = BKP / 8;          // 16-byte units per row
-  constexpr int CH = T / 8;               // channel chunks per operand
-  constexpr int TW = T / 64;              // 32x32 MFMA tiles per wave per dim (waves 2x2)
-  __shared__ __attribute__((aligned(16))) bf16_t As[T * PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[T * PITCH];
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void wgrad_tr_kernel(const bf16_t* __restrict__ dy,
+                                                       const bf16_t* __restrict__ x,
+                                                       float* __restrict__ part, WgradTrArgs g) {
+  constexpr int BKP = 32;
+  constexpr int PA = TM + 32, PB = TN + 32;                        // LDS row pitch, elements
+  constexpr int A_CPR = TM / 8, B_CPR = TN / 8;                    // 16-byte chunks per tile row
+  constexpr int A_N = BKP * A_CPR / 256, B_N = BKP * B_CPR / 256;  // chunks per thread
+  constexpr int A_RSTEP = 256 / A_CPR, B_RSTEP = 256 / B_CPR;      // rows between a thread's chunks
+  constexpr int TWM = TM / 64, TWN = TN / 64;                      // 32x32 tiles per wave (waves 2x2)
+  static_assert(A_N >= 1 && B_N >= 1, "tile too narrow for 256 threads");
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BKP * PA];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BKP * PB];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int k0 = blockIdx.x * T, j0 = blockIdx.y * T;
-  const long mbeg = (long)blockIdx.z * g.pix_per_split;
-  const long mend = min((long)g.M, mbeg + g.pix_per_split);
+  const int k0 = blockIdx.x * TM, j0 = blockIdx.y * TN;
+  const int mbeg = blockIdx.z * g.pix_per_split;
+  const int mend = min(g.M, mbeg + g.pix_per_split);
+  const int nsteps = (mend - mbeg + BKP - 1) / BKP;
+  const __amdgpu_buffer_rsrc_t rdy = tensor_rsrc(dy, g.dy_bytes), rx = tensor_rsrc(x, g.x_bytes);
 
-  const bool isA = tid < 128;
-  const int blk = isA ? tid : tid - 128;
-  const int cc = blk % CH, pg = blk / CH;   // channel chunk, pixel group
-  // B threads: column chunk -> (r, s, c0), fixed for the whole loop
-  int br = 0, bs = 0, bc = 0;
-  bool colvalid;
-  if (isA) {
-    colvalid = (k0 + cc * 8) < g.K;
-  } else {
-    const int j = j0 + cc * 8;
-    colvalid = j < g.J;
-    const int rs = colvalid ? j / g.C : 0;
-    bc = colvalid ? j - rs * g.C : 0;
+  // dy chunks: row a_row + i*A_RSTEP of the step, channels k0 + a_cc*8 .. +7.  Rows past the end of
+  // the tensor read as zeros (pix_per_split is a multiple of 32, so only the last split is ragged).
+  const int a_cc = tid % A_CPR, a_row = tid / A_CPR;
+  unsigned a_off[A_N];
+#pragma unroll
+  for (int i = 0; i < A_N; ++i)
+    a_off[i] = k0 + a_cc * 8 < g.K ? (unsigned)((mbeg + a_row + i * A_RSTEP) * g.K + k0 + a_cc * 8) * 2u : kOutOfRange;
+  const unsigned a_step = (unsigned)(BKP * g.K) * 2u;
+
+  // x chunks: column chunk -> tap (br, bs) and first channel bc, fixed; pixel -> (n, p, q), advanced
+  // by 32 pixels a step without divisions
+  const int b_cc = tid % B_CPR, b_row = tid / B_CPR;
+  const int jcol = j0 + b_cc * 8;
+  const bool b_ok = jcol < g.J;
+  int br, bs, bc;
+  {
+    const int rs = b_ok ? jcol / g.C : 0;
+    bc = b_ok ? jcol - rs * g.C : 0;
     br = rs / g.S;
     bs = rs - br * g.S;
   }
+  int bn[B_N], bp[B_N], bq[B_N], bm[B_N];
+#pragma unroll
+  for (int i = 0; i < B_N; ++i) {
+    bm[i] = mbeg + b_row + i * B_RSTEP;
+    bq[i] = bm[i] % g.Q;
+    const int t = bm[i] / g.Q;
+    bp[i] = t % g.P;
+    bn[i] = t / g.P;
+  }
 
-  f32x16 acc[TW][TW];
+  uint4 ra[A_N], rb[B_N];
+  auto load_step = [&]() {
 #pragma unroll
-  for (int i = 0; i < TW; ++i)
+    for (int i = 0; i < A_N; ++i) {
+      ra[i] = buffer_load16(rdy, a_off[i]);
+      a_off[i] += a_off[i] == kOutOfRange ? 0u : a_step;
+    }
 #pragma unroll
-    for (int j = 0; j < TW; ++j)
+    for (int i = 0; i < B_N; ++i) {
+      const int h = bp[i] * g.stride + br - g.pad, w = bq[i] * g.stride + bs - g.pad;
+      const bool ok = b_ok && bm[i] < mend && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+      const unsigned off = (unsigned)(((bn[i] * g.H + h) * g.W + w) * g.C + bc) * 2u;
+      rb[i] = buffer_load16(rx, ok ? off : kOutOfRange);
+      bm[i] += BKP;
+      int q = bq[i] + g.dq;
+      const int c1 = q >= g.Q ? 1 : 0;
+      bq[i] = q - (c1 ? g.Q : 0);
+      int pp = bp[i] + g.dp + c1;
+      const int c2 = pp >= g.P ? 1 : 0;
+      bp[i] = pp - (c2 ? g.P : 0);
+      bn[i] += g.dn + c2;
+    }
+  };
+  auto store_step = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_N; ++i)
+      *reinterpret_cast<uint4*>(&As[buf][(a_row + i * A_RSTEP) * PA + a_cc * 8]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_N; ++i)
+      *reinterpret_cast<uint4*>(&Bs[buf][(b_row + i * B_RSTEP) * PB + b_cc * 8]) = rb[i];
+  };
+
+  f32x16 acc[TWM][TWN];
+#pragma unroll
+  for (int i = 0; i < TWM; ++i)
+#pragma unroll
+    for (int j = 0; j < TWN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  for (long ms = mbeg; ms < mend; ms += BKP) {
-    uint4 in[8], tr[8];
-    const long mfirst = ms + pg * 8;
-    if (isA) {
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const long m = mfirst + p;
-        in[p] = (colvalid && m < mend)
-                    ? *reinterpret_cast<const uint4*>(dy + m * g.K + k0 + cc * 8)
-                    : make_uint4(0, 0, 0, 0);
-      }
-    } else {
-      long t = mfirst;
-      int q = (int)(t % g.Q); t /= g.Q;
-      int p_ = (int)(t % g.P);
-      int n = (int)(t / g.P);
-#pragma unroll
-      for (int p = 0; p < 8; ++p) {
-        const long m = mfirst + p;
-        const int h = p_ * g.stride + br - g.pad, w = q * g.stride + bs - g.pad;
-        const bool ok = colvalid && m < mend && h >= 0 && h < g.H && w >= 0 && w < g.W;
-        in[p] = ok ? *reinterpret_cast<const uint4*>(x + (((long)n * g.H + h) * g.W + w) * g.C + bc)
-                   : make_uint4(0, 0, 0, 0);
-        if (++q == g.Q) { q = 0; if (++p_ == g.P) { p_ = 0; ++n; } }
-      }
-    }
-    transpose8x8(in, tr);
-    __syncthreads();  // previous step's MFMA reads are done
-    bf16_t* dstbase = isA ? As : Bs;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int row = cc * 8 + i;
-      const int unit = pg ^ (cc & 7);       // swizzle: rows 8 apart would share banks
-      *reinterpret_cast<uint4*>(&dstbase[row * PITCH + unit * 8]) = tr[i];
-    }
-    __syncthreads();
+  // fragment addresses: 16-lane group gl reads channels 16*(gl&1)..+15 of pixels 8*(gl>>1)..+7
+  const int s16 = lane & 15, gl = lane >> 4;
+  const int frag_row = 8 * (gl >> 1) + (s16 >> 2), frag_col = 16 * (gl & 1) + 4 * (s16 & 3);
+  const int a_frag = frag_row * PA + wm * (TM / 2) + frag_col;
+  const int b_frag = frag_row * PB + wn * (TN / 2) + frag_col;
+
+  load_step();
+  store_step(0);
+  __syncthreads();
+  for (int st = 0; st < nsteps; ++st) {
+    const int buf = st & 1;
+    if (st + 1 < nsteps) load_step();
 #pragma unroll
     for (int ks = 0; ks < BKP / 16; ++ks) {
-      bf16x8 af[TW], bfr[TW];
+      bf16x8 af[TWM], bfr[TWN];
 #pragma unroll
-      for (int i = 0; i < TW; ++i) {
-        const int row = wm * TW * 32 + i * 32 + (lane & 31);
-        const int unit = (ks * 2 + (lane >> 5)) ^ ((row >> 3) & 7);
-        af[i] = *reinterpret_cast<const bf16x8*>(&As[row * PITCH + unit * 8]);
-      }
+      for (int i = 0; i < TWM; ++i) af[i] = lds_read_tr8(&As[buf][a_frag + ks * 16 * PA + i * 32], PA);
 #pragma unroll
-      for (int j = 0; j < TW; ++j) {
-        const int row = wn * TW * 32 + j * 32 + (lane & 31);
-        const int unit = (ks * 2 + (lane >> 5)) ^ ((row >> 3) & 7);
-        bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[row * PITCH + unit * 8]);
-      }
+      for (int j = 0; j < TWN; ++j) bfr[j] = lds_read_tr8(&Bs[buf][b_frag + ks * 16 * PB + j * 32], PB);
 #pragma unroll
-      for (int i = 0; i < TW; ++i)
+      for (int i = 0; i < TWM; ++i)
 #pragma unroll
-        for (int j = 0; j < TW; ++j)
+        for (int j = 0; j < TWN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    if (st + 1 < nsteps) store_step(buf ^ 1);
+    __syncthreads();
   }
-  static_assert(UNITS >= 8, "swizzle needs 8 units per row");
 
-  float* out = part + (long)blockIdx.z * g.K * g.J;
+  float* out = part + (size_t)blockIdx.z * g.K * g.J;
 #pragma unroll
-  for (int j = 0; j < TW; ++j) {
-    const int col = j0 + wn * TW * 32 + j * 32 + (lane & 31);
+  for (int j = 0; j < TWN; ++j) {
+    const int col = j0 + wn * (TN / 2) + j * 32 + (lane & 31);
     if (col >= g.J) continue;
 #pragma unroll
-    for (int i = 0; i < TW; ++i)
+    for (int i = 0; i < TWM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int row = k0 + wm * TW * 32 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (row < g.K) out[(long)row * g.J + col] = acc[i][j][v];
+        const int row = k0 + wm * (TM / 2) + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row < g.K) out[(size_t)row * g.J + col] = acc[i][j][v];
       }
   }
 }

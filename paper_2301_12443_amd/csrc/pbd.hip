@@ -201,12 +201,14 @@ ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 512) 
   return g;
 }
 
-struct WgradCfg { int T, BKP, tiles_k, tiles_j, splits, pix_per_split; };
+struct WgradCfg { int TM, TN, BKP, tiles_k, tiles_j, splits, pix_per_split; };
 WgradCfg wgrad_cfg(long M, int K, int J) {
   WgradCfg w;
-  if (K >= 128 && J >= 128) { w.T = 128; w.BKP = 64; } else { w.T = 64; w.BKP = 128; }
-  w.tiles_k = (K + w.T - 1) / w.T;
-  w.tiles_j = (J + w.T - 1) / w.T;
+  w.TM = K > 64 ? 128 : 64;       // a 128-wide tile that is 3/4 full still beats two 64-wide ones
+  w.TN = J > 64 ? 128 : 64;
+  w.BKP = 32;
+  w.tiles_k = (K + w.TM - 1) / w.TM;
+  w.tiles_j = (J + w.TN - 1) / w.TN;
   const long tiles = (long)w.tiles_k * w.tiles_j;
   long splits = std::max(1L, 256 / tiles);
   const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
@@ -497,14 +499,21 @@ template <class T> struct Exec {
     if (mfma()) {
       if constexpr (sizeof(T) == 2) {
         const WgradCfg w = wgrad_cfg(M, op.d.c_out, J);
-        WgradArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
-                    op.d.stride, op.d.pad, (int)M, J, w.pix_per_split};
+        const int pq = op.out.h * op.out.w;
+        WgradTrArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
+                      op.d.stride, op.d.pad, (int)M, J, w.pix_per_split,
+                      w.BKP / pq, (w.BKP % pq) / op.out.w, w.BKP % op.out.w,
+                      (unsigned)(M * op.d.c_out * 2), (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2)};
         dim3 grid(w.tiles_k, w.tiles_j, w.splits);
         float* part = w.splits == 1 ? dw : red();
         {
-          ProfScope ps(c, w.T == 128 ? "wgrad_128x64" : "wgrad_64x128", bytes, flops, net, blk, opi);
-          if (w.T == 128) launch(c, wgrad_kernel<128, 64>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g);
-          else launch(c, wgrad_kernel<64, 128>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g);
+          char name[32];
+          snprintf(name, sizeof name, "wgrad_%dx%d", w.TM, w.TN);
+          ProfScope ps(c, name, bytes, flops, net, blk, opi);
+#define PBD_WG(TM_, TN_) launch(c, wgrad_tr_kernel<TM_, TN_>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g)
+          if (w.TM == 128) { if (w.TN == 128) PBD_WG(128, 128); else PBD_WG(128, 64); }
+          else { if (w.TN == 128) PBD_WG(64, 128); else PBD_WG(64, 64); }
+#undef PBD_WG
         }
         if (w.splits > 1) {
           ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
@@ -1039,13 +1048,14 @@ int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t
     }
     c->act.push_back(t);
   }
-  // kernels index tensors with 32-bit element offsets
+  // kernels address tensors with 32-bit byte offsets and use 0x80000000 as "outside every tensor"
+  const long esize = opts->precision == PBD_BF16 ? 2 : 4;
   for (int which = 0; which < 2; ++which)
     for (const BlockPlan& bp : c->net[which])
       for (const Shape& s : bp.shapes)
-        if ((long)opts->batch * s.h * s.w * round8(s.c) >= (1L << 31) - 64) {
+        if ((long)opts->batch * s.h * s.w * round8(s.c) * esize >= (1L << 31) - 4096) {
           delete c;
-          return fail(nullptr, PBD_ESHAPE, "a tensor of batch x %d x %d x %d has 2^31 elements or more", s.h, s.w, s.c);
+          return fail(nullptr, PBD_ESHAPE, "a tensor of batch x %d x %d x %d takes 2 GiB or more", s.h, s.w, s.c);
         }
   plan(c);
   *out = c;
