@@ -837,28 +837,40 @@ __global__ void transpose_weights_kernel(const T* __restrict__ wc, T* __restrict
 }
 
 // out[j] = sum_s part[s*stride + j]   (ordered second stage of split reductions); n % 4 == 0.
-// Block = 32 float4 outputs x 8 split lanes: lane l adds splits l, l+8, ... in order, then the 8 lane
-// sums are added in order, so the result does not depend on scheduling.
+// Block = (256/SL) float4 outputs x SL split lanes: lane l adds splits l, l+SL, ... in order (four
+// loads in flight), then the SL lane sums are added in order, so the result does not depend on
+// scheduling.  SL = 8 for a few partials of a large tensor, 32 for many partials of a small one.
+template <int SL>
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float* __restrict__ part,
                                                            float* __restrict__ out, long n, int splits,
                                                            long stride) {
-  __shared__ float4 red[8][32];
-  const int o = threadIdx.x & 31, l = threadIdx.x >> 5;
+  constexpr int NO = 256 / SL;
+  __shared__ float4 red[SL][NO];
+  const int o = threadIdx.x % NO, l = threadIdx.x / NO;
   const long n4 = n / 4;
-  for (long base = (long)blockIdx.x * 32; base < n4; base += (long)gridDim.x * 32) {
+  for (long base = (long)blockIdx.x * NO; base < n4; base += (long)gridDim.x * NO) {
     const long i = base + o;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (i < n4)
-      for (int k = l; k < splits; k += 8) {
+    if (i < n4) {
+      int k = l;
+      for (; k + 3 * SL < splits; k += 4 * SL) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(part + (long)(k + u * SL) * stride + i * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+      }
+      for (; k < splits; k += SL) {
         const float4 v = *reinterpret_cast<const float4*>(part + (long)k * stride + i * 4);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
       }
+    }
     red[l][o] = s;
     __syncthreads();
     if (l == 0 && i < n4) {
       float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int k = 0; k < 8; ++k) { t.x += red[k][o].x; t.y += red[k][o].y; t.z += red[k][o].z; t.w += red[k][o].w; }
+      for (int k = 0; k < SL; ++k) { t.x += red[k][o].x; t.y += red[k][o].y; t.z += red[k][o].z; t.w += red[k][o].w; }
       *reinterpret_cast<float4*>(out + i * 4) = t;
     }
     __syncthreads();

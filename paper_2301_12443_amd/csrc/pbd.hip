@@ -517,7 +517,7 @@ template <class T> struct Exec {
         }
         if (w.splits > 1) {
           ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
-          launch(c, sum_partials_kernel, grid_for((long)op.wn / 4, 32), 256, 0, st, part, dw, (long)op.wn, w.splits, (long)op.wn);
+          sum_partials(part, dw, (long)op.wn, w.splits);
         }
       }
     } else {
@@ -525,6 +525,11 @@ template <class T> struct Exec {
       ProfScope ps(c, "conv_wgrad_direct", bytes, flops, net, blk, opi);
       launch(c, conv_direct_wgrad_kernel<T>, grid_for((long)op.wn, 64), 64, 0, st, dy, x, dw, g);
     }
+  }
+
+  void sum_partials(const float* part, float* out, long n, int splits) {
+    if (splits >= 64) launch(c, sum_partials_kernel<32>, grid_for(n / 4, 8), 256, 0, st, part, out, n, splits, n);
+    else launch(c, sum_partials_kernel<8>, grid_for(n / 4, 32), 256, 0, st, part, out, n, splits, n);
   }
 
   // ---- depthwise ----------------------------------------------------------
@@ -565,7 +570,7 @@ template <class T> struct Exec {
             (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
     }
     ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
-    launch(c, sum_partials_kernel, grid_for((long)op.wn / 4, 32), 256, 0, st, red(), dw, (long)op.wn, g.chunks, (long)op.wn);
+    sum_partials(red(), dw, (long)op.wn, g.chunks);
   }
 
   // ---- joins / pool -------------------------------------------------------
