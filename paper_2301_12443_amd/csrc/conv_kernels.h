@@ -146,15 +146,19 @@ enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 // staging writes (row = lane/4, chunk = lane%4) run at the full 128 B/clk with it (80 B makes the writes conflict)
 constexpr int IG_BK = 32, IG_PITCH = IG_BK + 16;
 
-template <int MODE, int BM, int BN, int EPI>
+// UNI: the channel count of the gathered tensor is a multiple of the 32-element K step, so a step
+// lies inside one filter tap and (r, s, c0) are the same for the whole workgroup: they live in
+// scalar registers and a load costs a lane two adds, two compares, an add and a select.
+template <int MODE, int BM, int BN, int EPI, bool UNI>
 __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A,
                                                     const bf16_t* __restrict__ Bw,
                                                     bf16_t* __restrict__ Out,
                                                     const float* __restrict__ ep_a,
                                                     const float* __restrict__ ep_b, int act,
                                                     IgemmArgs g) {
-  // wave grid: 128-row tiles 2x2 (BN 128) or 4x1; 64-row tiles 2x2 (BN >= 64) or 2x1 over 32 columns
-  constexpr int WAVES_M = BM == 128 ? (BN == 128 ? 2 : 4) : 2, WAVES_N = 4 / WAVES_M;
+  // wave grid: 256x128 tiles 2x2 (a wave owns 128x64); 128-row tiles 2x2 (BN 128) or 4x1; 64-row
+  // tiles 2x2 (BN >= 64) or 2x1 over 32 columns
+  constexpr int WAVES_M = BM == 256 ? 2 : (BM == 128 ? (BN == 128 ? 2 : 4) : 2), WAVES_N = 4 / WAVES_M;
   constexpr int TM = BM / (WAVES_M * 32);
   constexpr int TN = (BN / (WAVES_N * 32)) > 0 ? BN / (WAVES_N * 32) : 1;
   constexpr bool kIdleWaves = BN / (WAVES_N * 32) == 0;      // BM 64, BN 32: waves with wn = 1 only stage tiles
@@ -193,7 +197,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   }
   // reduction position of this thread's chunk: kk = (r*S + s)*CA + c
   const int kt0 = blockIdx.z * g.ksteps_per_split;
-  int kk = kt0 * IG_BK + chunk * 8;
+  int kk = kt0 * IG_BK + (UNI ? 0 : chunk * 8);
   int r, s, c;
   {
     const int rs = kk / g.CA;
@@ -201,12 +205,50 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     r = rs / g.S;
     s = rs - r * g.S;
   }
+  // UNI: byte offset = abase[i] + delta(r, s, c0), linear in the tap for either mode (for stride-2
+  // backward-data the halved coordinates are exact whenever the parity test passes); rows that do
+  // not exist get a coordinate that fails every range test
+  unsigned abase[A_LOADS], bbase[B_LOADS];
+  if (UNI) {
+#pragma unroll
+    for (int i = 0; i < A_LOADS; ++i) {
+      if (MODE == 0) abase[i] = (unsigned)(((rbase[i] + rh[i] * g.WA + rw[i]) * g.CA + chunk * 8) * 2);
+      else abase[i] = (unsigned)((rbase[i] * g.CA + ((rh[i] * g.WA + rw[i]) * g.CA >> sh) + chunk * 8) * 2);
+      if (!rvalid[i]) rh[i] = -(1 << 24);
+    }
+#pragma unroll
+    for (int i = 0; i < B_LOADS; ++i) bbase[i] = brow[i] >= 0 ? (unsigned)(brow[i] + chunk * 8) * 2u : kOutOfRange;
+  }
 
   // two register stages: tile kt+2 is requested while tile kt is multiplied and tile kt+1 moves to LDS
   uint4 areg[2][A_LOADS], breg[2][B_LOADS];
   const __amdgpu_buffer_rsrc_t a_rsrc = tensor_rsrc(A, g.a_bytes), b_rsrc = tensor_rsrc(Bw, g.b_bytes);
   auto load_tile = [&](auto stage) {
     constexpr int S_ = decltype(stage)::value;
+    if constexpr (UNI) {
+      const int tap = MODE == 0 ? r * g.WA + s : -(r * g.WA + s);
+      const unsigned delta = (unsigned)(((tap * g.CA) >> (MODE == 1 ? sh : 0)) + c) * 2u;
+      const unsigned hlim = MODE == 0 ? (unsigned)g.HA : (unsigned)g.HA << sh;
+      const unsigned wlim = MODE == 0 ? (unsigned)g.WA : (unsigned)g.WA << sh;
+#pragma unroll
+      for (int i = 0; i < A_LOADS; ++i) {
+        const int h = MODE == 0 ? rh[i] + r : rh[i] - r, w = MODE == 0 ? rw[i] + s : rw[i] - s;
+        bool ok = (unsigned)h < hlim && (unsigned)w < wlim;
+        if (MODE == 1) ok = ok && ((h | w) & smask) == 0;
+        areg[S_][i] = buffer_load16(a_rsrc, ok ? abase[i] + delta : kOutOfRange);
+      }
+#pragma unroll
+      for (int i = 0; i < B_LOADS; ++i) breg[S_][i] = buffer_load16(b_rsrc, bbase[i] + (unsigned)kk * 2u);
+      kk += IG_BK;
+      c += IG_BK;
+      const bool wrap = c >= g.CA;
+      c = wrap ? 0 : c;
+      s += wrap ? 1 : 0;
+      const bool wrap2 = s == g.S;
+      s = wrap2 ? 0 : s;
+      r += wrap2 ? 1 : 0;
+      return;
+    }
     const bool kvalid = r < g.R;
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {

@@ -230,6 +230,7 @@ IgemmCfg igemm_cfg(long M, int NC, int Kred) {
   c.BN = NC >= 128 ? 128 : (NC > 32 ? 64 : 32);
   const long tn = (NC + c.BN - 1) / c.BN;
   c.BM = ((M + 127) / 128) * tn >= 512 ? 128 : 64;
+  if (c.BN == 128 && ((M + 255) / 256) * tn >= 1024) c.BM = 256;
   const long tiles = ((M + c.BM - 1) / c.BM) * tn;
   const int nk = (Kred + IG_BK - 1) / IG_BK;
   c.splits = 1;
@@ -441,9 +442,11 @@ template <class T> struct Exec {
     g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
     dim3 grid((g.M + cfg.BM - 1) / cfg.BM, (g.NC + cfg.BN - 1) / cfg.BN,
               (nk + g.ksteps_per_split - 1) / g.ksteps_per_split);
-#define PBD_IG(BM_, BN_, EPI_, OUT_) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g)
+#define PBD_IG(BM_, BN_, EPI_, OUT_) do { \
+      if (g.CA % IG_BK == 0) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, true>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); \
+      else launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, false>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); } while (0)
 #define PBD_IG_BN(BM_, EPI_, OUT_) do { if (cfg.BN == 128) PBD_IG(BM_, 128, EPI_, OUT_); else if (cfg.BN == 64) PBD_IG(BM_, 64, EPI_, OUT_); else PBD_IG(BM_, 32, EPI_, OUT_); } while (0)
-#define PBD_IG_BM(EPI_, OUT_) do { if (cfg.BM == 128) PBD_IG_BN(128, EPI_, OUT_); else PBD_IG_BN(64, EPI_, OUT_); } while (0)
+#define PBD_IG_BM(EPI_, OUT_) do { if (cfg.BM == 256) PBD_IG(256, 128, EPI_, OUT_); else if (cfg.BM == 128) PBD_IG_BN(128, EPI_, OUT_); else PBD_IG_BN(64, EPI_, OUT_); } while (0)
     // profile entries are named after the kernel instantiation, so that each maps to one symbol of
     // a rocprofv3 kernel trace: igemm_<fwd|dgrad>_<BM>x<BN>_<epilogue>
     static const char* const kEpi[] = {"store", "affine", "accum", "partial"};
