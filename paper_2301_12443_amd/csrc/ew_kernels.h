@@ -929,6 +929,81 @@ __global__ __launch_bounds__(256) void dw_fwd_kernel(const T* __restrict__ x, co
   }
 }
 
+// Sliding-window forward / stride-1 backward-data: one thread = 8 channels of WS consecutive output
+// pixels of one row.  Per filter row it loads the (WS-1)*STRIDE + K input pixels once and uses each
+// for up to K outputs, so the loads per output drop from K*K to K*((WS-1)*STRIDE+K)/WS: the vector
+// memory pipeline, not HBM, is what a one-pixel-per-thread depthwise kernel saturates.
+// FLIP: read the filter mirrored (backward-data of a stride-1 convolution is the same sliding
+// sum with taps (K-1-r, K-1-s)); `accumulate` then adds to what dst holds.
+template <class T, int K, int STRIDE, int WS, bool FLIP>
+__global__ __launch_bounds__(256) void dw_slide_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                       T* dst, const float* __restrict__ a,
+                                                       const float* __restrict__ b, int act, int accumulate,
+                                                       int N, int H, int W, int P, int Q, int ncv, int pad,
+                                                       unsigned x_elems) {
+  constexpr int NIN = (WS - 1) * STRIDE + K;
+  const int QS = (Q + WS - 1) / WS;
+  const long nitem = (long)N * P * QS * ncv;
+  const __amdgpu_buffer_rsrc_t xr = tensor_rsrc(x, x_elems * (unsigned)sizeof(T));
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nitem; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long seg = i / ncv;
+    const int qs = (int)(seg % QS); seg /= QS;
+    const int p = (int)(seg % P);
+    const int n = (int)(seg / P);
+    const int q0 = qs * WS, w0 = q0 * STRIDE - pad;
+    float acc[WS][8];
+#pragma unroll
+    for (int o = 0; o < WS; ++o)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[o][e] = 0.f;
+#pragma unroll 1
+    for (int r = 0; r < K; ++r) {      // one filter row at a time bounds the registers
+      const int h = p * STRIDE + r - pad;
+      const bool row_ok = (unsigned)h < (unsigned)H;
+      const unsigned rowoff = (unsigned)((n * H + h) * W + w0) * (unsigned)ncv + (unsigned)cv;
+      typename BufIO<T>::Raw raw[NIN];
+#pragma unroll
+      for (int j = 0; j < NIN; ++j)
+        raw[j] = BufIO<T>::issue(xr, (rowoff + (unsigned)(j * ncv)) * 8u, row_ok && (unsigned)(w0 + j) < (unsigned)W);
+      float f[K][8];
+#pragma unroll
+      for (int t = 0; t < K; ++t) {
+        const int tap = FLIP ? (K - 1 - r) * K + (K - 1 - t) : r * K + t;
+        IO<T>::ld(w + ((long)tap * ncv + cv) * 8, f[t]);
+      }
+#pragma unroll
+      for (int j = 0; j < NIN; ++j) {
+        float v[8];
+        BufIO<T>::unpack(raw[j], v);
+#pragma unroll
+        for (int o = 0; o < WS; ++o) {
+          const int t = j - o * STRIDE;       // compile-time after unrolling
+          if (t < 0 || t >= K) continue;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[o][e] = fmaf(v[e], f[t][e], acc[o][e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int o = 0; o < WS; ++o) {
+      if (q0 + o >= Q) continue;
+      T* out = dst + ((((long)n * P + p) * Q + q0 + o) * ncv + cv) * 8;
+      if (a) {  // folded inference-mode BN + activation (teacher)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[o][e] = apply_act(fmaf(acc[o][e], a[cv * 8 + e], b[cv * 8 + e]), act);
+      }
+      if (accumulate) {
+        float old[8];
+        IO<T>::ld(out, old);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[o][e] += old[e];
+      }
+      IO<T>::st(out, acc[o]);
+    }
+  }
+}
+
 // Backward-data in gather form: dx[h,w] (+)= sum_taps dy[(h+pad-r)/st, (w+pad-s)/st] * w[r][s]
 template <class T, int KK>
 __global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dy, const T* __restrict__ w,

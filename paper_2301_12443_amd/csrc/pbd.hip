@@ -536,11 +536,25 @@ template <class T> struct Exec {
   }
 
   // ---- depthwise ----------------------------------------------------------
+  // sliding-window depthwise kernels: odd k in {3,5,7} with "same" padding, 4 outputs per thread
+  static constexpr int kDwSlide = 4;
+  static bool dw_slides(const OpPlan& op) {
+    return (op.d.k == 3 || op.d.k == 5 || op.d.k == 7) && op.d.pad == op.d.k / 2 && (op.d.stride == 1 || op.d.stride == 2);
+  }
   void dw_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
     ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
     const unsigned xe = (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p);
+    if (dw_slides(op)) {
+      const long nitem = (long)N * op.out.h * ((op.out.w + kDwSlide - 1) / kDwSlide) * ncv;
+#define PBD_DWS(K_, S_) launch(c, dw_slide_kernel<T, K_, S_, kDwSlide, false>, grid_for(nitem), 256, 0, st, x, w, y, a, b, act, 0, \
+    N, op.in.h, op.in.w, op.out.h, op.out.w, ncv, op.d.pad, xe)
+      if (op.d.stride == 1) { if (op.d.k == 3) PBD_DWS(3, 1); else if (op.d.k == 5) PBD_DWS(5, 1); else PBD_DWS(7, 1); }
+      else { if (op.d.k == 3) PBD_DWS(3, 2); else if (op.d.k == 5) PBD_DWS(5, 2); else PBD_DWS(7, 2); }
+#undef PBD_DWS
+      return;
+    }
 #define PBD_DWF(KK_) launch(c, dw_fwd_kernel<T, KK_>, grid_for(nvec), 256, 0, st, x, w, y, a, b, act, N, op.in.h, op.in.w, \
     op.out.h, op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, xe)
     if (op.d.k == 3) PBD_DWF(9); else if (op.d.k == 5) PBD_DWF(25); else if (op.d.k == 7) PBD_DWF(49); else PBD_DWF(1);
@@ -551,6 +565,14 @@ template <class T> struct Exec {
     const long nvec = (long)N * op.in.h * op.in.w * ncv;
     ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
     const unsigned de = (unsigned)((size_t)N * op.out.h * op.out.w * op.cout_p);
+    if (dw_slides(op) && op.d.stride == 1) {   // mirrored filter over dy: same sliding sum
+      const long nitem = (long)N * op.in.h * ((op.in.w + kDwSlide - 1) / kDwSlide) * ncv;
+#define PBD_DWS(K_) launch(c, dw_slide_kernel<T, K_, 1, kDwSlide, true>, grid_for(nitem), 256, 0, st, dy, w, dx, (const float*)nullptr, \
+    (const float*)nullptr, 0, accumulate ? 1 : 0, N, op.out.h, op.out.w, op.in.h, op.in.w, ncv, op.d.pad, de)
+      if (op.d.k == 3) PBD_DWS(3); else if (op.d.k == 5) PBD_DWS(5); else PBD_DWS(7);
+#undef PBD_DWS
+      return;
+    }
 #define PBD_DWD(KK_) launch(c, dw_dgrad_kernel<T, KK_>, grid_for(nvec), 256, 0, st, dy, w, dx, N, op.in.h, op.in.w, op.out.h, \
     op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, accumulate ? 1 : 0, de)
     if (op.d.k == 3) PBD_DWD(9); else if (op.d.k == 5) PBD_DWD(25); else if (op.d.k == 7) PBD_DWD(49); else PBD_DWD(1);
