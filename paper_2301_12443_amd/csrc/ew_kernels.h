@@ -1004,6 +1004,103 @@ __global__ __launch_bounds__(256) void dw_slide_kernel(const T* __restrict__ x, 
   }
 }
 
+// LDS-tiled stride-1 depthwise convolution (bf16): a block stages the (8+K-1) x (16+K-1) input
+// pixels x 64 channels behind an 8 x 16 output tile in LDS with ONE round of global loads (all in
+// flight together), then every thread slides over 4 outputs reading LDS.  Each input element is
+// fetched once per tile instead of ~K*K/2 times, which takes the kernel off the vector-memory
+// pipeline and onto HBM.  LDS pixel pitch 160 B: the two 4-pixel segments of a 16-lane group land
+// 128 B apart modulo the 256 B bank span.  FLIP / accumulate as in dw_slide_kernel.
+constexpr int kDwTileH = 8, kDwTileW = 16, kDwTileCv = 8, kDwTilePitch = kDwTileCv * 16 + 32;
+
+template <int K, bool FLIP>
+__global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w,
+                                                      bf16_t* dst, const float* __restrict__ a,
+                                                      const float* __restrict__ b, int act, int accumulate,
+                                                      int N, int H, int W, int ncv, int tiles_h, int tiles_w,
+                                                      unsigned x_bytes) {
+  constexpr int TH = kDwTileH, TW = kDwTileW, WS = 4, CVB = kDwTileCv, PIXB = kDwTilePitch;
+  constexpr int IH = TH + K - 1, IW = TW + K - 1, NIN = WS + K - 1, pad = K / 2;
+  constexpr int TOTAL = IH * IW * CVB, NLOAD = (TOTAL + 255) / 256;
+  __shared__ __attribute__((aligned(16))) unsigned char tile[IH * IW * PIXB];
+  const int tid = threadIdx.x;
+  int t = blockIdx.x;
+  const int tw = t % tiles_w; t /= tiles_w;
+  const int th_ = t % tiles_h;
+  const int n = t / tiles_h;
+  const int h0 = th_ * TH, w0 = tw * TW, cv0 = blockIdx.y * CVB;
+  const __amdgpu_buffer_rsrc_t xr = tensor_rsrc(x, x_bytes);
+
+  uint4 raw[NLOAD];
+#pragma unroll
+  for (int i = 0; i < NLOAD; ++i) {
+    const int c = tid + i * 256;
+    const int pix = c / CVB, cvl = c % CVB;
+    const int ih = pix / IW, iw = pix % IW;
+    const int h = h0 - pad + ih, ww = w0 - pad + iw;
+    const bool ok = c < TOTAL && (unsigned)h < (unsigned)H && (unsigned)ww < (unsigned)W && cv0 + cvl < ncv;
+    raw[i] = buffer_load16(xr, ok ? (unsigned)(((n * H + h) * W + ww) * ncv + cv0 + cvl) * 16u : kOutOfRange);
+  }
+#pragma unroll
+  for (int i = 0; i < NLOAD; ++i) {
+    const int c = tid + i * 256;
+    if (c < TOTAL) *reinterpret_cast<uint4*>(&tile[(c / CVB) * PIXB + (c % CVB) * 16]) = raw[i];
+  }
+  __syncthreads();
+
+  const int cvl = tid % CVB, seg = (tid / CVB) % (TW / WS), th = tid / (CVB * (TW / WS));
+  const int cv = cv0 + cvl;
+  if (cv >= ncv) return;
+  float acc[WS][8];
+#pragma unroll
+  for (int o = 0; o < WS; ++o)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[o][e] = 0.f;
+#pragma unroll 1
+  for (int r = 0; r < K; ++r) {
+    const unsigned char* rowp = &tile[((th + r) * IW + seg * WS) * PIXB + cvl * 16];
+    uint4 in[NIN];
+#pragma unroll
+    for (int j = 0; j < NIN; ++j) in[j] = *reinterpret_cast<const uint4*>(rowp + j * PIXB);
+    float f[K][8];
+#pragma unroll
+    for (int tt = 0; tt < K; ++tt) {
+      const int tap = FLIP ? (K - 1 - r) * K + (K - 1 - tt) : r * K + tt;
+      IO<bf16_t>::ld(w + ((long)tap * ncv + cv) * 8, f[tt]);
+    }
+#pragma unroll
+    for (int j = 0; j < NIN; ++j) {
+      float v[8];
+      BufIO<bf16_t>::unpack(in[j], v);
+#pragma unroll
+      for (int o = 0; o < WS; ++o) {
+        const int tt = j - o;
+        if (tt < 0 || tt >= K) continue;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[o][e] = fmaf(v[e], f[tt][e], acc[o][e]);
+      }
+    }
+  }
+  const int h = h0 + th;
+  if (h >= H) return;
+#pragma unroll
+  for (int o = 0; o < WS; ++o) {
+    const int ww = w0 + seg * WS + o;
+    if (ww >= W) continue;
+    bf16_t* out = dst + ((((long)n * H + h) * W + ww) * ncv + cv) * 8;
+    if (a) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[o][e] = apply_act(fmaf(acc[o][e], a[cv * 8 + e], b[cv * 8 + e]), act);
+    }
+    if (accumulate) {
+      float old[8];
+      IO<bf16_t>::ld(out, old);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[o][e] += old[e];
+    }
+    IO<bf16_t>::st(out, acc[o]);
+  }
+}
+
 // Backward-data in gather form: dx[h,w] (+)= sum_taps dy[(h+pad-r)/st, (w+pad-s)/st] * w[r][s]
 template <class T, int KK>
 __global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dy, const T* __restrict__ w,
@@ -1124,6 +1221,116 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy,
 #pragma unroll
         for (int e = 0; e < 8; ++e) pp[e] = out[t * 8 + e];
       }
+    }
+  }
+}
+
+
+// LDS-tiled depthwise backward-weight (bf16, stride 1).  Wavefront r of the block owns filter row r:
+// it walks the 256 (output row, 4-pixel segment, channel vector) items of each 8 x 16 tile and
+// accumulates dW[r][t][c] += dy[o] * x[o + t] for the K taps of its row, x and dy read from LDS
+// tiles staged as in dw_tile_kernel.  A block runs over `tiles_per_block` tiles, so x and dy are
+// fetched once (not once per filter row) and the K x 8 accumulators are reduced over the lanes
+// that share a channel vector only once, at the end (xor tree: a fixed association).
+template <int K>
+__global__ __launch_bounds__(64 * K) void dw_wgrad_tile_kernel(const bf16_t* __restrict__ dy,
+                                                               const bf16_t* __restrict__ x,
+                                                               float* __restrict__ part, int N, int H, int W,
+                                                               int ncv, int tiles_h, int tiles_w, int ntiles,
+                                                               int tiles_per_block, unsigned bytes) {
+  constexpr int TH = kDwTileH, TW = kDwTileW, WS = 4, CVB = kDwTileCv, PIXB = kDwTilePitch, NT = 64 * K;
+  constexpr int IH = TH + K - 1, IW = TW + K - 1, NIN = WS + K - 1, pad = K / 2;
+  constexpr int TOTX = IH * IW * CVB, NLX = (TOTX + NT - 1) / NT;
+  constexpr int TOTD = TH * TW * CVB, NLD = (TOTD + NT - 1) / NT;
+  __shared__ __attribute__((aligned(16))) unsigned char xt[IH * IW * PIXB];
+  __shared__ __attribute__((aligned(16))) unsigned char dt[TH * TW * PIXB];
+  const int tid = threadIdx.x, lane = tid & 63, r = tid >> 6;
+  const int cv0 = blockIdx.y * CVB;
+  const __amdgpu_buffer_rsrc_t xr = tensor_rsrc(x, bytes), dr = tensor_rsrc(dy, bytes);
+  float acc[K][8];
+#pragma unroll
+  for (int t = 0; t < K; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[t][e] = 0.f;
+
+  const int tile_end = min(ntiles, ((int)blockIdx.x + 1) * tiles_per_block);
+  for (int tile = blockIdx.x * tiles_per_block; tile < tile_end; ++tile) {
+    int t_ = tile;
+    const int tw = t_ % tiles_w; t_ /= tiles_w;
+    const int th_ = t_ % tiles_h;
+    const int n = t_ / tiles_h;
+    const int h0 = th_ * TH, w0 = tw * TW;
+    uint4 rx[NLX], rd[NLD];
+#pragma unroll
+    for (int i = 0; i < NLX; ++i) {
+      const int c = tid + i * NT;
+      const int pix = c / CVB, cvl = c % CVB;
+      const int h = h0 - pad + pix / IW, ww = w0 - pad + pix % IW;
+      const bool ok = c < TOTX && (unsigned)h < (unsigned)H && (unsigned)ww < (unsigned)W && cv0 + cvl < ncv;
+      rx[i] = buffer_load16(xr, ok ? (unsigned)(((n * H + h) * W + ww) * ncv + cv0 + cvl) * 16u : kOutOfRange);
+    }
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = tid + i * NT;
+      const int pix = c / CVB, cvl = c % CVB;
+      const int h = h0 + pix / TW, ww = w0 + pix % TW;
+      const bool ok = c < TOTD && h < H && ww < W && cv0 + cvl < ncv;
+      rd[i] = buffer_load16(dr, ok ? (unsigned)(((n * H + h) * W + ww) * ncv + cv0 + cvl) * 16u : kOutOfRange);
+    }
+    __syncthreads();                                 // the previous tile has been consumed
+#pragma unroll
+    for (int i = 0; i < NLX; ++i) {
+      const int c = tid + i * NT;
+      if (c < TOTX) *reinterpret_cast<uint4*>(&xt[(c / CVB) * PIXB + (c % CVB) * 16]) = rx[i];
+    }
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int c = tid + i * NT;
+      if (c < TOTD) *reinterpret_cast<uint4*>(&dt[(c / CVB) * PIXB + (c % CVB) * 16]) = rd[i];
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int it = 0; it < TOTD / (64 * WS); ++it) {
+      const int item = lane + 64 * it;
+      const int cvl = item % CVB, seg = (item / CVB) % (TW / WS), th = item / (CVB * (TW / WS));
+      const unsigned char* dp = &dt[(th * TW + seg * WS) * PIXB + cvl * 16];
+      const unsigned char* xp = &xt[((th + r) * IW + seg * WS) * PIXB + cvl * 16];
+      uint4 din[WS], xin[NIN];
+#pragma unroll
+      for (int o = 0; o < WS; ++o) din[o] = *reinterpret_cast<const uint4*>(dp + o * PIXB);
+#pragma unroll
+      for (int j = 0; j < NIN; ++j) xin[j] = *reinterpret_cast<const uint4*>(xp + j * PIXB);
+      float d[WS][8];
+#pragma unroll
+      for (int o = 0; o < WS; ++o) BufIO<bf16_t>::unpack(din[o], d[o]);
+#pragma unroll
+      for (int j = 0; j < NIN; ++j) {
+        float v[8];
+        BufIO<bf16_t>::unpack(xin[j], v);
+#pragma unroll
+        for (int o = 0; o < WS; ++o) {
+          const int t = j - o;
+          if (t < 0 || t >= K) continue;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[t][e] = fmaf(d[o][e], v[e], acc[t][e]);
+        }
+      }
+    }
+  }
+  // lanes with equal lane % 8 hold the same channel vector
+#pragma unroll
+  for (int t = 0; t < K; ++t)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+#pragma unroll
+      for (int m = 8; m < 64; m <<= 1) acc[t][e] += __shfl_xor(acc[t][e], m, 64);
+    }
+  if (lane < CVB && cv0 + lane < ncv) {
+#pragma unroll
+    for (int t = 0; t < K; ++t) {
+      float* pp = part + ((long)blockIdx.x * K * K + r * K + t) * (ncv * 8) + (cv0 + lane) * 8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pp[e] = acc[t][e];
     }
   }
 }

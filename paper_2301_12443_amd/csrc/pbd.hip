@@ -201,6 +201,31 @@ ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 512) 
   return g;
 }
 
+// Partial results of a depthwise backward-weight: row chunks of the column-grid kernel, or blocks of
+// tiles of the LDS-tiled kernel (bf16, stride 1, odd k <= 7, image at least 8 x 12).
+inline bool dw_tiled(bool bf16, int k, int stride, int pad, int h_out, int w_out) {
+  return bf16 && (k == 3 || k == 5 || k == 7) && pad == k / 2 && stride == 1 && h_out >= 8 && w_out >= 12;
+}
+struct DwWgradCfg { bool tiled; int chunks, tiles_h, tiles_w, ntiles, tiles_per_block; ColGrid g; };
+inline DwWgradCfg dw_wgrad_cfg(bool bf16, int N, int h_out, int w_out, int Cp, int k, int stride, int pad) {
+  DwWgradCfg w{};
+  const long M = (long)N * h_out * w_out;
+  w.tiled = dw_tiled(bf16, k, stride, pad, h_out, w_out);
+  if (w.tiled) {
+    w.tiles_h = (h_out + 7) / 8;
+    w.tiles_w = (w_out + 15) / 16;
+    w.ntiles = N * w.tiles_h * w.tiles_w;
+    const int cvblocks = (Cp / 8 + 7) / 8;
+    const int want = std::max(1, std::min(w.ntiles, 1024 / cvblocks));
+    w.tiles_per_block = (w.ntiles + want - 1) / want;
+    w.chunks = (w.ntiles + w.tiles_per_block - 1) / w.tiles_per_block;
+  } else {
+    w.g = col_grid(M, Cp, 16, k <= 3 ? 512 : 768 / k);
+    w.chunks = w.g.chunks;
+  }
+  return w;
+}
+
 struct WgradCfg { int TM, TN, BKP, tiles_k, tiles_j, splits, pix_per_split; };
 WgradCfg wgrad_cfg(long M, int K, int J) {
   WgradCfg w;
@@ -325,7 +350,8 @@ int plan(pbd_ctx* c) {
         const ColGrid g = col_grid(M, op.cout_p);
         need_red((size_t)g.chunks * 2 * op.cout_p * 4);
         if (op.dw) {
-          const ColGrid gw = col_grid(M, op.cout_p, 16, op.d.k <= 3 ? 512 : 768 / op.d.k);
+          const DwWgradCfg gw = dw_wgrad_cfg(bf && !c->o.force_direct, c->o.batch, op.out.h, op.out.w, op.cout_p, op.d.k,
+                                             op.d.stride, op.d.pad);
           need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
@@ -541,11 +567,26 @@ template <class T> struct Exec {
   static bool dw_slides(const OpPlan& op) {
     return (op.d.k == 3 || op.d.k == 5 || op.d.k == 7) && op.d.pad == op.d.k / 2 && (op.d.stride == 1 || op.d.stride == 2);
   }
+  // LDS-tiled kernels: bf16, stride 1, images of at least one tile row and most of a tile's width
+  static bool dw_tiles(const OpPlan& op) {
+    return dw_tiled(sizeof(T) == 2, op.d.k, op.d.stride, op.d.pad, op.out.h, op.out.w);
+  }
   void dw_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
     ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
     const unsigned xe = (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p);
+    if (dw_tiles(op)) {
+      if constexpr (sizeof(T) == 2) {
+        const int th = (op.out.h + kDwTileH - 1) / kDwTileH, tw = (op.out.w + kDwTileW - 1) / kDwTileW;
+        const dim3 grid(N * th * tw, (ncv + kDwTileCv - 1) / kDwTileCv);
+#define PBD_DWT(K_) launch(c, dw_tile_kernel<K_, false>, grid, 256, 0, st, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, 0, \
+    N, op.in.h, op.in.w, ncv, th, tw, xe * 2u)
+        if (op.d.k == 3) PBD_DWT(3); else if (op.d.k == 5) PBD_DWT(5); else PBD_DWT(7);
+#undef PBD_DWT
+      }
+      return;
+    }
     if (dw_slides(op)) {
       const long nitem = (long)N * op.out.h * ((op.out.w + kDwSlide - 1) / kDwSlide) * ncv;
 #define PBD_DWS(K_, S_) launch(c, dw_slide_kernel<T, K_, S_, kDwSlide, false>, grid_for(nitem), 256, 0, st, x, w, y, a, b, act, 0, \
@@ -565,6 +606,17 @@ template <class T> struct Exec {
     const long nvec = (long)N * op.in.h * op.in.w * ncv;
     ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
     const unsigned de = (unsigned)((size_t)N * op.out.h * op.out.w * op.cout_p);
+    if (dw_tiles(op)) {
+      if constexpr (sizeof(T) == 2) {
+        const int th = (op.in.h + kDwTileH - 1) / kDwTileH, tw = (op.in.w + kDwTileW - 1) / kDwTileW;
+        const dim3 grid(N * th * tw, (ncv + kDwTileCv - 1) / kDwTileCv);
+#define PBD_DWT(K_) launch(c, dw_tile_kernel<K_, true>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const float*)nullptr, \
+    (const float*)nullptr, 0, accumulate ? 1 : 0, N, op.out.h, op.out.w, ncv, th, tw, de * 2u)
+        if (op.d.k == 3) PBD_DWT(3); else if (op.d.k == 5) PBD_DWT(5); else PBD_DWT(7);
+#undef PBD_DWT
+      }
+      return;
+    }
     if (dw_slides(op) && op.d.stride == 1) {   // mirrored filter over dy: same sliding sum
       const long nitem = (long)N * op.in.h * ((op.in.w + kDwSlide - 1) / kDwSlide) * ncv;
 #define PBD_DWS(K_) launch(c, dw_slide_kernel<T, K_, 1, kDwSlide, true>, grid_for(nitem), 256, 0, st, dy, w, dx, (const float*)nullptr, \
@@ -580,22 +632,35 @@ template <class T> struct Exec {
   }
   void dw_wgrad(const OpPlan& op, const T* dy, const T* x, float* dw) {
     const int N = c->o.batch;
-    const long M = (long)N * op.out.h * op.out.w;
-    const ColGrid g = col_grid(M, op.cout_p, 16, op.d.k <= 3 ? 512 : 768 / op.d.k);
-    const size_t smem = 256 * 8 * sizeof(float) * (op.d.k <= 3 ? 3 : 7);
+    const DwWgradCfg cfg = dw_wgrad_cfg(mfma(), N, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad);
     {
-      ProfScope ps(c, "dw_wgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
-      if (op.d.k <= 3)
-        launch(c, dw_wgrad_kernel<T, 3, 3>, dim3(g.slabs, g.chunks, 1), 256, smem, st, 
-            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
-            (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
-      else
-        launch(c, dw_wgrad_kernel<T, 7, 1>, dim3(g.slabs, g.chunks, op.d.k), 256, smem, st, 
-            dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
-            (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
+      ProfScope ps(c, "dw_wgrad", bytes_of(op.in) + bytes_of(op.out), 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k,
+                   net, blk, opi);
+      if (cfg.tiled) {
+        if constexpr (sizeof(T) == 2) {
+          const int ncv = op.cout_p / 8;
+          const dim3 grid(cfg.chunks, (ncv + kDwTileCv - 1) / kDwTileCv);
+          const unsigned bytes = (unsigned)((size_t)N * op.out.h * op.out.w * op.cout_p * 2);
+#define PBD_DWW(K_) launch(c, dw_wgrad_tile_kernel<K_>, grid, 64 * K_, 0, st, (const bf16_t*)dy, (const bf16_t*)x, red(), N, op.out.h, \
+    op.out.w, ncv, cfg.tiles_h, cfg.tiles_w, cfg.ntiles, cfg.tiles_per_block, bytes)
+          if (op.d.k == 3) PBD_DWW(3); else if (op.d.k == 5) PBD_DWW(5); else PBD_DWW(7);
+#undef PBD_DWW
+        }
+      } else {
+        const ColGrid g = cfg.g;
+        const size_t smem = 256 * 8 * sizeof(float) * (op.d.k <= 3 ? 3 : 7);
+        if (op.d.k <= 3)
+          launch(c, dw_wgrad_kernel<T, 3, 3>, dim3(g.slabs, g.chunks, 1), 256, smem, st,
+              dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
+              (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
+        else
+          launch(c, dw_wgrad_kernel<T, 7, 1>, dim3(g.slabs, g.chunks, op.d.k), 256, smem, st,
+              dy, x, red(), N, op.in.h, op.in.w, op.out.h, op.out.w, op.cout_p, op.d.k, op.d.stride, op.d.pad, g,
+              (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p));
+      }
     }
-    ProfScope ps(c, "sum_partials", (double)(g.chunks + 1) * op.wn * 4, 0, net, blk, opi);
-    sum_partials(red(), dw, (long)op.wn, g.chunks);
+    ProfScope ps(c, "sum_partials", (double)(cfg.chunks + 1) * op.wn * 4, 0, net, blk, opi);
+    sum_partials(red(), dw, (long)op.wn, cfg.chunks);
   }
 
   // ---- joins / pool -------------------------------------------------------
