@@ -241,7 +241,21 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, 
   if (cv < ncv) {
     float piv[8];
     IO<T>::ld(y + (long)cv * 8, piv);
-    for (long r = r0 + row_lane; r < r1; r += rl) {
+    long r = r0 + row_lane;
+    for (; r + 3 * rl < r1; r += 4 * rl) {           // four rows in flight
+      float v[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const float d = v[u][k] - piv[k];
+          acc[k] += d;
+          acc[8 + k] = fmaf(d, d, acc[8 + k]);
+        }
+    }
+    for (; r < r1; r += rl) {
       float v[8];
       IO<T>::ld(y + (r * ncv + cv) * 8, v);
 #pragma unroll
@@ -324,16 +338,37 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     for (int k = 0; k < 8; ++k) {
       av[k] = gamma[cv * 8 + k]; bv[k] = beta[cv * 8 + k]; mv[k] = mean[cv * 8 + k]; iv[k] = invstd[cv * 8 + k];
     }
-    for (long r = r0 + row_lane; r < r1; r += rl) {
+    float sc[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) sc[k] = av[k] * iv[k];
+    long r = r0 + row_lane;
+    for (; r + rl < r1; r += 2 * rl) {               // two rows (four loads) in flight
+      float d[2][8], v[2][8];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        IO<T>::ld(dz + ((r + u * rl) * ncv + cv) * 8, d[u]);
+        IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const float yc = v[u][k] - mv[k];
+          const float dp = act_pass(fmaf(yc, sc[k], bv[k]), act) ? d[u][k] : 0.f;
+          acc[k] += dp;
+          acc[8 + k] = fmaf(dp, yc * iv[k], acc[8 + k]);
+        }
+    }
+    for (; r < r1; r += rl) {
       float d[8], v[8];
       IO<T>::ld(dz + (r * ncv + cv) * 8, d);
       IO<T>::ld(y + (r * ncv + cv) * 8, v);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const float xh = (v[k] - mv[k]) * iv[k];
-        const float dp = act_pass(fmaf(v[k] - mv[k], av[k] * iv[k], bv[k]), act) ? d[k] : 0.f;
+        const float yc = v[k] - mv[k];
+        const float dp = act_pass(fmaf(yc, sc[k], bv[k]), act) ? d[k] : 0.f;
         acc[k] += dp;
-        acc[8 + k] = fmaf(dp, xh, acc[8 + k]);
+        acc[8 + k] = fmaf(dp, yc * iv[k], acc[8 + k]);
       }
     }
   }
