@@ -131,6 +131,14 @@ int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
  * A_0..A_B, borrowed from the workspace and valid until the next relay. */
 int pbd_teacher_relay(pbd_ctx* ctx, const float* x_dev, pbd_tensor* A);
 
+/* The teacher WITHOUT relaying (Sec. III, Fig. 1: in the baseline every worker re-runs the
+ * teacher from the input up to its own block): runs T_1..T_upto from x, upto in 1..B, and
+ * leaves A_0..A_upto in the workspace; A (host array of upto+1 views, may be null) as in
+ * pbd_teacher_relay.  Later activations are stale afterwards: pbd_student_step(i) and
+ * pbd_read_act(i) need i <= upto (PBD_ESTATE otherwise).  Exists so that the cost of the
+ * redundant teacher passes can be timed next to the relay on the same kernels. */
+int pbd_teacher_prefix(pbd_ctx* ctx, const float* x_dev, int32_t upto, pbd_tensor* A);
+
 /* One student block (Algorithm 1, S.forward, S.backward(L), update_weight; Sec. II-A
  * for L; Sec. IV-B for the immediate update).  i in 1..B.  A_prev, A_i: views returned
  * by the last relay for A_{i-1} and A_i (checked).  Forward with batch statistics,

@@ -88,7 +88,8 @@ struct pbd_ctx {
   std::vector<hipEvent_t> ev_fork, ev_join;
   char* ws = nullptr;
   hipStream_t stream = nullptr;
-  bool bound = false, relayed = false, fold_dirty = true;
+  bool bound = false, fold_dirty = true;
+  int relayed_upto = 0;                 // A_0..A_relayed_upto hold the current input's activations
   std::string err;
   // profiling
   size_t lr_off = 0, loss_off = 0;      // device scalars: learning rate, per-block losses
@@ -574,7 +575,8 @@ template <class T> struct Exec {
   void dw_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
-    ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+    ProfScope ps(c, "dw_fwd", bytes_of(op.in) + bytes_of(op.out), 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k,
+                 net, blk, opi);
     const unsigned xe = (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p);
     if (dw_tiles(op)) {
       if constexpr (sizeof(T) == 2) {
@@ -604,7 +606,8 @@ template <class T> struct Exec {
   void dw_dgrad(const OpPlan& op, const T* dy, const T* w, T* dx, bool accumulate) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.in.h * op.in.w * ncv;
-    ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+    ProfScope ps(c, "dw_dgrad", bytes_of(op.in) + bytes_of(op.out), 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k,
+                 net, blk, opi);
     const unsigned de = (unsigned)((size_t)N * op.out.h * op.out.w * op.cout_p);
     if (dw_tiles(op)) {
       if constexpr (sizeof(T) == 2) {
@@ -741,11 +744,14 @@ template <class T> struct Exec {
       launch(c, cast_input_kernel<T>, grid_for(nvec), 256, 0, st, x_dev, relay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
     }
   }
-  void relay_all(const float* x_dev) {
+  void relay_all(const float* x_dev) { relay_prefix(x_dev, c->B); }
+  // T_1..T_upto from the input: the whole relay, or what a worker of the baseline without relaying
+  // runs before it can train block `upto` (Sec. III)
+  void relay_prefix(const float* x_dev, int upto) {
     if (c->fold_dirty) fold_teacher_bn();
     cast_input(x_dev);
-    for (int b = 0; b < c->B; ++b) teacher_block(b);
-    c->relayed = true;
+    for (int b = 0; b < upto; ++b) teacher_block(b);
+    c->relayed_upto = upto;
   }
   // the pointer-independent body of a step: T_1..T_B once each, then every student block
   // With `fork` (graph capture, disjoint scratch) student block b runs on its own stream as soon as
@@ -767,7 +773,7 @@ template <class T> struct Exec {
       if (fork) (void)hipStreamWaitEvent(main, c->ev_join[b], 0);
       else student_block(b, wsf(c->loss_off) + b);
     }
-    c->relayed = true;
+    c->relayed_upto = c->B;
   }
 
   // =========================================================================
@@ -1184,7 +1190,7 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
   if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
   c->graph_tried = false;
   c->bound = true;
-  c->relayed = false;
+  c->relayed_upto = 0;
   c->fold_dirty = true;
   for (BlockPlan& bp : c->net[1]) bp.stepped = false;
   // BN identity: gamma = 1, running variance = 1
@@ -1260,7 +1266,7 @@ int pbd_read_act(pbd_ctx* c, int32_t i, float* host, size_t n) {
   if (rc) return rc;
   if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
   if (i < 0 || i > c->B) return fail(c, PBD_EINVAL, "activation index %d outside 0..%d", i, c->B);
-  if (!c->relayed) return fail(c, PBD_ESTATE, "no teacher relay has run yet");
+  if (c->relayed_upto < std::max(i, 1)) return fail(c, PBD_ESTATE, "the teacher has not produced A_%d yet", i);
   const Shape s = c->act[i];
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "A_%d has %zu elements, %zu asked", i, (size_t)c->o.batch * s.c * s.h * s.w, n);
   return download_act(c, c->ws + c->r_relay + c->act_off[i], s, host);
@@ -1290,13 +1296,24 @@ int pbd_teacher_relay(pbd_ctx* c, const float* x_dev, pbd_tensor* A) {
   return PBD_OK;
 }
 
+int pbd_teacher_prefix(pbd_ctx* c, const float* x_dev, int32_t upto, pbd_tensor* A) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
+  if (upto < 1 || upto > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", upto, c->B);
+  rc = dispatch(c, [&](auto& e) { e.relay_prefix(x_dev, upto); });
+  if (rc) return rc;
+  if (A) for (int i = 0; i <= upto; ++i) fill_view(c, i, &A[i]);
+  return PBD_OK;
+}
+
 int pbd_student_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr, float* loss_dev) {
   int rc = check_ready(c);
   if (rc) return rc;
   if (i < 1 || i > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", i, c->B);
   if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
   if (!loss_dev) return fail(c, PBD_EINVAL, "loss_dev is null");
-  if (!c->relayed) return fail(c, PBD_ESTATE, "no teacher relay has run yet");
+  if (c->relayed_upto < i) return fail(c, PBD_ESTATE, "the teacher has not produced A_%d yet", i);
   if ((rc = check_view(c, A_prev, i - 1, "A_prev"))) return rc;
   if ((rc = check_view(c, A_i, i, "A_i"))) return rc;
   return dispatch(c, [&](auto& e) { e.set_lr(lr); e.student_block(i - 1, loss_dev); });
@@ -1339,7 +1356,7 @@ int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev
   }
   if (want_graph && c->gexec) {
     HIP_TRY(c, hipGraphLaunch(c->gexec, c->stream));
-    c->relayed = true;
+    c->relayed_upto = c->B;
     for (BlockPlan& bp : c->net[1]) bp.stepped = c->concurrent;
     c->net[1].back().stepped = true;
   } else {

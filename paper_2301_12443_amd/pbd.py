@@ -22,7 +22,7 @@ STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
 
 SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
            "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
-           "pbd_teacher_relay", "pbd_student_step", "pbd_distill_step", "pbd_uses_graph", "pbd_sync",
+           "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_distill_step", "pbd_uses_graph", "pbd_sync",
            "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
 
 
@@ -73,6 +73,7 @@ def lib():
         L.pbd_read_act.argtypes = [C.c_void_p, C.c_int32, fp, C.c_size_t]
         L.pbd_read_value.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
         L.pbd_teacher_relay.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pbd_tensor)]
+        L.pbd_teacher_prefix.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(pbd_tensor)]
         L.pbd_student_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(pbd_tensor), C.POINTER(pbd_tensor),
                                        C.c_float, C.c_void_p]
         L.pbd_distill_step.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
@@ -170,6 +171,14 @@ class Distiller:
         assert x_dev.is_cuda and x_dev.dtype.is_floating_point and x_dev.is_contiguous()
         views = (pbd_tensor * (self.B + 1))()
         self._check(lib().pbd_teacher_relay(self.h, x_dev.data_ptr(), views))
+        self.views = views
+        return views
+
+    def teacher_prefix(self, x_dev, upto):
+        """The teacher without relaying: T_1..T_upto from x.  Returns the views A_0..A_upto."""
+        assert x_dev.is_cuda and x_dev.dtype.is_floating_point and x_dev.is_contiguous()
+        views = (pbd_tensor * (self.B + 1))()
+        self._check(lib().pbd_teacher_prefix(self.h, x_dev.data_ptr(), upto, views))
         self.views = views
         return views
 

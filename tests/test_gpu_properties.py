@@ -68,6 +68,32 @@ def test_no_graph_option_gives_the_same_bits():
         np.testing.assert_array_equal(ta, tb)
 
 
+def test_teacher_without_relaying_gives_the_same_step():
+    """Sec. III vs Sec. IV-A: re-running T_1..T_i from the input before every block (the baseline's
+    redundant teacher work) and relaying the activations are the same computation, bit for bit."""
+    import torch
+    wl = W.CONFIGS["vgg16_dsconv"]()
+    x = torch.from_numpy(W.make_input(wl)).cuda()
+    a = parity.make_distiller(wl)
+    a.teacher_relay(x)
+    for i in range(1, wl.B + 1):
+        a.student_step(i, wl.lr)
+    a.sync()
+    b = parity.make_distiller(wl)
+    for i in range(1, wl.B + 1):
+        views = b.teacher_prefix(x, i)
+        assert views[i].ptr and (i == wl.B or not views[i + 1].ptr)
+        b.student_step(i, wl.lr)
+    b.sync()
+    np.testing.assert_array_equal(a.losses.cpu().numpy(), b.losses.cpu().numpy())
+    for ta, tb in zip(_state(a, wl), _state(b, wl)):
+        np.testing.assert_array_equal(ta, tb)
+    # a block beyond the prefix has no valid target
+    b.teacher_prefix(x, 1)
+    with pytest.raises(RuntimeError):
+        b.student_step(2, wl.lr)
+
+
 def test_relay_views_and_shared_input():
     """S_i reads the very buffer T_i read: the view of A_{i-1} handed out by the relay."""
     import torch
