@@ -25,9 +25,8 @@ PEAK_FP32_VALU_TFLOPS = 78.6
 # the figures are carried here and apply to the workload they were measured on only.
 HBM_TRAFFIC_PER_LAUNCH = {
     "vgg16_dsconv": {
-        "dw_wgrad": 17085429, "bn_bwd_reduce": 30422306, "bn_bwd_apply": 45063308, "bn_stats": 15411621,
-        "bn_apply": 30080577, "sum_partials": 7965464, "dw_fwd": 26760444, "dw_dgrad": 33013179,
-        "bn_small_fwd": 5312642, "bn_small_bwd": 8057364,
+        "bn_bwd_reduce": 30471454, "bn_bwd_apply": 45055117, "bn_apply": 30077505, "bn_stats": 15426960,
+        "dw_wgrad": 35871122, "sum_partials": 5425392, "bn_small_bwd": 8049685, "bn_small_fwd": 5318274,
     },
 }
 
@@ -57,6 +56,27 @@ def roofline_from_profile(prof, steps):
     return dict(bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit, frac=round(achieved / peak, 4),
                 traffic=None, kernel=name, avg_launch_us=round(avg_s * 1e6, 2),
                 launches_per_step=a["n"] // steps), classes
+
+
+def measure_peaks(torch):
+    """Achievable rates on this machine, for context beside the datasheet peaks: a device-to-device copy
+    (read + write bytes over time) and a large bf16 GEMM through the vendor library."""
+    def timed(fn, reps):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+    src = torch.ones(2**28, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    t_copy = timed(lambda: dst.copy_(src), 20)
+    del src, dst
+    a = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda:0")
+    b = torch.randn(8192, 8192, dtype=torch.bfloat16, device="cuda:0")
+    t_mm = timed(lambda: torch.matmul(a, b), 10)
+    return {"copy_GBs": round(2 * 2**30 / t_copy / 1e9, 1), "matmul_bf16_TFLOPs": round(2 * 8192**3 / t_mm / 1e12, 1)}
 
 
 def cpu_baseline(wl):
@@ -92,6 +112,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true",
                     help="launch the step's kernels one by one (for rocprofv3 --pmc runs)")
     ap.add_argument("--classes", action="store_true", help="also print the per-kernel-class table to stderr")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure what this box reaches on a plain 1 GiB device copy and on a library "
+                         "bf16 GEMM (8192^3, torch.matmul), reported under \"calibration\" next to the datasheet peaks")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB (a kernel of known "
                          "traffic to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings by)")
@@ -160,6 +183,8 @@ def main():
                                "teacher relay + student fwd/MSE/bwd/SGD-momentum", "lr": wl.lr},
         "roofline": roof,
     }
+    if args.peaks:
+        rec["calibration"] = measure_peaks(torch)
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(rec))
