@@ -518,6 +518,7 @@ __global__ __launch_bounds__(kSmallThreads) void bn_small_fwd_kernel(
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
 #pragma unroll
   for (int u = 0; u < kSmallRows; ++u) {
+    if (u * kSmallThreads + (tid & ~63) >= M) continue;     // no lane of this wave owns the row
     const bool ok = u * kSmallThreads + tid < M;
     float v[8];
     BufIO<T>::unpack(raw[u], v);
@@ -530,24 +531,33 @@ __global__ __launch_bounds__(kSmallThreads) void bn_small_fwd_kernel(
   }
   double sum[16];
   block_sum16(acc, sum, red, tot);
-  float mu[8], a[8], b[8];
-  const double m = (double)M;
+  // thread k < 8 finalises channel k in double (once, not in every thread) and hands the float
+  // coefficients to the block through LDS
+  __shared__ float coef[3][8];
+  if (tid < 8) {
+    const int c = cv * 8 + tid;
+    const double m = (double)M;
+    double s1 = 0.0, s2 = 0.0;
+    float pv = 0.f;
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    const int c = cv * 8 + k;
-    const double shift = sum[k] / m;
-    const double mean_d = (double)piv[k] + shift;
-    double var = sum[8 + k] / m - shift * shift;
+    for (int k = 0; k < 8; ++k)
+      if (k == tid) { s1 = sum[k]; s2 = sum[8 + k]; pv = piv[k]; }
+    const double shift = s1 / m;
+    const double mean_d = (double)pv + shift;
+    double var = s2 / m - shift * shift;
     if (var < 0.0) var = 0.0;
     const float is = (float)(1.0 / sqrt(var + (double)eps));
-    mu[k] = (float)mean_d; a[k] = gamma[c] * is; b[k] = beta[c];
-    if (tid == 0) {
-      mean[c] = mu[k];
-      invstd[c] = is;
-      rmean[c] = (1.f - rho) * rmean[c] + rho * mu[k];
-      rvar[c] = (1.f - rho) * rvar[c] + rho * (float)(var * m / (m - 1.0));
-    }
+    const float muf = (float)mean_d;
+    mean[c] = muf;
+    invstd[c] = is;
+    rmean[c] = (1.f - rho) * rmean[c] + rho * muf;
+    rvar[c] = (1.f - rho) * rvar[c] + rho * (float)(var * m / (m - 1.0));
+    coef[0][tid] = muf; coef[1][tid] = gamma[c] * is; coef[2][tid] = beta[c];
   }
+  __syncthreads();
+  float mu[8], a[8], b[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { mu[k] = coef[0][k]; a[k] = coef[1][k]; b[k] = coef[2][k]; }
 #pragma unroll
   for (int u = 0; u < kSmallRows; ++u) {
     const int r = u * kSmallThreads + tid;
@@ -589,6 +599,7 @@ __global__ __launch_bounds__(kSmallThreads) void bn_small_bwd_kernel(
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
 #pragma unroll
   for (int u = 0; u < kSmallRows; ++u) {
+    if (u * kSmallThreads + (tid & ~63) >= M) continue;     // no lane of this wave owns the row
     float d[8], v[8];                                // rows past M read as dz = 0: they add nothing
     BufIO<T>::unpack(rawd[u], d);
     BufIO<T>::unpack(rawy[u], v);
@@ -602,14 +613,22 @@ __global__ __launch_bounds__(kSmallThreads) void bn_small_bwd_kernel(
   }
   double sum[16];
   block_sum16(acc, sum, red, tot);
-  float c2[8], c3[8];
-  const double m = (double)M;
+  __shared__ float coef[2][8];
+  if (tid < 8) {
+    double sb = 0.0, sg = 0.0;
 #pragma unroll
-  for (int k = 0; k < 8; ++k) {
-    c2[k] = (float)(sum[k] / m);
-    c3[k] = (float)(sum[8 + k] / m);
-    if (tid == 0) { g_beta[cv * 8 + k] = (float)sum[k]; g_gamma[cv * 8 + k] = (float)sum[8 + k]; }
+    for (int k = 0; k < 8; ++k)
+      if (k == tid) { sb = sum[k]; sg = sum[8 + k]; }
+    const double m = (double)M;
+    g_beta[cv * 8 + tid] = (float)sb;
+    g_gamma[cv * 8 + tid] = (float)sg;
+    coef[0][tid] = (float)(sb / m);
+    coef[1][tid] = (float)(sg / m);
   }
+  __syncthreads();
+  float c2[8], c3[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) { c2[k] = coef[0][k]; c3[k] = coef[1][k]; }
 #pragma unroll
   for (int u = 0; u < kSmallRows; ++u) {
     const int r = u * kSmallThreads + tid;
