@@ -1149,6 +1149,14 @@ int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t
     }
     c->act.push_back(t);
   }
+  // training-mode BN over a single value per channel has no variance (the unbiased running
+  // variance divides by m - 1)
+  for (const BlockPlan& bp : c->net[1])
+    for (const OpPlan& op : bp.ops)
+      if (op.d.type == OP_CBA && (long)opts->batch * op.out.h * op.out.w < 2) {
+        delete c;
+        return fail(nullptr, PBD_ESHAPE, "a student batch norm would see one value per channel (batch x %d x %d)", op.out.h, op.out.w);
+      }
   // kernels address tensors with 32-bit byte offsets and use 0x80000000 as "outside every tensor"
   const long esize = opts->precision == PBD_BF16 ? 2 : 4;
   for (int which = 0; which < 2; ++which)

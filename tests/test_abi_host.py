@@ -61,6 +61,25 @@ def test_create_validates_descriptor_and_options():
         W.pack(w2)
 
 
+def test_create_rejects_degenerate_and_oversized_shapes():
+    """Limits of the kernels, enforced on the host before anything is launched."""
+    # a single block with a single op per net on a 1x1 image is a complete workload at batch 2 ...
+    t, s = W.Block(), W.Block()
+    t.cba(0, 8, 1); s.cba(0, 8, 1)
+    one = W.Workload("one", 2, (8, 1, 1), [t], [s], "f32", lr=0.1)
+    words, pool = W.pack(one)
+    assert _create(words, pool, pbd.pbd_opts(2, pbd.PBD_F32, 0.9, 1e-5, 0.1, 0))[0] == 0
+    # ... but at batch 1 the student's batch norm would see one value per channel
+    rc, msg = _create(words, pool, pbd.pbd_opts(1, pbd.PBD_F32, 0.9, 1e-5, 0.1, 0))
+    assert rc == -2 and "one value per channel" in msg
+    # 32-bit byte offsets: a tensor must stay below 2 GiB (ResNet-50 x1.5 at batch 1500, bf16: 2.2 GiB in block 1)
+    wl = W.resnet50_wide(batch=1500)
+    words, pool = W.pack(wl)
+    rc, msg = _create(words, pool, pbd.pbd_opts(1500, pbd.PBD_BF16, 0.9, 1e-5, 0.1, 0))
+    assert rc == -2 and "2 GiB" in msg
+    assert _create(words, pool, pbd.pbd_opts(256, pbd.PBD_BF16, 0.9, 1e-5, 0.1, 0))[0] == 0
+
+
 def test_workspace_sizes_and_unbound_calls():
     for name, make in W.CONFIGS.items():
         d = pbd.Distiller(make())

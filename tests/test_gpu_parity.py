@@ -80,6 +80,28 @@ def test_long_columns_take_the_chunked_bn_kernels(precision):
         _assert_bf16_step(rounded)
 
 
+def test_degenerate_shapes():
+    """One block, one 1x1 convolution on a 1x1 image, batch 4 (batch norm over four values per
+    channel; at the smallest accepted batch, 2, x-hat is +-1 whatever the input and the weight
+    gradient is a pure rounding residue, so there is nothing to compare); and a block of
+    stride-2 convolutions on a 3x5 image (every tile ragged)."""
+    t, s = W.Block(), W.Block()
+    t.cba(0, 8, 1); s.cba(0, 8, 1)
+    one = W.Workload("one", 4, (8, 1, 1), [t], [s], "f32", lr=0.1)
+    errs = parity.compare_step(one, precision="f32", steps=2, kink_floor=KINK_FLOOR)
+    _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
+    t, s = W.Block(), W.Block()
+    t.cba(0, 24, 3, 2); v = s.cba(0, 8, 3, 2, groups=8); s.cba(v, 24, 1)
+    odd = W.Workload("odd", 3, (8, 3, 5), [t], [s], "f32", lr=0.1)
+    for precision in ("f32", "bf16"):
+        errs = parity.compare_step(odd, precision=precision, steps=1, kink_floor=KINK_FLOOR if precision == "f32" else 0.0,
+                                   storage=None if precision == "f32" else "bf16", noise=precision == "bf16")
+        if precision == "f32":
+            _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
+        else:
+            _assert_bf16_step(errs)
+
+
 def test_f32_block_order_is_irrelevant():
     wl = W.tiny_cnn()
     a = parity.compare_step(wl, precision="f32", steps=1, order=(3, 1, 4, 2), kink_floor=KINK_FLOOR)
