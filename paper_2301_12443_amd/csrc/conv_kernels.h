@@ -135,8 +135,9 @@ struct IgemmArgs {
   int R, S, stride, pad;
   int M;      // N*HO*WO
   int Kred;   // R*S*CA
-  int ksteps_per_split;  // reduction steps of IG_BK handled by one blockIdx.z (split-K)
+  int ksteps_per_split;  // reduction steps of IG_BK handled by one K slice (split-K)
   unsigned a_bytes, b_bytes;  // sizes of the A tensor and of the weight matrix
+  int tiles_m, tiles_n, splits;   // the 1-D grid holds tiles_m * tiles_n * splits workgroups
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
@@ -145,6 +146,12 @@ enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 // LDS row pitch 96 B: both the MFMA fragment reads (row = lane%32, 16-byte chunk = lane/32) and the
 // staging writes (row = lane/4, chunk = lane%4) run at the full 128 B/clk with it (80 B makes the writes conflict)
 constexpr int IG_BK = 32, IG_PITCH = IG_BK + 16;
+
+// workgroup w runs on XCD w % 8: give XCD c the c-th contiguous run of the `total` work items
+__device__ __forceinline__ int xcd_contiguous(int w, int total) {
+  const int q = total >> 3, r = total & 7, c = w & 7;
+  return c * q + min(c, r) + (w >> 3);
+}
 
 // UNI: the channel count of the gathered tensor is a multiple of the 32-element K step, so a step
 // lies inside one filter tap and (r, s, c0) are the same for the whole workgroup: they live in
@@ -169,7 +176,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  // Workgroups are dealt to the 8 XCDs round-robin, each with an L2 of its own.  Remapped so that
+  // an XCD works through a contiguous run of tiles (column tiles of one row tile next to each other,
+  // then the next row tile): the 3x3 halo rows and the rows shared by column tiles are then re-read
+  // from that XCD's L2 instead of crossing the fabric once per tap.
+  const int tile = xcd_contiguous(blockIdx.x, g.tiles_m * g.tiles_n * g.splits);
+  const int tile_n = tile % g.tiles_n, tile_m = (tile / g.tiles_n) % g.tiles_m, kslice = tile / (g.tiles_n * g.tiles_m);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int chunk = tid & 3;
   const int sh = g.stride == 2 ? 1 : 0, smask = g.stride - 1;
 
@@ -196,7 +209,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     brow[i] = (row < BN && n0 + row < g.NC) ? (n0 + row) * g.Kred : -1;
   }
   // reduction position of this thread's chunk: kk = (r*S + s)*CA + c
-  const int kt0 = blockIdx.z * g.ksteps_per_split;
+  const int kt0 = kslice * g.ksteps_per_split;
   int kk = kt0 * IG_BK + (UNI ? 0 : chunk * 8);
   int r, s, c;
   {
@@ -365,7 +378,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
 #pragma unroll
         for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
         if (EPI == EPI_PARTIAL) {
-          float* dst = reinterpret_cast<float*>(Out) + ((size_t)blockIdx.z * g.M + row) * g.NC + col;
+          float* dst = reinterpret_cast<float*>(Out) + ((size_t)kslice * g.M + row) * g.NC + col;
           *reinterpret_cast<float4*>(dst) = make_float4(o[0], o[1], o[2], o[3]);
           continue;
         }

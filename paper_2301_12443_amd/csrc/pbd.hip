@@ -467,8 +467,10 @@ template <class T> struct Exec {
     const IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred);
     const int nk = (g.Kred + IG_BK - 1) / IG_BK;
     g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
-    dim3 grid((g.M + cfg.BM - 1) / cfg.BM, (g.NC + cfg.BN - 1) / cfg.BN,
-              (nk + g.ksteps_per_split - 1) / g.ksteps_per_split);
+    g.tiles_m = (g.M + cfg.BM - 1) / cfg.BM;
+    g.tiles_n = (g.NC + cfg.BN - 1) / cfg.BN;
+    g.splits = (nk + g.ksteps_per_split - 1) / g.ksteps_per_split;
+    const dim3 grid(g.tiles_m * g.tiles_n * g.splits);
 #define PBD_IG(BM_, BN_, EPI_, OUT_) do { \
       if (g.CA % IG_BK == 0) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, true>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); \
       else launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, false>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); } while (0)
@@ -478,15 +480,15 @@ template <class T> struct Exec {
     // a rocprofv3 kernel trace: igemm_<fwd|dgrad>_<BM>x<BN>_<epilogue>
     static const char* const kEpi[] = {"store", "affine", "accum", "partial"};
     char name[32];
-    snprintf(name, sizeof name, "igemm_%s_%dx%d_%s", MODE ? "dgrad" : "fwd", cfg.BM, cfg.BN, kEpi[grid.z > 1 ? 3 : epi]);
-    if (grid.z > 1) {
+    snprintf(name, sizeof name, "igemm_%s_%dx%d_%s", MODE ? "dgrad" : "fwd", cfg.BM, cfg.BN, kEpi[g.splits > 1 ? 3 : epi]);
+    if (g.splits > 1) {
       {
         ProfScope ps(c, name, bytes, flops, net, blk, opi);
         PBD_IG_BM(EPI_PARTIAL, reinterpret_cast<bf16_t*>(red()));
       }
       const long nvec = (long)g.M * g.NC / 8;
-      ProfScope ps(c, "splitk_epilogue", (double)nvec * 8 * (4.0 * grid.z + 2), 0, net, blk, opi);
-      launch(c, splitk_epilogue_kernel, grid_for(nvec), 256, 0, st, red(), out, a, b, act, epi, nvec, g.NC / 8, (int)grid.z);
+      ProfScope ps(c, "splitk_epilogue", (double)nvec * 8 * (4.0 * g.splits + 2), 0, net, blk, opi);
+      launch(c, splitk_epilogue_kernel, grid_for(nvec), 256, 0, st, red(), out, a, b, act, epi, nvec, g.NC / 8, g.splits);
     } else {
       ProfScope ps(c, name, bytes, flops, net, blk, opi);
       if (epi == EPI_AFFINE_ACT) PBD_IG_BM(EPI_AFFINE_ACT, out);
