@@ -145,7 +145,11 @@ enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 
 // LDS row pitch 96 B: both the MFMA fragment reads (row = lane%32, 16-byte chunk = lane/32) and the
 // staging writes (row = lane/4, chunk = lane%4) run at the full 128 B/clk with it (80 B makes the writes conflict)
-constexpr int IG_BK = 32, IG_PITCH = IG_BK + 16;
+// K step 32 (any channel count) or 64 (channel counts that are multiples of 64: a row's chunk is
+// then a whole 128-byte cache line, 8 lanes wide, instead of half of one).  LDS row pitch 96 / 144
+// bytes: conflict-free for the fragment reads of 16-lane groups in both cases.
+constexpr int IG_BK = 32;
+constexpr int ig_pitch(int bk) { return bk == 64 ? 72 : 48; }
 
 // workgroup w runs on XCD w % 8: give XCD c the c-th contiguous run of the `total` work items
 __device__ __forceinline__ int xcd_contiguous(int w, int total) {
@@ -156,7 +160,7 @@ __device__ __forceinline__ int xcd_contiguous(int w, int total) {
 // UNI: the channel count of the gathered tensor is a multiple of the 32-element K step, so a step
 // lies inside one filter tap and (r, s, c0) are the same for the whole workgroup: they live in
 // scalar registers and a load costs a lane two adds, two compares, an add and a select.
-template <int MODE, int BM, int BN, int EPI, bool UNI>
+template <int MODE, int BM, int BN, int EPI, bool UNI, int BK = IG_BK>
 __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A,
                                                     const bf16_t* __restrict__ Bw,
                                                     bf16_t* __restrict__ Out,
@@ -169,10 +173,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   constexpr int TM = BM / (WAVES_M * 32);
   constexpr int TN = (BN / (WAVES_N * 32)) > 0 ? BN / (WAVES_N * 32) : 1;
   constexpr bool kIdleWaves = BN / (WAVES_N * 32) == 0;      // BM 64, BN 32: waves with wn = 1 only stage tiles
-  constexpr int A_LOADS = BM / 64;
-  constexpr int B_LOADS = (BN * 4 + 255) / 256;  // 16-byte chunks of the weight tile per thread
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * IG_PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * IG_PITCH];
+  constexpr int CPR = BK / 8, RPP = 256 / CPR;   // 16-byte chunks per tile row, rows staged per pass
+  constexpr int PITCH = ig_pitch(BK);
+  constexpr int A_LOADS = BM / RPP;
+  constexpr int B_LOADS = (BN + RPP - 1) / RPP;  // 16-byte chunks of the weight tile per thread
+  static_assert(!(BK == 64) || UNI, "the 64-wide K step needs uniform taps");
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * PITCH];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * PITCH];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -183,7 +190,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   const int tile = xcd_contiguous(blockIdx.x, g.tiles_m * g.tiles_n * g.splits);
   const int tile_n = tile % g.tiles_n, tile_m = (tile / g.tiles_n) % g.tiles_m, kslice = tile / (g.tiles_n * g.tiles_m);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int chunk = tid & 3;
+  const int chunk = tid % CPR, prow = tid / CPR;
   const int sh = g.stride == 2 ? 1 : 0, smask = g.stride - 1;
 
   // The A rows this thread stages, decoded once.  All offsets are 32-bit element indices
@@ -192,7 +199,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   bool rvalid[A_LOADS];
 #pragma unroll
   for (int i = 0; i < A_LOADS; ++i) {
-    const int m = m0 + (tid >> 2) + 64 * i;
+    const int m = m0 + prow + RPP * i;
     rvalid[i] = m < g.M;
     const int mm = rvalid[i] ? m : 0;
     const int b_ = mm % g.WO;
@@ -205,12 +212,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   int brow[B_LOADS];
 #pragma unroll
   for (int i = 0; i < B_LOADS; ++i) {
-    const int row = (tid >> 2) + 64 * i;
+    const int row = prow + RPP * i;
     brow[i] = (row < BN && n0 + row < g.NC) ? (n0 + row) * g.Kred : -1;
   }
   // reduction position of this thread's chunk: kk = (r*S + s)*CA + c
   const int kt0 = kslice * g.ksteps_per_split;
-  int kk = kt0 * IG_BK + (UNI ? 0 : chunk * 8);
+  int kk = kt0 * BK + (UNI ? 0 : chunk * 8);
   int r, s, c;
   {
     const int rs = kk / g.CA;
@@ -252,8 +259,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
       }
 #pragma unroll
       for (int i = 0; i < B_LOADS; ++i) breg[S_][i] = buffer_load16(b_rsrc, bbase[i] + (unsigned)kk * 2u);
-      kk += IG_BK;
-      c += IG_BK;
+      kk += BK;
+      c += BK;
       const bool wrap = c >= g.CA;
       c = wrap ? 0 : c;
       s += wrap ? 1 : 0;
@@ -283,9 +290,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i)
       breg[S_][i] = buffer_load16(b_rsrc, (brow[i] >= 0 && kvalid) ? (unsigned)(brow[i] + kk) * 2u : kOutOfRange);
-    kk += IG_BK;
-    c += IG_BK;
-    if (g.CA >= IG_BK) {          // at most one wrap per step
+    kk += BK;
+    c += BK;
+    if (g.CA >= BK) {             // at most one wrap per step
       const bool wrap = c >= g.CA;
       c -= wrap ? g.CA : 0;
       s += wrap ? 1 : 0;
@@ -303,11 +310,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     constexpr int S_ = decltype(stage)::value;
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i)
-      *reinterpret_cast<uint4*>(&As[buf][((tid >> 2) + 64 * i) * IG_PITCH + chunk * 8]) = areg[S_][i];
+      *reinterpret_cast<uint4*>(&As[buf][(prow + RPP * i) * PITCH + chunk * 8]) = areg[S_][i];
 #pragma unroll
     for (int i = 0; i < B_LOADS; ++i) {
-      const int row = (tid >> 2) + 64 * i;
-      if (row < BN) *reinterpret_cast<uint4*>(&Bs[buf][row * IG_PITCH + chunk * 8]) = breg[S_][i];
+      const int row = prow + RPP * i;
+      if (row < BN) *reinterpret_cast<uint4*>(&Bs[buf][row * PITCH + chunk * 8]) = breg[S_][i];
     }
   };
 
@@ -322,7 +329,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nk = min(g.ksteps_per_split, (g.Kred + IG_BK - 1) / IG_BK - kt0);
+  const int nk = min(g.ksteps_per_split, (g.Kred + BK - 1) / BK - kt0);
   using S0 = std::integral_constant<int, 0>;
   using S1 = std::integral_constant<int, 1>;
   load_tile(S0{});
@@ -336,16 +343,16 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     if (kt + 2 < nk) load_tile(Cur{});          // stage C_ went to LDS one iteration ago
     if (!(kIdleWaves && wn > 0)) {
 #pragma unroll
-      for (int ks = 0; ks < IG_BK / 16; ++ks) {
+      for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8 af[TM], bfr[TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
           af[i] = *reinterpret_cast<const bf16x8*>(
-              &As[C_][(wm * TM * 32 + i * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
+              &As[C_][(wm * TM * 32 + i * 32 + (lane & 31)) * PITCH + ks * 16 + (lane >> 5) * 8]);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           bfr[j] = *reinterpret_cast<const bf16x8*>(
-              &Bs[C_][(wn * TN * 32 + j * 32 + (lane & 31)) * IG_PITCH + ks * 16 + (lane >> 5) * 8]);
+              &Bs[C_][(wn * TN * 32 + j * 32 + (lane & 31)) * PITCH + ks * 16 + (lane >> 5) * 8]);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -250,20 +250,22 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
 // Tile shape and split-K factor of an implicit-GEMM launch.  256 CUs want >= 512 workgroups: layers
 // with few output tiles (late VGG / ResNet stages at small batch x image) first drop to 64-row tiles
 // and then cut their reduction into slices that run side by side.
-struct IgemmCfg { int BM, BN, splits; };
-IgemmCfg igemm_cfg(long M, int NC, int Kred) {
+struct IgemmCfg { int BM, BN, BK, splits; };
+IgemmCfg igemm_cfg(long M, int NC, int Kred, int CA) {
   IgemmCfg c;
+  c.BK = CA % 64 == 0 ? 64 : 32;       // whole cache lines per row chunk where the channel count allows
   c.BN = NC >= 128 ? 128 : (NC > 32 ? 64 : 32);
   const long tn = (NC + c.BN - 1) / c.BN;
   c.BM = ((M + 127) / 128) * tn >= 512 ? 128 : 64;
-  if (c.BN == 128 && ((M + 255) / 256) * tn >= 1024) c.BM = 256;
+  if (c.BK == 32 && c.BN == 128 && ((M + 255) / 256) * tn >= 1024) c.BM = 256;
   const long tiles = ((M + c.BM - 1) / c.BM) * tn;
-  const int nk = (Kred + IG_BK - 1) / IG_BK;
+  const int nk = (Kred + c.BK - 1) / c.BK, nk32 = (Kred + 31) / 32;
   c.splits = 1;
-  if (tiles < 512 && nk >= 32) c.splits = (int)std::max(1L, std::min<long>(std::min<long>((1024 + tiles - 1) / tiles, nk / 16), 32L));
+  if (tiles < 512 && nk32 >= 32)
+    c.splits = (int)std::max(1L, std::min<long>(std::min<long>(std::min<long>((1024 + tiles - 1) / tiles, nk32 / 16), 32L), nk));
   return c;
 }
-int igemm_splits(long M, int NC, int Kred) { return igemm_cfg(M, NC, Kred).splits; }
+int igemm_splits(long M, int NC, int Kred, int CA) { return igemm_cfg(M, NC, Kred, CA).splits; }
 
 constexpr int kMseBlocks = 1024;
 
@@ -281,7 +283,7 @@ int plan(pbd_ctx* c) {
       if (op.d.type != OP_CBA) continue;
       if (!op.dw && bf) {
         const long M = (long)c->o.batch * op.out.h * op.out.w;
-        need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p) * M * op.d.c_out * 4);
+        need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p) * M * op.d.c_out * 4);
       }
       op.t_w = take(op.wn * es);
       op.t_gamma = take(op.cout_p * 4); op.t_beta = take(op.cout_p * 4);
@@ -358,8 +360,8 @@ int plan(pbd_ctx* c) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
           need_red((size_t)w.splits * op.wn * 4);
           const long Min = (long)c->o.batch * op.in.h * op.in.w;
-          need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p) * M * op.d.c_out * 4);
-          need_red((size_t)igemm_splits(Min, op.cin_p, op.d.k * op.d.k * op.d.c_out) * Min * op.cin_p * 4);
+          need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p) * M * op.d.c_out * 4);
+          need_red((size_t)igemm_splits(Min, op.cin_p, op.d.k * op.d.k * op.d.c_out, op.d.c_out) * Min * op.cin_p * 4);
         }
       } else if (op.d.type == OP_POOL) {
         op.idx = s; s += align_up((size_t)M * op.cout_p);
@@ -464,15 +466,16 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
-    const IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred);
-    const int nk = (g.Kred + IG_BK - 1) / IG_BK;
+    const IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred, g.CA);
+    const int nk = (g.Kred + cfg.BK - 1) / cfg.BK;
     g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
     g.tiles_m = (g.M + cfg.BM - 1) / cfg.BM;
     g.tiles_n = (g.NC + cfg.BN - 1) / cfg.BN;
     g.splits = (nk + g.ksteps_per_split - 1) / g.ksteps_per_split;
     const dim3 grid(g.tiles_m * g.tiles_n * g.splits);
 #define PBD_IG(BM_, BN_, EPI_, OUT_) do { \
-      if (g.CA % IG_BK == 0) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, true>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); \
+      if (cfg.BK == 64) { if constexpr (BM_ != 256) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, true, 64>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); } \
+      else if (g.CA % IG_BK == 0) launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, true>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); \
       else launch(c, igemm_kernel<MODE, BM_, BN_, EPI_, false>, grid, 256, 0, st, A, Bw, OUT_, a, b, act, g); } while (0)
 #define PBD_IG_BN(BM_, EPI_, OUT_) do { if (cfg.BN == 128) PBD_IG(BM_, 128, EPI_, OUT_); else if (cfg.BN == 64) PBD_IG(BM_, 64, EPI_, OUT_); else PBD_IG(BM_, 32, EPI_, OUT_); } while (0)
 #define PBD_IG_BM(EPI_, OUT_) do { if (cfg.BM == 256) PBD_IG(256, 128, EPI_, OUT_); else if (cfg.BM == 128) PBD_IG_BN(128, EPI_, OUT_); else PBD_IG_BN(64, EPI_, OUT_); } while (0)
