@@ -458,6 +458,7 @@ struct WgradTrArgs {
   int pix_per_split;  // multiple of 32
   int dn, dp, dq;     // 32 pixels = dn images + dp rows + dq columns (mixed radix P, Q)
   unsigned dy_bytes, x_bytes;
+  int tiles_k, tiles_j, splits;   // the 1-D grid holds tiles_k * tiles_j * splits workgroups
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -487,8 +488,11 @@ __global__ __launch_bounds__(256) void wgrad_tr_kernel(const bf16_t* __restrict_
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int k0 = blockIdx.x * TM, j0 = blockIdx.y * TN;
-  const int mbeg = blockIdx.z * g.pix_per_split;
+  // all tiles of one pixel slice read the same rows of dy and x: keep them on one XCD (one L2)
+  const int tile = xcd_contiguous(blockIdx.x, g.tiles_k * g.tiles_j * g.splits);
+  const int slice = tile / (g.tiles_k * g.tiles_j);
+  const int k0 = ((tile / g.tiles_j) % g.tiles_k) * TM, j0 = (tile % g.tiles_j) * TN;
+  const int mbeg = slice * g.pix_per_split;
   const int mend = min(g.M, mbeg + g.pix_per_split);
   const int nsteps = (mend - mbeg + BKP - 1) / BKP;
   const __amdgpu_buffer_rsrc_t rdy = tensor_rsrc(dy, g.dy_bytes), rx = tensor_rsrc(x, g.x_bytes);
@@ -593,7 +597,7 @@ __global__ __launch_bounds__(256) void wgrad_tr_kernel(const bf16_t* __restrict_
     __syncthreads();
   }
 
-  float* out = part + (size_t)blockIdx.z * g.K * g.J;
+  float* out = part + (size_t)slice * g.K * g.J;
 #pragma unroll
   for (int j = 0; j < TWN; ++j) {
     const int col = j0 + wn * (TN / 2) + j * 32 + (lane & 31);

@@ -236,7 +236,10 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
   w.tiles_k = (K + w.TM - 1) / w.TM;
   w.tiles_j = (J + w.TN - 1) / w.TN;
   const long tiles = (long)w.tiles_k * w.tiles_j;
-  long splits = std::max(1L, 256 / tiles);
+  // long reductions: three workgroups per compute unit hide the load latency; short ones: one per
+  // compute unit, or the partial sums cost more than the overlap gains
+  const long target = M >= 65536 ? 768 : 256;
+  long splits = std::max(1L, (target + tiles - 1) / tiles);
   const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
   splits = std::min(splits, max_by_mem);
   splits = std::min(splits, (M + w.BKP - 1) / w.BKP);
@@ -538,8 +541,9 @@ template <class T> struct Exec {
         WgradTrArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                       op.d.stride, op.d.pad, (int)M, J, w.pix_per_split,
                       w.BKP / pq, (w.BKP % pq) / op.out.w, w.BKP % op.out.w,
-                      (unsigned)(M * op.d.c_out * 2), (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2)};
-        dim3 grid(w.tiles_k, w.tiles_j, w.splits);
+                      (unsigned)(M * op.d.c_out * 2), (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2),
+                      w.tiles_k, w.tiles_j, w.splits};
+        const dim3 grid(w.tiles_k * w.tiles_j * w.splits);
         float* part = w.splits == 1 ? dw : red();
         {
           char name[32];
