@@ -1203,6 +1203,54 @@ __global__ __launch_bounds__(256) void dw_dgrad_kernel(const T* __restrict__ dy,
   }
 }
 
+// Backward-data of a stride-2 depthwise convolution: an input pixel only meets the taps whose
+// parity matches its own, (K+1)/2 per dimension, so only those are visited (K*K/4 instead of K*K
+// masked loads).
+template <class T, int K>
+__global__ __launch_bounds__(256) void dw_dgrad_s2_kernel(const T* __restrict__ dy, const T* __restrict__ w,
+                                                          T* __restrict__ dx, int N, int H, int W, int P, int Q,
+                                                          int ncv, int pad, int accumulate, unsigned dy_elems) {
+  constexpr int HK = (K + 1) / 2;
+  const long nvec = (long)N * H * W * ncv;
+  const __amdgpu_buffer_rsrc_t dr = tensor_rsrc(dy, dy_elems * (unsigned)sizeof(T));
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int ww = (int)(pix % W); pix /= W;
+    const int h = (int)(pix % H);
+    const int n = (int)(pix / H);
+    const int ph = h + pad, qw = ww + pad, r0 = ph & 1, s0 = qw & 1;
+    float acc[8];
+    if (accumulate) IO<T>::ld(dx + i * 8, acc);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    }
+    typename BufIO<T>::Raw raw[HK * HK];
+#pragma unroll
+    for (int a = 0; a < HK; ++a)
+#pragma unroll
+      for (int b = 0; b < HK; ++b) {
+        const int r = r0 + 2 * a, s = s0 + 2 * b;
+        const int p = (ph - r) >> 1, q = (qw - s) >> 1;
+        const bool ok = r < K && s < K && (unsigned)p < (unsigned)P && (unsigned)q < (unsigned)Q;
+        raw[a * HK + b] = BufIO<T>::issue(dr, (unsigned)(((n * P + p) * Q + q) * ncv + cv) * 8u, ok);
+      }
+#pragma unroll
+    for (int a = 0; a < HK; ++a)
+#pragma unroll
+      for (int b = 0; b < HK; ++b) {
+        const int r = min(r0 + 2 * a, K - 1), s = min(s0 + 2 * b, K - 1);   // clamped taps carry zeros
+        float d[8], f[8];
+        BufIO<T>::unpack(raw[a * HK + b], d);
+        IO<T>::ld(w + ((long)(r * K + s) * ncv + cv) * 8, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(d[e], f[e], acc[e]);
+      }
+    IO<T>::st(dx + i * 8, acc);
+  }
+}
+
 // dW[r][t][c] = sum over output pixels dY * X(shifted).  ROWS tap rows per block: 3x3 filters keep all
 // 9 x 8 accumulators in registers and read dY / X once; larger filters take one tap row per
 // blockIdx.z (grid = (slabs, chunks, k / ROWS)).  All taps of a pixel are requested before use.

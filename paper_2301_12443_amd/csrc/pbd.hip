@@ -637,6 +637,13 @@ template <class T> struct Exec {
 #undef PBD_DWS
       return;
     }
+    if (dw_slides(op) && op.d.stride == 2) {   // only the taps whose parity matches the input pixel
+#define PBD_DWD2(K_) launch(c, dw_dgrad_s2_kernel<T, K_>, grid_for(nvec), 256, 0, st, dy, w, dx, N, op.in.h, op.in.w, op.out.h, \
+    op.out.w, ncv, op.d.pad, accumulate ? 1 : 0, de)
+      if (op.d.k == 3) PBD_DWD2(3); else if (op.d.k == 5) PBD_DWD2(5); else PBD_DWD2(7);
+#undef PBD_DWD2
+      return;
+    }
 #define PBD_DWD(KK_) launch(c, dw_dgrad_kernel<T, KK_>, grid_for(nvec), 256, 0, st, dy, w, dx, N, op.in.h, op.in.w, op.out.h, \
     op.out.w, ncv, op.d.k, op.d.stride, op.d.pad, accumulate ? 1 : 0, de)
     if (op.d.k == 3) PBD_DWD(9); else if (op.d.k == 5) PBD_DWD(25); else if (op.d.k == 7) PBD_DWD(49); else PBD_DWD(1);
