@@ -25,8 +25,8 @@ PEAK_FP32_VALU_TFLOPS = 78.6
 # the figures are carried here and apply to the workload they were measured on only.
 HBM_TRAFFIC_PER_LAUNCH = {
     "vgg16_dsconv": {
-        "bn_bwd_reduce": 30471454, "bn_bwd_apply": 45055117, "bn_apply": 30077505, "bn_stats": 15426960,
-        "dw_wgrad": 35871122, "sum_partials": 5425392, "bn_small_bwd": 8049685, "bn_small_fwd": 5318274,
+        "bn_bwd_reduce": 30463263, "bn_bwd_apply": 45063308, "bn_apply": 30080577, "bn_stats": 15426981,
+        "dw_wgrad": 35863403, "sum_partials": 7974621, "bn_small_bwd": 7979547,
     },
 }
 
