@@ -75,7 +75,7 @@ typedef struct {
 
 /* One timed kernel launch (see pbd_set_profile). */
 typedef struct {
-  char name[32];        /* kernel class, e.g. "conv_fwd_mfma", "bn_apply" */
+  char name[32];        /* kernel class, e.g. "igemm_fwd_128x128_affine", "bn_apply" */
   float ms;             /* HIP-event time of this launch on the bound stream */
   double bytes;         /* algorithmic bytes: tensors the operation must touch once */
   double flops;         /* algorithmic flops: 2 x MACs of the unpadded problem, else 0 */

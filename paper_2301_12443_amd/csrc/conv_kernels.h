@@ -143,11 +143,11 @@ struct IgemmArgs {
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
 enum { EPI_STORE = 0, EPI_AFFINE_ACT = 1, EPI_ACCUM = 2, EPI_PARTIAL = 3 };
 
-// LDS row pitch 96 B: both the MFMA fragment reads (row = lane%32, 16-byte chunk = lane/32) and the
-// staging writes (row = lane/4, chunk = lane%4) run at the full 128 B/clk with it (80 B makes the writes conflict)
 // K step 32 (any channel count) or 64 (channel counts that are multiples of 64: a row's chunk is
 // then a whole 128-byte cache line, 8 lanes wide, instead of half of one).  LDS row pitch 96 / 144
-// bytes: conflict-free for the fragment reads of 16-lane groups in both cases.
+// bytes: conflict-free for the fragment reads (row = lane%32, 16-byte chunk = lane/32) in both
+// cases; at 96 bytes the staging writes (row = lane/4, chunk = lane%4) are conflict-free too, at 144
+// bytes neighbouring rows overlap on 4 of 32 banks.
 constexpr int IG_BK = 32;
 constexpr int ig_pitch(int bk) { return bk == 64 ? 72 : 48; }
 
