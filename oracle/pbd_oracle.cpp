@@ -21,6 +21,17 @@
 // with zero padding; max-pool gradients go to the first maximum in row-major
 // window order.
 //
+// Architecture round of a NAS supernet (Sec. VI-A, the neural architecture search workload): a mix
+// op's weights are p = softmax(alpha) over its candidates, alpha being the trainable architecture
+// parameters; a step has a second forward/backward round that trains alpha with the weights frozen,
+// and that round is an ordinary training step of the block.  Here: same forward (student BN in
+// training mode, running statistics updated), same loss, backward through the block to every mix,
+//   g_k = <dL/dz, y_k>,   dL/dalpha_j = p_j (g_j - sum_k p_k g_k)      (chain rule through softmax)
+// then the SGD-momentum rule on alpha only.  Readings where the paper is silent: the same optimiser
+// rule for alpha as for weights with a learning rate of its own; every candidate evaluated and
+// mixed (no sampling of paths); alpha starts at ln p_k of the descriptor's weights, and a mix keeps
+// the descriptor's p_k untouched until alpha is set or trained.
+//
 // Optional storage rounding (storage = 1): the bf16 path of the method keeps tensors
 // (activations, compute copies of weights, activation gradients) in bfloat16 and
 // everything else in wider precision.  ReLU masks, max-pool winners and the bf16
@@ -34,7 +45,8 @@
 // product, adjoint identities for dgrad/wgrad, BN closed forms, central finite
 // differences of loss_i over every parameter, PyTorch-CPU fp64 autograd on the
 // same blocks, SGD closed form, relay == redundant bitwise, block-order
-// independence.
+// independence; for the architecture round central finite differences of loss_i over alpha,
+// PyTorch autograd with alpha as a leaf, sum_j dL/dalpha_j = 0, identical candidates.
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
@@ -408,6 +420,9 @@ struct NetBase {
   virtual long value_numel(int b, int v) = 0;
   virtual double kink_margin(int b) = 0;
   virtual void get_value(int b, int v, double* out) = 0;
+  virtual int set_alpha(int b, int j, const double* a, int n) = 0;
+  virtual int get_alpha(int kind, int b, int j, double* out, int n) = 0;
+  virtual void relay_arch_step(const double* x, double lr, double* losses) = 0;
 };
 
 template <class R>
@@ -431,6 +446,10 @@ struct Net final : NetBase {
   };
   std::vector<std::vector<std::vector<R>>> val;  // [block][value]
   std::vector<std::vector<Saved>> saved;         // [block][op]
+
+  // architecture parameters of the student's mix ops [block][op]: value, gradient, momentum;
+  // empty until set or trained (the mix then uses the descriptor's weights)
+  std::vector<std::vector<std::vector<R>>> alpha, alpha_g, alpha_v;
 
   int storage = 0;  // 1: round stored tensors to bfloat16
 
@@ -473,6 +492,66 @@ struct Net final : NetBase {
     A.resize(d.B + 1);
     val.resize(d.B);
     saved.resize(d.B);
+    alpha.resize(d.B);
+    alpha_g.resize(d.B);
+    alpha_v.resize(d.B);
+    for (int b = 0; b < d.B; ++b) {
+      alpha[b].resize(d.net[1][b].ops.size());
+      alpha_g[b].resize(d.net[1][b].ops.size());
+      alpha_v[b].resize(d.net[1][b].ops.size());
+    }
+  }
+
+  // mixing weights of student mix op j of block b: softmax(alpha) once alpha exists
+  std::vector<R> probs(int b, int j) const {
+    const OpD& o = d.net[1][b].ops[j];
+    std::vector<R> p(o.nin);
+    const std::vector<R>& a = alpha[b][j];
+    if (a.empty()) {
+      for (int k = 0; k < o.nin; ++k) p[k] = (R)d.pool[o.pofs + k];
+      return p;
+    }
+    const R top = *std::max_element(a.begin(), a.end());
+    R sum = 0;
+    for (int k = 0; k < o.nin; ++k) { p[k] = std::exp(a[k] - top); sum += p[k]; }
+    for (int k = 0; k < o.nin; ++k) p[k] /= sum;
+    return p;
+  }
+  void define_alpha(int b) {
+    const BlockD& blk = d.net[1][b];
+    for (size_t j = 0; j < blk.ops.size(); ++j) {
+      const OpD& o = blk.ops[j];
+      if (o.type != OP_MIX) continue;
+      if (alpha[b][j].empty()) {
+        alpha[b][j].resize(o.nin);
+        for (int k = 0; k < o.nin; ++k) alpha[b][j][k] = (R)std::log(d.pool[o.pofs + k]);
+      }
+      if (alpha_g[b][j].empty()) alpha_g[b][j].assign(o.nin, R(0));
+      if (alpha_v[b][j].empty()) alpha_v[b][j].assign(o.nin, R(0));
+    }
+  }
+  int set_alpha(int b, int j, const double* a, int n) override {
+    if (b < 0 || b >= d.B || j < 0 || j >= (int)d.net[1][b].ops.size()) return -1;
+    const OpD& o = d.net[1][b].ops[j];
+    if (o.type != OP_MIX || n != o.nin) return -1;
+    alpha[b][j].resize(n);
+    for (int k = 0; k < n; ++k) alpha[b][j][k] = (R)a[k];
+    return 0;
+  }
+  // kind 0: alpha, 1: its gradient, 2: its momentum, 3: the mixing weights in use
+  int get_alpha(int kind, int b, int j, double* out, int n) override {
+    if (b < 0 || b >= d.B || j < 0 || j >= (int)d.net[1][b].ops.size()) return -1;
+    const OpD& o = d.net[1][b].ops[j];
+    if (o.type != OP_MIX || n != o.nin) return -1;
+    if (kind == 3) {
+      const std::vector<R> p = probs(b, j);
+      for (int k = 0; k < n; ++k) out[k] = (double)p[k];
+      return 0;
+    }
+    const std::vector<R>& src = kind == 0 ? alpha[b][j] : kind == 1 ? alpha_g[b][j] : alpha_v[b][j];
+    if (kind < 0 || kind > 2 || (int)src.size() != n) return -1;
+    for (int k = 0; k < n; ++k) out[k] = (double)src[k];
+    return 0;
   }
 
   std::vector<R>* find(int kind, int net, int b, int j, int slot) {
@@ -598,10 +677,9 @@ struct Net final : NetBase {
         act_fwd(sv[j].pre.data(), out.data(), out.size(), o.act);
         rnd(out);
       } else {
-        for (int k = 0; k < o.nin; ++k) {
-          const R p = (R)d.pool[o.pofs + k];
-          for (size_t i = 0; i < out.size(); ++i) out[i] += p * v[o.in[k]][i];
-        }
+        const std::vector<R> p = probs(b, (int)j);
+        for (int k = 0; k < o.nin; ++k)
+          for (size_t i = 0; i < out.size(); ++i) out[i] += p[k] * v[o.in[k]][i];
         rnd(out);
       }
     }
@@ -667,8 +745,9 @@ struct Net final : NetBase {
     }
   }
 
-  // gradient of loss_i w.r.t. every parameter of S_i; dval[0] (w.r.t. A_{i-1}) is never formed
-  void student_backward(int b, std::vector<R>& dout) {
+  // gradient of loss_i w.r.t. every parameter of S_i; dval[0] (w.r.t. A_{i-1}) is never formed.
+  // arch: the architecture round - gradients of alpha instead of those of the frozen weights
+  void student_backward(int b, std::vector<R>& dout, bool arch = false) {
     const BlockD& blk = d.net[1][b];
     auto& v = val[b];
     std::vector<std::vector<R>> dv(blk.ops.size() + 1);
@@ -692,8 +771,9 @@ struct Net final : NetBase {
         bn_train_bwd(dpre.data(), s.conv.data(), c.p[1].data(), s.mean.data(), s.var.data(),
                      dconv.data(), c.g[1].data(), c.g[2].data(), N, so.c, so.h * so.w, eps);
         rnd(dconv);
-        conv_wgrad(dconv.data(), v[o.in[0]].data(), c.g[0].data(), N, si.c, si.h, si.w, so.c, o.k,
-                   o.stride, o.pad, o.groups);
+        if (!arch)
+          conv_wgrad(dconv.data(), v[o.in[0]].data(), c.g[0].data(), N, si.c, si.h, si.w, so.c, o.k,
+                     o.stride, o.pad, o.groups);
         if (o.in[0] != 0) {
           std::vector<R> dx((size_t)N * si.numel());
           const std::vector<R> w = stored(c.p[0]);
@@ -713,10 +793,21 @@ struct Net final : NetBase {
         accumulate(o.in[0], dpre);
         accumulate(o.in[1], dpre);
       } else {
+        const std::vector<R> p = probs(b, j);
+        if (arch) {
+          // z = sum_k p_k y_k, p = softmax(alpha):  dp_k/dalpha_j = p_k ([k == j] - p_j)
+          std::vector<R> g(o.nin, R(0));
+          R mean = 0;
+          for (int k = 0; k < o.nin; ++k) {
+            const std::vector<R>& y = v[o.in[k]];
+            for (size_t i = 0; i < dy.size(); ++i) g[k] += dy[i] * y[i];
+            mean += p[k] * g[k];
+          }
+          for (int k = 0; k < o.nin; ++k) alpha_g[b][j][k] = p[k] * (g[k] - mean);
+        }
         for (int k = 0; k < o.nin; ++k) {
-          const R p = (R)d.pool[o.pofs + k];
           std::vector<R> g(dy.size());
-          for (size_t i = 0; i < dy.size(); ++i) g[i] = p * dy[i];
+          for (size_t i = 0; i < dy.size(); ++i) g[i] = p[k] * dy[i];
           accumulate(o.in[k], g);
         }
       }
@@ -724,16 +815,25 @@ struct Net final : NetBase {
     }
   }
 
-  // mode 0: loss only (no state change); 1: loss + gradients; 2: full step
+  // mode 0: loss only (no state change); 1: loss + gradients; 2: full step;
+  // 3: architecture round, loss + gradients of alpha; 4: architecture round, full step
   R student_step_r(int i, const std::vector<R>& a_prev, const std::vector<R>& a_i, R lr, int mode) {
     const int b = i - 1;
+    const bool arch = mode >= 3;
+    if (arch) define_alpha(b);
     student_forward(b, a_prev);
     const std::vector<R>& s = val[b].back();
     std::vector<R> ds(mode ? s.size() : 0);
     const R loss = mse(s.data(), a_i.data(), mode ? ds.data() : nullptr, s.size());
     if (mode == 0) return loss;
     rnd(ds);
-    student_backward(b, ds);
+    student_backward(b, ds, arch);
+    if (mode == 4) {
+      update_running_stats(b);
+      for (size_t j = 0; j < alpha[b].size(); ++j)
+        if (!alpha[b][j].empty())
+          sgd(alpha[b][j].data(), alpha_v[b][j].data(), alpha_g[b][j].data(), alpha[b][j].size(), lr, mu);
+    }
     if (mode == 2) {
       update_running_stats(b);
       for (Cba<R>& c : par[1][b])
@@ -753,6 +853,11 @@ struct Net final : NetBase {
   void relay_step(const double* x, double lr, double* losses) override {
     teacher_relay(x);
     for (int i = 1; i <= d.B; ++i) losses[i - 1] = (double)student_step_r(i, A[i - 1], A[i], (R)lr, 2);
+  }
+  // the architecture round of every block on relayed activations
+  void relay_arch_step(const double* x, double lr, double* losses) override {
+    teacher_relay(x);
+    for (int i = 1; i <= d.B; ++i) losses[i - 1] = (double)student_step_r(i, A[i - 1], A[i], (R)lr, 4);
   }
   // block by block, teacher re-run from the input each time (Sec. II-B baseline)
   void redundant_step(const double* x, double lr, double* losses) override {
@@ -808,6 +913,13 @@ void orc_relay_step(void* h, const double* x, double lr, double* losses) {
 }
 void orc_redundant_step(void* h, const double* x, double lr, double* losses) {
   static_cast<NetBase*>(h)->redundant_step(x, lr, losses);
+}
+void orc_relay_arch_step(void* h, const double* x, double lr, double* losses) {
+  static_cast<NetBase*>(h)->relay_arch_step(x, lr, losses);
+}
+int orc_set_alpha(void* h, int b, int j, const double* a, int n) { return static_cast<NetBase*>(h)->set_alpha(b, j, a, n); }
+int orc_get_alpha(void* h, int kind, int b, int j, double* out, int n) {
+  return static_cast<NetBase*>(h)->get_alpha(kind, b, j, out, n);
 }
 double orc_kink_margin(void* h, int b) { return static_cast<NetBase*>(h)->kink_margin(b); }
 long orc_value_numel(void* h, int b, int v) { return static_cast<NetBase*>(h)->value_numel(b, v); }

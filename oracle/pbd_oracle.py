@@ -17,7 +17,8 @@ _SRC = os.path.join(_HERE, "pbd_oracle.cpp")
 _LIB = os.path.join(_HERE, "libpbd_oracle.so")
 
 KIND_PARAM, KIND_GRAD, KIND_MOMENTUM = 0, 1, 2
-MODE_LOSS, MODE_GRADS, MODE_STEP = 0, 1, 2
+MODE_LOSS, MODE_GRADS, MODE_STEP, MODE_ARCH_GRADS, MODE_ARCH_STEP = 0, 1, 2, 3, 4
+ALPHA_VALUE, ALPHA_GRAD, ALPHA_MOMENTUM, ALPHA_PROB = 0, 1, 2, 3
 
 _dp = C.POINTER(C.c_double)
 _ip = C.POINTER(C.c_int32)
@@ -54,6 +55,11 @@ def lib():
         L.orc_student_step.argtypes = [C.c_void_p, C.c_int, _dp, _dp, C.c_double, C.c_int]
         L.orc_relay_step.argtypes = [C.c_void_p, _dp, C.c_double, _dp]
         L.orc_redundant_step.argtypes = [C.c_void_p, _dp, C.c_double, _dp]
+        L.orc_relay_arch_step.argtypes = [C.c_void_p, _dp, C.c_double, _dp]
+        L.orc_set_alpha.restype = C.c_int
+        L.orc_set_alpha.argtypes = [C.c_void_p, C.c_int, C.c_int, _dp, C.c_int]
+        L.orc_get_alpha.restype = C.c_int
+        L.orc_get_alpha.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, _dp, C.c_int]
         L.orc_value_numel.restype = C.c_long
         L.orc_value_numel.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.orc_get_value.argtypes = [C.c_void_p, C.c_int, C.c_int, _dp]
@@ -271,6 +277,24 @@ class Oracle:
         losses = np.empty(self.B)
         lib().orc_redundant_step(self.h, _d(x), lr, _d(losses))
         return losses
+
+    def relay_arch_step(self, x, lr):
+        """Teacher once, then the architecture round (alpha trained, weights frozen) of every block."""
+        x = _f64(x)
+        losses = np.empty(self.B)
+        lib().orc_relay_arch_step(self.h, _d(x), lr, _d(losses))
+        return losses
+
+    def set_alpha(self, b, j, alpha):
+        a = _f64(alpha).ravel()
+        if lib().orc_set_alpha(self.h, b, j, _d(a), a.size) != 0:
+            raise ValueError(f"op {j} of block {b} is not a mix of {a.size} inputs")
+
+    def get_alpha(self, b, j, n, kind=ALPHA_VALUE):
+        out = np.empty(n)
+        if lib().orc_get_alpha(self.h, kind, b, j, _d(out), n) != 0:
+            raise ValueError(f"no architecture tensor {kind} for op {j} of block {b} with {n} inputs")
+        return out
 
     def kink_margin(self, b):
         """Smallest distance of block b's last forward from a ReLU / ReLU6 / max-pool kink."""

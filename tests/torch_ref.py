@@ -6,8 +6,9 @@ import torch.nn.functional as F
 from paper_2301_12443_amd import workloads as W
 
 
-def run_block(block, x, params, train, eps=1e-5):
-    """params[(j, slot)] -> tensor.  Returns (output, {j: (batch mean, biased var)})."""
+def run_block(block, x, params, train, eps=1e-5, alphas=None):
+    """params[(j, slot)] -> tensor; alphas[j] -> architecture parameters of mix op j (its weights are
+    then softmax(alphas[j]) instead of the descriptor's).  Returns (output, {j: (batch mean, biased var)})."""
     vals = [x]
     stats = {}
     for j, op in enumerate(block.ops):
@@ -32,7 +33,8 @@ def run_block(block, x, params, train, eps=1e-5):
             y = a + vals[op.inputs[1]]
             vals.append(F.relu(y) if op.act == W.ACT_RELU else y)
         elif op.type == W.OP_MIX:
-            vals.append(sum(p * vals[i] for p, i in zip(op.p, op.inputs)))
+            p = torch.softmax(alphas[j], dim=0) if alphas is not None and j in alphas else op.p
+            vals.append(sum(p[k] * vals[i] for k, i in enumerate(op.inputs)))
     return vals[-1], stats
 
 
