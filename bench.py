@@ -17,6 +17,7 @@ PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 # fp32 vector FMA without packed instructions (this build must compile them out): 256 CUs x 4 SIMDs
 # x 16 lanes x 2 flop x 2.4 GHz; the published 157.3 TFLOP/s counts the packed form
 PEAK_FP32_VALU_TFLOPS = 78.6
+LR_ALPHA = 0.005          # learning rate of the architecture parameters in the arch / two_round modes
 
 # HBM bytes per launch (mean over a kernel class's launches in one step) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by what the same counter reads for a
@@ -105,10 +106,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="vgg16_dsconv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--mode", choices=["relay", "redundant"], default="relay",
+    ap.add_argument("--mode", choices=["relay", "redundant", "arch", "two_round"], default="relay",
                     help="relay: pbd_distill_step (the method; the metric).  redundant: the baseline's teacher "
                          "schedule on the same kernels (before block i, T_1..T_i are run again from the input, "
-                         "Sec. III), for the relay-vs-redundant ratio; never the headline value")
+                         "Sec. III), for the relay-vs-redundant ratio; never the headline value.  arch: "
+                         "pbd_distill_arch_step, the architecture round of a supernet student (Sec. VI-A).  two_round: "
+                         "the NAS step, architecture round then weight round on the same batch")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch the step's kernels one by one (for rocprofv3 --pmc runs)")
     ap.add_argument("--classes", action="store_true", help="also print the per-kernel-class table to stderr")
@@ -135,6 +138,11 @@ def main():
     def step():
         if args.mode == "relay":
             d.distill_step(x, wl.lr)
+        elif args.mode == "arch":
+            d.distill_arch_step(x, LR_ALPHA)
+        elif args.mode == "two_round":
+            d.distill_arch_step(x, LR_ALPHA)
+            d.distill_step(x, wl.lr)
         else:
             for i in range(1, wl.B + 1):
                 d.teacher_prefix(x, i)
@@ -155,7 +163,10 @@ def main():
     psteps = 5
     d.set_profile(True); d.reset_profile()
     for _ in range(psteps):
-        d.distill_step(x, wl.lr)
+        if args.mode in ("arch", "two_round"):
+            d.distill_arch_step(x, LR_ALPHA)
+        if args.mode != "arch":
+            d.distill_step(x, wl.lr)
     prof = d.get_profile()
     d.set_profile(False)
     roof, classes = roofline_from_profile(prof, psteps)
@@ -172,15 +183,19 @@ def main():
         torch.cuda.synchronize()
 
     rec = {
-        "metric": "distillation samples/sec/GPU (full relay step)" if args.mode == "relay"
-                  else "distillation samples/sec/GPU (teacher re-run per block, no relay; direct launches)",
+        "metric": {"relay": "distillation samples/sec/GPU (full relay step)",
+                   "redundant": "distillation samples/sec/GPU (teacher re-run per block, no relay; direct launches)",
+                   "arch": "distillation samples/sec/GPU (relay + architecture round only)",
+                   "two_round": "distillation samples/sec/GPU (NAS step: relay + architecture round, relay + weight round)"}[args.mode],
         "value": round(wl.batch * args.steps / dt, 1), "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(dt / args.steps * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.precision == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {wl.batch}, input {wl.in_shape}, {wl.B} blocks, "
-                               "teacher relay + student fwd/MSE/bwd/SGD-momentum", "lr": wl.lr},
+                               + {"arch": "teacher relay + student fwd/MSE/bwd to the mix ops/alpha update",
+                                  "two_round": "architecture round (alpha) then weight round, one relay each"}.get(
+                                      args.mode, "teacher relay + student fwd/MSE/bwd/SGD-momentum"), "lr": wl.lr},
         "roofline": roof,
     }
     if args.peaks:

@@ -46,7 +46,7 @@ typedef enum {
 enum { PBD_F32 = 0, PBD_BF16 = 1 };                       /* arithmetic / storage type */
 enum { PBD_TEACHER = 0, PBD_STUDENT = 1 };                /* net */
 enum { PBD_WEIGHT = 0, PBD_GAMMA = 1, PBD_BETA = 2, PBD_RMEAN = 3, PBD_RVAR = 4 }; /* slot */
-enum { PBD_PARAM = 0, PBD_GRAD = 1, PBD_MOMENTUM = 2 };   /* kind */
+enum { PBD_PARAM = 0, PBD_GRAD = 1, PBD_MOMENTUM = 2, PBD_PROB = 3 };   /* kind (PBD_PROB: pbd_read_alpha only) */
 
 typedef struct pbd_ctx pbd_ctx;
 
@@ -156,7 +156,36 @@ int pbd_student_step(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pb
  * workspace addresses; x_dev, lr and losses_dev stay outside the graph). */
 int pbd_distill_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
 
-/* 1 if pbd_distill_step currently replays a captured HIP graph, 0 if it launches directly. */
+/* Architecture round of a supernet student (Sec. VI-A, neural architecture search: every step has a
+ * second forward/backward round that trains the architecture parameters, and that round is an
+ * ordinary training step of the block).  A type-4 op of the student computes z = sum_k p_k y_k over its
+ * candidates with p = softmax(alpha).  The round runs the same forward (batch statistics, running
+ * statistics updated) and the same loss as pbd_student_step, back-propagates to every mix op, forms
+ *   g_k = <dL/dz, y_k>,   dL/dalpha_j = p_j (g_j - sum_k p_k g_k)
+ * and applies v <- mu v + dL/dalpha, alpha <- alpha - lr_alpha v, p <- softmax(alpha).  Weights, gamma
+ * and beta are frozen: their values and momenta are untouched (their gradient tensors are unspecified
+ * afterwards), and layers with no mix op above them are not back-propagated at all.  Later weight
+ * rounds mix with the new p.  Until alpha is loaded or first trained a mix uses the descriptor's
+ * weights unchanged; the first round then starts from alpha_k = ln p_k, which requires those weights
+ * to be positive and to sum to 1 (PBD_ESTATE otherwise: load alpha first).  Arguments as for
+ * pbd_student_step.  A block without mix ops only gets its forward pass and loss. */
+int pbd_arch_step(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i,
+                  float lr_alpha, float* loss_dev);
+
+/* Relay, then the architecture round of every block; arguments and graph capture as for
+ * pbd_distill_step (the two rounds are captured separately). */
+int pbd_distill_arch_step(pbd_ctx* ctx, const float* x_dev, float lr_alpha, float* losses_dev);
+
+/* Architecture parameters of student block b (from 0), op index op (a type-4 op with n inputs).
+ * pbd_load_alpha copies n float32 from host and sets p = softmax(alpha); momentum is kept.
+ * pbd_read_alpha copies alpha (PBD_PARAM), its last gradient (PBD_GRAD), its momentum (PBD_MOMENTUM)
+ * or the weights p in use (PBD_PROB) to host; all but PBD_PROB need alpha to be defined (PBD_ESTATE).
+ * Both wait for the stream. */
+int pbd_load_alpha(pbd_ctx* ctx, int32_t b, int32_t op, const float* host, size_t n);
+int pbd_read_alpha(pbd_ctx* ctx, int32_t kind, int32_t b, int32_t op, float* host, size_t n);
+
+/* 1 if pbd_distill_step or pbd_distill_arch_step currently replays a captured HIP graph, 0 if they
+ * launch directly. */
 int pbd_uses_graph(const pbd_ctx* ctx);
 
 /* Wait for the bound stream; reports asynchronous failures. */

@@ -738,21 +738,31 @@ struct Join {
   const void* src[8];
   void* dst[8];
   float p[8];
+  const float* pdev;     // when set, the weights are read from device memory instead (trainable mix)
   int accumulate[8];
   int n;
 };
 
+__device__ __forceinline__ void join_weights(const Join& j, float (&p)[8]) {
+#pragma unroll
+  for (int k = 0; k < 8; ++k) p[k] = k < j.n ? (j.pdev ? j.pdev[k] : j.p[k]) : 0.f;
+}
+
 template <class T>
 __global__ void join_fwd_kernel(Join j, T* __restrict__ z, long nvec, int act) {
+  float p[8];
+  join_weights(j, p);
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int k = 0; k < j.n; ++k) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (k >= j.n) break;
       float v[8];
       IO<T>::ld(static_cast<const T*>(j.src[k]) + i * 8, v);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = fmaf(j.p[k], v[e], acc[e]);
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(p[k], v[e], acc[e]);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = apply_act(acc[e], act);
@@ -763,6 +773,8 @@ __global__ void join_fwd_kernel(Join j, T* __restrict__ z, long nvec, int act) {
 // z is the post-activation output: for ReLU the gradient passes where z > 0
 template <class T>
 __global__ void join_bwd_kernel(Join j, const T* __restrict__ dz, const T* __restrict__ z, long nvec, int act) {
+  float p[8];
+  join_weights(j, p);
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
     float d[8];
     IO<T>::ld(dz + i * 8, d);
@@ -772,20 +784,114 @@ __global__ void join_bwd_kernel(Join j, const T* __restrict__ dz, const T* __res
 #pragma unroll
       for (int e = 0; e < 8; ++e) d[e] = act_pass(v[e], act) ? d[e] : 0.f;
     }
-    for (int k = 0; k < j.n; ++k) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (k >= j.n) break;
       T* dst = static_cast<T*>(j.dst[k]);
       if (!dst) continue;
       float o[8];
       if (j.accumulate[k]) {
         IO<T>::ld(dst + i * 8, o);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = fmaf(j.p[k], d[e], o[e]);
+        for (int e = 0; e < 8; ++e) o[e] = fmaf(p[k], d[e], o[e]);
       } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = j.p[k] * d[e];
+        for (int e = 0; e < 8; ++e) o[e] = p[k] * d[e];
       }
       IO<T>::st(dst + i * 8, o);
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// architecture round of a supernet (Sec. VI-A, neural architecture search): a mix op computes
+// z = act(sum_k p_k y_k) with p = softmax(alpha).  With d = dL/dz masked by the activation,
+//   g_k = <d, y_k>,   dL/dalpha_j = p_j (g_j - sum_k p_k g_k).
+// mix_dot_kernel leaves one partial g per workgroup; mix_alpha_update_kernel sums them in a fixed
+// order, forms the gradient, applies  v <- mu v + g ; alpha <- alpha - lr v  and writes the new p.
+// One mix op owns 32 floats of state: alpha[8], momentum[8], gradient[8], p[8].
+// ---------------------------------------------------------------------------
+constexpr int kMixState = 32, kMixAlpha = 0, kMixMom = 8, kMixGrad = 16, kMixP = 24;
+constexpr int kMixDotBlocks = 512;
+
+template <class T>
+__global__ __launch_bounds__(256) void mix_dot_kernel(Join j, const T* __restrict__ dz, const T* __restrict__ z,
+                                                      float* __restrict__ part, long nvec, int act) {
+  __shared__ float red[4][8];
+  float acc[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) acc[k] = 0.f;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    float d[8];
+    IO<T>::ld(dz + i * 8, d);
+    if (act != ACT_NONE) {
+      float v[8];
+      IO<T>::ld(z + i * 8, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = act_pass(v[e], act) ? d[e] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (k >= j.n) break;
+      float v[8];
+      IO<T>::ld(static_cast<const T*>(j.src[k]) + i * 8, v);
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s = fmaf(d[e], v[e], s);
+      acc[k] += s;
+    }
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    float v = acc[k];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0) red[wave][k] = v;
+  }
+  __syncthreads();
+  if (threadIdx.x < 8) part[blockIdx.x * 8 + threadIdx.x] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+// one workgroup of 256 threads; state = the mix op's 32 floats; update == 0 leaves alpha, momentum and p
+__global__ __launch_bounds__(256) void mix_alpha_update_kernel(const float* __restrict__ part, int nblocks,
+                                                               float* __restrict__ state, int n,
+                                                               const float* __restrict__ lr_ptr, float mu, int update) {
+  __shared__ double red[32][8];
+  __shared__ double g[8];
+  __shared__ float alpha[8];
+  const int k = threadIdx.x & 7, row = threadIdx.x >> 3;
+  double s = 0.0;
+  for (int b = row; b < nblocks; b += 32) s += (double)part[b * 8 + k];
+  red[row][k] = s;
+  __syncthreads();
+  for (int h = 16; h > 0; h >>= 1) {
+    if (row < h) red[row][k] += red[row + h][k];
+    __syncthreads();
+  }
+  if (threadIdx.x < 8) g[threadIdx.x] = red[0][threadIdx.x];
+  __syncthreads();
+  if ((int)threadIdx.x < n) {
+    double mean = 0.0;
+    for (int q = 0; q < n; ++q) mean += (double)state[kMixP + q] * g[q];
+    const float grad = (float)((double)state[kMixP + threadIdx.x] * (g[threadIdx.x] - mean));
+    state[kMixGrad + threadIdx.x] = grad;
+    float a = state[kMixAlpha + threadIdx.x];
+    if (update) {
+      const float v = fmaf(mu, state[kMixMom + threadIdx.x], grad);
+      a -= *lr_ptr * v;
+      state[kMixMom + threadIdx.x] = v;
+      state[kMixAlpha + threadIdx.x] = a;
+    }
+    alpha[threadIdx.x] = a;
+  }
+  __syncthreads();   // every read of the old p is done; alpha[] is complete
+  if (update && (int)threadIdx.x < n) {
+    float top = alpha[0];
+    for (int q = 1; q < n; ++q) top = fmaxf(top, alpha[q]);
+    float sum = 0.f;
+    for (int q = 0; q < n; ++q) sum += expf(alpha[q] - top);
+    state[kMixP + threadIdx.x] = expf(alpha[threadIdx.x] - top) / sum;
   }
 }
 

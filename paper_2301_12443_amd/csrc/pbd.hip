@@ -53,6 +53,7 @@ struct OpPlan {
   long e_wt = -1;           // element offset in the block's transposed-weight arena
   // scratch byte offsets
   size_t y = 0, idx = 0;
+  int mix_slot = -1;        // student mix op: which 32-float state record of the block it owns
 };
 
 struct BlockPlan {
@@ -66,6 +67,9 @@ struct BlockPlan {
   std::vector<TransposeEntry> ttable;
   size_t scratch_bytes = 0, red_bytes = 0;
   size_t scr_off = 0, red_off = 0;   // absolute workspace offsets of this block's scratch regions
+  size_t mix = 0;                // byte offset (param region) of the mix ops' state records
+  int nmix = 0;
+  std::vector<char> alpha_defined;  // per mix op: alpha was loaded or trained (else p is the descriptor's)
   bool stepped = false;          // student: saved values in scratch belong to a finished step
   bool dirty = true;             // compute copies stale w.r.t. master weights
 };
@@ -93,8 +97,8 @@ struct pbd_ctx {
   std::string err;
   // profiling
   size_t lr_off = 0, loss_off = 0;      // device scalars: learning rate, per-block losses
-  hipGraphExec_t gexec = nullptr;       // the captured step (teacher blocks + student blocks)
-  bool graph_tried = false;
+  hipGraphExec_t gexec[2] = {nullptr, nullptr};   // the captured step: [0] weight round, [1] architecture round
+  bool graph_tried[2] = {false, false};
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
   hipEvent_t pend_start = nullptr, pend_stop = nullptr;   // events waiting for the next launch
@@ -296,7 +300,9 @@ int plan(pbd_ctx* c) {
   // student parameters: one flat arena per block
   for (BlockPlan& bp : c->net[1]) {
     size_t e = 0, et = 0;
+    bp.nmix = 0;
     for (OpPlan& op : bp.ops) {
+      if (op.d.type == OP_MIX) op.mix_slot = bp.nmix++;
       if (op.d.type != OP_CBA) continue;
       op.e_w = e; e += op.wn;
       op.e_gamma = e; e += op.cout_p;
@@ -316,6 +322,8 @@ int plan(pbd_ctx* c) {
     bp.wc = bf ? take(e * 2) : bp.master;
     bp.wt = take(std::max<size_t>(et, 1) * es);
     bp.table = take(std::max<size_t>(bp.ttable.size(), 1) * sizeof(TransposeEntry));
+    bp.mix = take((size_t)std::max(bp.nmix, 1) * kMixState * sizeof(float));
+    bp.alpha_defined.assign(bp.nmix, 0);
   }
   c->lr_off = take(256);
   c->loss_off = take((size_t)c->B * 4);
@@ -368,6 +376,8 @@ int plan(pbd_ctx* c) {
         }
       } else if (op.d.type == OP_POOL) {
         op.idx = s; s += align_up((size_t)M * op.cout_p);
+      } else if (op.d.type == OP_MIX) {
+        need_red((size_t)kMixDotBlocks * 8 * sizeof(float));
       }
     }
     bp.scratch_bytes = align_up(s);
@@ -772,7 +782,7 @@ template <class T> struct Exec {
   // the pointer-independent body of a step: T_1..T_B once each, then every student block
   // With `fork` (graph capture, disjoint scratch) student block b runs on its own stream as soon as
   // T_b has produced its target, next to T_{b+1}: the one-device form of the overlap of Sec. IV-A.
-  void step_body(bool fork) {
+  void step_body(bool fork, bool arch = false) {
     hipStream_t main = st;
     for (int b = 0; b < c->B; ++b) {
       teacher_block(b);
@@ -780,14 +790,14 @@ template <class T> struct Exec {
         (void)hipEventRecord(c->ev_fork[b], main);
         (void)hipStreamWaitEvent(c->side[b], c->ev_fork[b], 0);
         st = c->side[b];
-        student_block(b, wsf(c->loss_off) + b);
+        student_block(b, wsf(c->loss_off) + b, arch);
         (void)hipEventRecord(c->ev_join[b], st);
         st = main;
       }
     }
     for (int b = 0; b < c->B; ++b) {
       if (fork) (void)hipStreamWaitEvent(main, c->ev_join[b], 0);
-      else student_block(b, wsf(c->loss_off) + b);
+      else student_block(b, wsf(c->loss_off) + b, arch);
     }
     c->relayed_upto = c->B;
   }
@@ -811,7 +821,9 @@ template <class T> struct Exec {
                                                       reinterpret_cast<const TransposeEntry*>(c->ws + bp.table));
   }
 
-  void student_block(int b, float* loss_dev) {
+  // arch: the architecture round (Sec. VI-A, neural architecture search) - same forward and loss;
+  // the backward reaches every mix op, forms dL/dalpha there and trains alpha; weights stay frozen
+  void student_block(int b, float* loss_dev, bool arch = false) {
     BlockPlan& bp = c->net[1][b];
     net = PBD_STUDENT; blk = b;
     if (bp.dirty) refresh_compute_copies(bp);
@@ -824,6 +836,7 @@ template <class T> struct Exec {
     float* grad = wsf(bp.grad);
     const float* master = wsf(bp.master);
     const int nval = (int)bp.shapes.size();
+    auto mix_state = [&](const OpPlan& op) -> float* { return wsf(bp.mix) + (size_t)op.mix_slot * kMixState; };
 
     // ---- forward ----------------------------------------------------------
     for (size_t j = 0; j < bp.ops.size(); ++j) {
@@ -865,8 +878,9 @@ template <class T> struct Exec {
         jn.n = op.d.nin;
         for (int k = 0; k < op.d.nin; ++k) {
           jn.src[k] = value(op.d.in[k]);
-          jn.p[k] = op.d.type == OP_MIX ? (float)c->pool[op.d.pofs + k] : 1.f;
+          jn.p[k] = 1.f;
         }
+        if (op.d.type == OP_MIX) jn.pdev = mix_state(op) + kMixP;
         join_fwd(op, jn, z);
       }
     }
@@ -886,6 +900,17 @@ template <class T> struct Exec {
     // ---- backward ---------------------------------------------------------
     std::vector<char> have(nval, 0);
     have[nval - 1] = 1;
+    // wanted[v]: the gradient of value v is needed.  Weight round: every value but the block's input.
+    // Architecture round: only values that have a mix op at or above them.
+    std::vector<char> wanted(nval, 1);
+    wanted[0] = 0;
+    if (arch)
+      for (int j = 0; j < (int)bp.ops.size(); ++j) {
+        const OpD& o = bp.ops[j].d;
+        char w = o.type == OP_MIX;
+        for (int k = 0; k < (o.type == OP_ADD || o.type == OP_MIX ? o.nin : 1); ++k) w |= wanted[o.in[k]];
+        wanted[j + 1] = w;
+      }
     for (int j = (int)bp.ops.size() - 1; j >= 0; --j) {
       const OpPlan& op = bp.ops[j];
       opi = j;
@@ -893,6 +918,7 @@ template <class T> struct Exec {
       T* dz = dvalue(j + 1);
       const int iv = op.d.in[0];
       if (op.d.type == OP_CBA) {
+        if (arch && !wanted[iv]) continue;   // frozen weights and nothing trainable above: nothing to do
         const T* y = ws(scr + op.y);
         const long M = (long)N * op.out.h * op.out.w;
         if (short_column(M)) {
@@ -920,15 +946,17 @@ template <class T> struct Exec {
           }
         }
         const T* x = value(iv);
-        if (op.dw) dw_wgrad(op, dz, x, grad + op.e_w);
-        else conv_wgrad(op, dz, x, grad + op.e_w);
-        if (iv != 0) {  // A_{i-1} is a constant: no backward-data for the block's first layer
+        if (!arch) {
+          if (op.dw) dw_wgrad(op, dz, x, grad + op.e_w);
+          else conv_wgrad(op, dz, x, grad + op.e_w);
+        }
+        if (wanted[iv]) {  // A_{i-1} is a constant: no backward-data for the block's first layer
           if (op.dw) dw_dgrad(op, dz, wc + op.e_w, dvalue(iv), have[iv]);
           else conv_dgrad(op, dz, wc + op.e_w, op.e_wt >= 0 ? ws(bp.wt) + op.e_wt : nullptr, dvalue(iv), have[iv]);
           have[iv] = 1;
         }
       } else if (op.d.type == OP_POOL) {
-        if (iv != 0) {
+        if (wanted[iv]) {
           const int ncv = op.cout_p / 8;
           const long nvec = (long)N * op.in.h * op.in.w * ncv;
           ProfScope ps(c, "maxpool_bwd", bytes_of(op.in) + 1.5 * bytes_of(op.out), 0, net, blk, opi);
@@ -943,21 +971,32 @@ template <class T> struct Exec {
         int live = 0;
         for (int k = 0; k < op.d.nin; ++k) {
           const int v = op.d.in[k];
-          jn.p[k] = op.d.type == OP_MIX ? (float)c->pool[op.d.pofs + k] : 1.f;
-          jn.dst[k] = v == 0 ? nullptr : dvalue(v);
-          jn.accumulate[k] = v != 0 && have[v];
-          if (v != 0) { have[v] = 1; ++live; }
+          jn.p[k] = 1.f;
+          jn.src[k] = value(v);
+          jn.dst[k] = wanted[v] ? dvalue(v) : nullptr;
+          jn.accumulate[k] = wanted[v] && have[v];
+          if (wanted[v]) { have[v] = 1; ++live; }
+        }
+        const long nvec = (long)N * op.out.h * op.out.w * op.cout_p / 8;
+        if (op.d.type == OP_MIX) jn.pdev = mix_state(op) + kMixP;
+        const bool train_alpha = arch && op.d.type == OP_MIX;
+        const int nb = (int)std::min<long>(kMixDotBlocks, (nvec + 255) / 256);
+        if (train_alpha) {
+          ProfScope ps(c, "mix_dot", bytes_of(op.out) * (op.d.nin + 1 + (op.d.act ? 1 : 0)), 0, net, blk, opi);
+          launch(c, mix_dot_kernel<T>, nb, 256, 0, st, jn, dz, value(j + 1), red(), nvec, op.d.act);
         }
         if (live) {
-          const long nvec = (long)N * op.out.h * op.out.w * op.cout_p / 8;
           ProfScope ps(c, "join_bwd", bytes_of(op.out) * (live + 1 + (op.d.act ? 1 : 0)), 0, net, blk, opi);
           launch(c, join_bwd_kernel<T>, grid_for(nvec), 256, 0, st, jn, dz, value(j + 1), nvec, op.d.act);
         }
+        // after the last reader of this round's p: gradient, momentum step and the new softmax
+        if (train_alpha)
+          launch(c, mix_alpha_update_kernel, 1, 256, 0, st, red(), nb, mix_state(op), op.d.nin, wsf(c->lr_off), c->o.momentum, 1);
       }
     }
 
     // ---- decoupled update of this block only -----------------------------
-    {
+    if (!arch) {
       opi = -1;
       const long n4 = (long)bp.arena_elems / 4;
       ProfScope ps(c, "sgd_momentum", (double)bp.arena_elems * (20 + (sizeof(T) == 2 ? 2 : 0)), 0, net, blk, opi);
@@ -965,8 +1004,8 @@ template <class T> struct Exec {
         launch(c, sgd_momentum_kernel<bf16_t>, grid_for(n4), 256, 0, st, wsf(bp.master), wsf(bp.mom), grad, (bf16_t*)wc, n4, wsf(c->lr_off), c->o.momentum);
       else
         launch(c, sgd_momentum_kernel<bf16_t>, grid_for(n4), 256, 0, st, wsf(bp.master), wsf(bp.mom), grad, nullptr, n4, wsf(c->lr_off), c->o.momentum);
+      transpose_weights(bp);
     }
-    transpose_weights(bp);
     red_off = c->r_tred;
     if (!c->concurrent)
       for (BlockPlan& other : c->net[1]) other.stepped = false;   // shared scratch was overwritten
@@ -1112,12 +1151,98 @@ int check_view(pbd_ctx* c, const pbd_tensor* t, int i, const char* what) {
   return PBD_OK;
 }
 
+const OpPlan* find_mix(pbd_ctx* c, int b, int op) {
+  if (b < 0 || b >= c->B) return nullptr;
+  const BlockPlan& bp = c->net[1][b];
+  if (op < 0 || op >= (int)bp.ops.size() || bp.ops[op].d.type != OP_MIX) return nullptr;
+  return &bp.ops[op];
+}
+char* mix_record(pbd_ctx* c, int b, const OpPlan& op) {
+  return c->ws + c->net[1][b].mix + (size_t)op.mix_slot * kMixState * sizeof(float);
+}
+
+// Before the first architecture round of block b: alpha_k = ln p_k of the descriptor's weights, which
+// must then be probabilities (the round differentiates p = softmax(alpha)).
+int define_alpha(pbd_ctx* c, int b) {
+  BlockPlan& bp = c->net[1][b];
+  for (size_t j = 0; j < bp.ops.size(); ++j) {
+    const OpPlan& op = bp.ops[j];
+    if (op.d.type != OP_MIX || bp.alpha_defined[op.mix_slot]) continue;
+    double sum = 0.0;
+    float a[8] = {};
+    for (int k = 0; k < op.d.nin; ++k) {
+      const double pk = c->pool[op.d.pofs + k];
+      if (!(pk > 0.0)) return fail(c, PBD_ESTATE, "block %d op %zu: mix weight %d is not positive; load alpha first", b + 1, j, k);
+      sum += pk;
+      a[k] = (float)std::log(pk);
+    }
+    if (std::fabs(sum - 1.0) > 1e-6)
+      return fail(c, PBD_ESTATE, "block %d op %zu: mix weights sum to %g, not 1; load alpha first", b + 1, j, sum);
+    HIP_TRY(c, hipMemcpyAsync(mix_record(c, b, op) + kMixAlpha * sizeof(float), a, sizeof a, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    bp.alpha_defined[op.mix_slot] = 1;
+  }
+  return PBD_OK;
+}
+
 void fill_view(pbd_ctx* c, int i, pbd_tensor* t) {
   const Shape s = c->act[i];
   t->ptr = c->ws + c->r_relay + c->act_off[i];
   t->n = c->o.batch; t->c = s.c; t->h = s.h; t->w = s.w;
   t->c_phys = round8(s.c);
   t->dtype = c->o.precision;
+}
+
+// The whole step in one of its two rounds (r = 0: weights, 1: architecture parameters).
+int whole_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev, int r) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
+  if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
+  if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
+  if (r == 1)
+    for (int b = 0; b < c->B; ++b)
+      if ((rc = define_alpha(c, b))) return rc;
+  // The body of the step touches only workspace addresses, so it is captured once into a HIP
+  // graph and replayed: ~300 small launches per step would otherwise be bound by launch cost.
+  // Capture needs a real stream and no profiling events; otherwise the kernels are launched directly.
+  const bool want_graph = c->stream != nullptr && !c->prof_on && !c->o.no_graph;
+  rc = dispatch(c, [&](auto& e) { e.set_lr(lr); e.prepare(x_dev); });
+  if (rc) return rc;
+  if (want_graph && !c->gexec[r] && !c->graph_tried[r]) {
+    c->graph_tried[r] = true;
+    hipGraph_t graph = nullptr;
+    bool fork = c->concurrent;
+    if (fork && c->side.empty()) {
+      for (int b = 0; b < c->B && fork; ++b) {
+        hipStream_t s2; hipEvent_t e1, e2;
+        fork = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&e1, hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&e2, hipEventDisableTiming) == hipSuccess;
+        if (fork) { c->side.push_back(s2); c->ev_fork.push_back(e1); c->ev_join.push_back(e2); }
+      }
+    }
+    fork = fork && (int)c->side.size() == c->B;
+    if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
+      dispatch(c, [&](auto& e) { e.step_body(fork, r == 1); });
+      hipError_t ee = hipStreamEndCapture(c->stream, &graph);
+      if (ee == hipSuccess && graph && hipGraphInstantiate(&c->gexec[r], graph, nullptr, nullptr, 0) != hipSuccess)
+        c->gexec[r] = nullptr;
+      if (graph) (void)hipGraphDestroy(graph);
+    }
+    (void)hipGetLastError();
+  }
+  if (want_graph && c->gexec[r]) {
+    HIP_TRY(c, hipGraphLaunch(c->gexec[r], c->stream));
+    c->relayed_upto = c->B;
+    for (BlockPlan& bp : c->net[1]) bp.stepped = c->concurrent;
+    c->net[1].back().stepped = true;
+  } else {
+    rc = dispatch(c, [&](auto& e) { e.step_body(false, r == 1); });
+    if (rc) return rc;
+  }
+  HIP_TRY(c, hipMemcpyAsync(losses_dev, c->ws + c->loss_off, (size_t)c->B * 4, hipMemcpyDeviceToDevice, c->stream));
+  return after_launches(c);
 }
 
 }  // namespace
@@ -1189,7 +1314,7 @@ int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t
 
 void pbd_destroy(pbd_ctx* c) {
   if (!c) return;
-  if (c->gexec) (void)hipGraphExecDestroy(c->gexec);
+  for (hipGraphExec_t g : c->gexec) if (g) (void)hipGraphExecDestroy(g);
   for (hipStream_t s2 : c->side) (void)hipStreamDestroy(s2);
   for (hipEvent_t e : c->ev_fork) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev_join) (void)hipEventDestroy(e);
@@ -1211,8 +1336,10 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
   // parameters, optimiser state and statistics start at zero; the relay store too,
   // so that padded channels never hold stale bits
   HIP_TRY(c, hipMemsetAsync(c->ws, 0, c->r_tscr, c->stream));
-  if (c->gexec) { (void)hipGraphExecDestroy(c->gexec); c->gexec = nullptr; }
-  c->graph_tried = false;
+  for (int r = 0; r < 2; ++r) {
+    if (c->gexec[r]) { (void)hipGraphExecDestroy(c->gexec[r]); c->gexec[r] = nullptr; }
+    c->graph_tried[r] = false;
+  }
   c->bound = true;
   c->relayed_upto = 0;
   c->fold_dirty = true;
@@ -1238,6 +1365,16 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
           HIP_TRY(c, hipMemcpyAsync(c->ws + bp.table, bp.ttable.data(), bp.ttable.size() * sizeof(TransposeEntry),
                                     hipMemcpyHostToDevice, c->stream));
         bp.dirty = true;
+        // mix ops start from the descriptor's weights; alpha stays undefined until loaded or trained
+        bp.alpha_defined.assign(bp.nmix, 0);
+        for (const OpPlan& op : bp.ops) {
+          if (op.d.type != OP_MIX) continue;
+          float pk[8] = {};
+          for (int k = 0; k < op.d.nin; ++k) pk[k] = (float)c->pool[op.d.pofs + k];
+          HIP_TRY(c, hipMemcpyAsync(c->ws + bp.mix + ((size_t)op.mix_slot * kMixState + kMixP) * sizeof(float), pk,
+                                    sizeof pk, hipMemcpyHostToDevice, c->stream));
+          HIP_TRY(c, hipStreamSynchronize(c->stream));
+        }
       }
     }
   HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1344,54 +1481,71 @@ int pbd_student_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_
 }
 
 int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev) {
-  int rc = check_ready(c);
-  if (rc) return rc;
-  if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
-  if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
-  if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
-  // The body of the step touches only workspace addresses, so it is captured once into a HIP
-  // graph and replayed: ~300 small launches per step would otherwise be bound by launch cost.
-  // Capture needs a real stream and no profiling events; otherwise the kernels are launched directly.
-  const bool want_graph = c->stream != nullptr && !c->prof_on && !c->o.no_graph;
-  rc = dispatch(c, [&](auto& e) { e.set_lr(lr); e.prepare(x_dev); });
-  if (rc) return rc;
-  if (want_graph && !c->gexec && !c->graph_tried) {
-    c->graph_tried = true;
-    hipGraph_t graph = nullptr;
-    bool fork = c->concurrent;
-    if (fork && c->side.empty()) {
-      for (int b = 0; b < c->B && fork; ++b) {
-        hipStream_t s2; hipEvent_t e1, e2;
-        fork = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking) == hipSuccess &&
-               hipEventCreateWithFlags(&e1, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&e2, hipEventDisableTiming) == hipSuccess;
-        if (fork) { c->side.push_back(s2); c->ev_fork.push_back(e1); c->ev_join.push_back(e2); }
-      }
-    }
-    fork = fork && (int)c->side.size() == c->B;
-    if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
-      dispatch(c, [&](auto& e) { e.step_body(fork); });
-      hipError_t ee = hipStreamEndCapture(c->stream, &graph);
-      if (ee == hipSuccess && graph && hipGraphInstantiate(&c->gexec, graph, nullptr, nullptr, 0) != hipSuccess)
-        c->gexec = nullptr;
-      if (graph) (void)hipGraphDestroy(graph);
-    }
-    (void)hipGetLastError();
-  }
-  if (want_graph && c->gexec) {
-    HIP_TRY(c, hipGraphLaunch(c->gexec, c->stream));
-    c->relayed_upto = c->B;
-    for (BlockPlan& bp : c->net[1]) bp.stepped = c->concurrent;
-    c->net[1].back().stepped = true;
-  } else {
-    rc = dispatch(c, [&](auto& e) { e.step_body(false); });
-    if (rc) return rc;
-  }
-  HIP_TRY(c, hipMemcpyAsync(losses_dev, c->ws + c->loss_off, (size_t)c->B * 4, hipMemcpyDeviceToDevice, c->stream));
-  return after_launches(c);
+  return whole_step(c, x_dev, lr, losses_dev, 0);
 }
 
-int pbd_uses_graph(const pbd_ctx* c) { return c && c->gexec ? 1 : 0; }
+int pbd_distill_arch_step(pbd_ctx* c, const float* x_dev, float lr_alpha, float* losses_dev) {
+  return whole_step(c, x_dev, lr_alpha, losses_dev, 1);
+}
+
+int pbd_arch_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr_alpha, float* loss_dev) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (i < 1 || i > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", i, c->B);
+  if (!std::isfinite(lr_alpha)) return fail(c, PBD_EINVAL, "learning rate is not finite");
+  if (!loss_dev) return fail(c, PBD_EINVAL, "loss_dev is null");
+  if (c->relayed_upto < i) return fail(c, PBD_ESTATE, "the teacher has not produced A_%d yet", i);
+  if ((rc = check_view(c, A_prev, i - 1, "A_prev"))) return rc;
+  if ((rc = check_view(c, A_i, i, "A_i"))) return rc;
+  if ((rc = define_alpha(c, i - 1))) return rc;
+  return dispatch(c, [&](auto& e) { e.set_lr(lr_alpha); e.student_block(i - 1, loss_dev, true); });
+}
+
+int pbd_load_alpha(pbd_ctx* c, int32_t b, int32_t opi, const float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  const OpPlan* op = find_mix(c, b, opi);
+  if (!op) return fail(c, PBD_EINVAL, "op %d of student block %d is not a mix", opi, b);
+  if (n != (size_t)op->d.nin) return fail(c, PBD_ESHAPE, "the mix has %d inputs, %zu given", op->d.nin, n);
+  float rec[kMixState] = {};
+  double top = -INFINITY, sum = 0.0;
+  for (size_t k = 0; k < n; ++k) {
+    if (!std::isfinite(host[k])) return fail(c, PBD_EINVAL, "alpha[%zu] is not finite", k);
+    top = std::max(top, (double)host[k]);
+  }
+  for (size_t k = 0; k < n; ++k) sum += std::exp((double)host[k] - top);
+  for (size_t k = 0; k < n; ++k) {
+    rec[kMixAlpha + k] = host[k];
+    rec[kMixP + k] = (float)(std::exp((double)host[k] - top) / sum);
+  }
+  char* dev = mix_record(c, b, *op);
+  HIP_TRY(c, hipMemcpyAsync(dev + kMixAlpha * sizeof(float), rec + kMixAlpha, 8 * sizeof(float), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(dev + kMixP * sizeof(float), rec + kMixP, 8 * sizeof(float), hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->net[1][b].alpha_defined[op->mix_slot] = 1;
+  return PBD_OK;
+}
+
+int pbd_read_alpha(pbd_ctx* c, int32_t kind, int32_t b, int32_t opi, float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  const OpPlan* op = find_mix(c, b, opi);
+  if (!op) return fail(c, PBD_EINVAL, "op %d of student block %d is not a mix", opi, b);
+  if (n != (size_t)op->d.nin) return fail(c, PBD_ESHAPE, "the mix has %d inputs, %zu asked", op->d.nin, n);
+  if (kind < PBD_PARAM || kind > PBD_PROB) return fail(c, PBD_EINVAL, "kind %d is none of PBD_PARAM, PBD_GRAD, PBD_MOMENTUM, PBD_PROB", kind);
+  if (kind != PBD_PROB && !c->net[1][b].alpha_defined[op->mix_slot])
+    return fail(c, PBD_ESTATE, "alpha of op %d of block %d is undefined until it is loaded or trained", opi, b);
+  const int at = kind == PBD_PARAM ? kMixAlpha : kind == PBD_GRAD ? kMixGrad : kind == PBD_MOMENTUM ? kMixMom : kMixP;
+  float rec[8];
+  HIP_TRY(c, hipMemcpyAsync(rec, mix_record(c, b, *op) + at * sizeof(float), sizeof rec, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (size_t k = 0; k < n; ++k) host[k] = rec[k];
+  return PBD_OK;
+}
+
+int pbd_uses_graph(const pbd_ctx* c) { return c && (c->gexec[0] || c->gexec[1]) ? 1 : 0; }
 
 int pbd_sync(pbd_ctx* c) {
   int rc = check_ready(c);

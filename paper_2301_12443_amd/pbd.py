@@ -16,13 +16,14 @@ LIB_PATH = os.path.join(_HERE, "libpbd.so")
 
 PBD_F32, PBD_BF16 = 0, 1
 PBD_TEACHER, PBD_STUDENT = 0, 1
-PBD_PARAM, PBD_GRAD, PBD_MOMENTUM = 0, 1, 2
+PBD_PARAM, PBD_GRAD, PBD_MOMENTUM, PBD_PROB = 0, 1, 2, 3
 STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
           -4: "PBD_ESTATE", -5: "PBD_EHIP"}
 
 SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
            "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
            "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_distill_step", "pbd_uses_graph", "pbd_sync",
+           "pbd_arch_step", "pbd_distill_arch_step", "pbd_load_alpha", "pbd_read_alpha",
            "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
 
 
@@ -77,6 +78,10 @@ def lib():
         L.pbd_student_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(pbd_tensor), C.POINTER(pbd_tensor),
                                        C.c_float, C.c_void_p]
         L.pbd_distill_step.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
+        L.pbd_arch_step.argtypes = L.pbd_student_step.argtypes
+        L.pbd_distill_arch_step.argtypes = L.pbd_distill_step.argtypes
+        L.pbd_load_alpha.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
+        L.pbd_read_alpha.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, fp, C.c_size_t]
         L.pbd_uses_graph.argtypes = [C.c_void_p]
         L.pbd_sync.argtypes = [C.c_void_p]
         L.pbd_set_profile.argtypes = [C.c_void_p, C.c_int32]
@@ -191,6 +196,25 @@ class Distiller:
 
     def distill_step(self, x_dev, lr):
         self._check(lib().pbd_distill_step(self.h, x_dev.data_ptr(), lr, self.losses.data_ptr()))
+
+    def arch_step(self, i, lr_alpha, a_prev=None, a_i=None):
+        """Architecture round of block i (1-based): alpha trained, weights frozen."""
+        a_prev = self.views[i - 1] if a_prev is None else a_prev
+        a_i = self.views[i] if a_i is None else a_i
+        self._check(lib().pbd_arch_step(self.h, i, C.byref(a_prev), C.byref(a_i), lr_alpha,
+                                        self.losses.data_ptr() + 4 * (i - 1)))
+
+    def distill_arch_step(self, x_dev, lr_alpha):
+        self._check(lib().pbd_distill_arch_step(self.h, x_dev.data_ptr(), lr_alpha, self.losses.data_ptr()))
+
+    def load_alpha(self, b, j, alpha):
+        a = np.ascontiguousarray(alpha, dtype=np.float32).ravel()
+        self._check(lib().pbd_load_alpha(self.h, b, j, _fp(a), a.size))
+
+    def read_alpha(self, b, j, n, kind=PBD_PARAM):
+        out = np.empty(n, dtype=np.float32)
+        self._check(lib().pbd_read_alpha(self.h, kind, b, j, _fp(out), n))
+        return out
 
     def uses_graph(self) -> bool:
         return bool(lib().pbd_uses_graph(self.h))

@@ -110,3 +110,26 @@ def layer_workloads():
     v = s.cba(0, 384, 1); s.cba(v, 384, 3)
     wl("l_deepK3x3", (256, 7, 7), t, s, 32)
     return out
+
+
+def supernet():
+    """The tiny two-layer supernet block of pattern_workloads()."""
+    return next(w for w in pattern_workloads() if w.name == "p_supernet")
+
+
+def mix_ops(wl, b=0):
+    return [(j, len(op.inputs)) for j, op in enumerate(wl.student[b].ops) if op.type == W.OP_MIX]
+
+
+def twin_candidates(n=3, act=W.ACT_NONE):
+    """A mix of n candidates of one shape (dense 3x3 -> 1x1), then a rectified residual sum."""
+    t, s = W.Block(), W.Block()
+    t.cba(0, 8, 3)
+    outs = []
+    for _ in range(n):
+        v = s.cba(0, 16, 3)
+        outs.append(s.cba(v, 8, 1, act=W.ACT_NONE))
+    m = s.mix(outs, [1.0 / n] * n)
+    v = s.cba(m, 8, 3)
+    s.add(m, v, act=act)
+    return W.Workload("twins", 3, (8, 6, 6), [t], [s], "f32", lr=0.05)

@@ -1,0 +1,301 @@
+"""GPU parity of the architecture round (Sec. VI-A, neural architecture search: a second
+forward/backward round per step trains the architecture parameters alpha of the supernet's mix ops
+with the weights frozen) through the C ABI, against the CPU oracle.
+
+Tolerances: float32 path 1e-4, bf16 path 2e-2 (max-norm relative error per tensor; the gradient of
+alpha is measured against its largest component within the mix op)."""
+import numpy as np
+import pytest
+
+import parity
+from helpers import make_oracle, max_rel, mix_ops, supernet, twin_candidates
+from oracle import pbd_oracle as orc
+from paper_2301_12443_amd import pbd, workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+KINK_FLOOR = 2e-6
+LR_ALPHA = 0.3
+
+
+def _weights(d, wl, b):
+    return {k: d.read_tensor(pbd.PBD_PARAM, 1, b, k[0], k[1], shape).copy()
+            for k, shape in W.param_shapes(wl, W.NET_STUDENT, b).items() if k[1] <= W.P_BETA}
+
+
+def _two_round_steps(wl, precision, steps, alpha0=None, storage=None, kink_floor=0.0, order=None, noise=False):
+    """Per step and block: architecture round, then weight round, on both sides.  Returns errors.
+    noise=True (one step, storage-rounded oracle): also "<key>.noise", what the storage rounding alone
+    does to the gradient of alpha (oracle vs plain fp64 oracle)."""
+    import torch
+    d = parity.make_distiller(wl, wl.batch, precision)
+    o = make_oracle(wl, storage=storage)
+    o64 = make_oracle(wl) if noise else None
+    assert not noise or (steps == 1 and not alpha0)
+    if alpha0:
+        for (b, j), a in alpha0.items():
+            d.load_alpha(b, j, a)
+            o.set_alpha(b, j, a)
+            assert max_rel(d.read_alpha(b, j, len(a), pbd.PBD_PROB), o.get_alpha(b, j, len(a), orc.ALPHA_PROB)) < 1e-6
+    errs = {}
+    for step in range(steps):
+        x = W.make_input(wl, step=step)
+        acts = o.teacher_relay(x)
+        d.teacher_relay(torch.from_numpy(x).cuda())
+        for i in (order or range(1, wl.B + 1)):
+            b = i - 1
+            for cand in range(64 if kink_floor else 0):
+                o.student_step(i, acts[i - 1], acts[i], 0.0, orc.MODE_LOSS)
+                if o.kink_margin(b) >= kink_floor:
+                    break
+                x = W.make_input(wl, step=step + 1000 * (cand + 1))
+                acts = o.teacher_relay(x)
+                d.teacher_relay(torch.from_numpy(x).cuda())
+            before = _weights(d, wl, b)
+            d.arch_step(i, LR_ALPHA)
+            loss_o = o.student_step(i, acts[i - 1], acts[i], LR_ALPHA, orc.MODE_ARCH_STEP)
+            if o64 is not None:
+                acts64 = o64.teacher_relay(x)
+                o64.student_step(i, acts64[i - 1], acts64[i], LR_ALPHA, orc.MODE_ARCH_STEP)
+            d.sync()
+            tag = f"s{step}.b{b}"
+            errs[f"{tag}.arch.loss"] = abs(float(d.losses[b].item()) - loss_o) / abs(loss_o)
+            for j, n in mix_ops(wl, b):
+                ref = o.get_alpha(b, j, n, orc.ALPHA_GRAD)
+                den = np.max(np.abs(ref))
+                errs[f"{tag}.op{j}.dalpha"] = float(np.max(np.abs(d.read_alpha(b, j, n, pbd.PBD_GRAD) - ref)) / den)
+                if o64 is not None:
+                    errs[f"{tag}.op{j}.dalpha.noise"] = float(np.max(np.abs(o64.get_alpha(b, j, n, orc.ALPHA_GRAD) - ref)) / den)
+                refm = o.get_alpha(b, j, n, orc.ALPHA_MOMENTUM)
+                errs[f"{tag}.op{j}.alpha_mom"] = float(np.max(np.abs(d.read_alpha(b, j, n, pbd.PBD_MOMENTUM) - refm)) / np.max(np.abs(refm)))
+                refa = o.get_alpha(b, j, n)
+                # alpha moves by lr x momentum: measured against that step (alpha itself may be near 0)
+                errs[f"{tag}.op{j}.alpha"] = float(np.max(np.abs(d.read_alpha(b, j, n) - refa)) /
+                                                  max(np.max(np.abs(refa)), LR_ALPHA * np.max(np.abs(refm))))
+                errs[f"{tag}.op{j}.p"] = max_rel(d.read_alpha(b, j, n, pbd.PBD_PROB), o.get_alpha(b, j, n, orc.ALPHA_PROB))
+            after = _weights(d, wl, b)
+            for k in before:     # frozen in this round: bit for bit
+                assert np.array_equal(before[k], after[k]), (tag, k)
+            for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+                if slot in (W.P_RMEAN, W.P_RVAR):
+                    ref = o.get_tensor(orc.KIND_PARAM, 1, b, j, slot, shape)
+                    den = np.max(np.abs(ref))
+                    if slot == W.P_RMEAN:
+                        den = max(den, 0.1 * float(np.sqrt(np.max(o.get_tensor(orc.KIND_PARAM, 1, b, j, W.P_RVAR, shape)))))
+                    errs[f"{tag}.op{j}.running{slot}"] = float(np.max(np.abs(d.read_tensor(pbd.PBD_PARAM, 1, b, j, slot, shape) - ref)) / den)
+            # weight round with the alpha just trained
+            d.student_step(i, wl.lr)
+            loss_o = o.student_step(i, acts[i - 1], acts[i], wl.lr)
+            d.sync()
+            errs[f"{tag}.weight.loss"] = abs(float(d.losses[b].item()) - loss_o) / abs(loss_o)
+            for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+                if slot == W.P_WEIGHT:
+                    ref = o.get_tensor(orc.KIND_PARAM, 1, b, j, slot, shape)
+                    errs[f"{tag}.op{j}.w"] = max_rel(d.read_tensor(pbd.PBD_PARAM, 1, b, j, slot, shape), ref)
+    return errs
+
+
+def _assert_all(errs, tol):
+    bad = {k: v for k, v in errs.items() if not v < tol}
+    assert not bad, dict(list(sorted(bad.items(), key=lambda kv: -kv[1]))[:8])
+
+
+def test_f32_two_round_steps_from_the_descriptor_weights():
+    """alpha starts at ln p of the descriptor (0.5, 0.3, 0.2); three steps of both rounds."""
+    _assert_all(_two_round_steps(supernet(), "f32", 3, kink_floor=KINK_FLOOR), TOL_F32)
+
+
+def test_f32_two_round_steps_from_loaded_alpha():
+    wl = supernet()
+    rng = np.random.default_rng(9)
+    alpha0 = {(0, j): rng.normal(0.0, 0.8, n).astype(np.float32) for j, n in mix_ops(wl)}
+    _assert_all(_two_round_steps(wl, "f32", 2, alpha0=alpha0, kink_floor=KINK_FLOOR), TOL_F32)
+
+
+@pytest.mark.parametrize("n", [2, 4, 8])
+def test_f32_mix_widths_and_rectified_residual(n):
+    """2, 4 and 8 candidates (the widest a mix op takes), a rectified sum after the mix."""
+    wl = twin_candidates(n, W.ACT_RELU)
+    rng = np.random.default_rng(n)
+    alpha0 = {(0, j): rng.normal(0.0, 0.5, m).astype(np.float32) for j, m in mix_ops(wl)}
+    _assert_all(_two_round_steps(wl, "f32", 2, alpha0=alpha0, kink_floor=KINK_FLOOR), TOL_F32)
+
+
+def test_bf16_two_round_step():
+    """bf16 kernels against the oracle with bf16 storage rounding (decisions taken in one precision) on
+    two mixed layers of three MBConv candidates at a MobileNet layer shape.  The gradient of alpha is
+    a difference of inner products that nearly agree (every candidate approximates the same target),
+    so storage noise is amplified in it: per mix op the bound for alpha's gradient, momentum and step
+    is the larger of 2e-2 and half of what the storage rounding alone does to that gradient."""
+    t, s = W.Block(), W.Block()
+    v = W._mbconv(t, 0, 16, 24, 3, 6, 2); W._mbconv(t, v, 24, 24, 3, 6, 1)
+    cands = ((3, 3), (5, 6), (7, 3))
+    v = s.mix([W._mbconv(s, 0, 16, 24, k, e, 2, residual=False) for k, e in cands], [0.5, 0.3, 0.2])
+    m = s.mix([W._mbconv(s, v, 24, 24, k, e, 1, residual=False) for k, e in cands], [0.2, 0.3, 0.5])
+    s.add(v, m)
+    wl = W.Workload("l_supernet", 16, (16, 28, 28), [t], [s], "bf16", lr=0.05)
+    errs = _two_round_steps(wl, "bf16", 1, storage="bf16", noise=True)
+    print({k: round(v, 4) for k, v in errs.items() if "alpha" in k}, flush=True)
+    bad = {}
+    for k, v in errs.items():
+        if k.endswith(".noise"):
+            continue
+        tol = TOL_BF16
+        if "alpha" in k:
+            stem = k[:k.rindex(".")]
+            tol = max(tol, 0.5 * errs[stem + ".dalpha.noise"])
+        if not v < tol:
+            bad[k] = (v, tol)
+    assert not bad, bad
+
+
+def _whole_step_case(precision, hw, shift):
+    """The supernet graph of config 4 (6 blocks x 4 mixed layers x 6 candidates) at batch 2 through
+    pbd_distill_arch_step; returns (distiller, oracle, x)."""
+    import torch
+    wl = W.mbv2_supernet(batch=2, hw=hw, precision=precision)
+    d = parity.make_distiller(wl, 2, precision)
+    o = make_oracle(wl, storage="bf16" if precision == "bf16" else None)
+    if shift is not None:
+        for b in range(wl.B):
+            for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+                if slot == W.P_BETA:
+                    beta = np.full(shape, shift, dtype=np.float32)
+                    o.set_param(1, b, j, slot, beta)
+                    d.load_param(1, b, j, slot, beta)
+    x = W.make_input(wl)
+    d.distill_arch_step(torch.from_numpy(x).cuda(), LR_ALPHA)
+    d.sync()
+    return wl, d, o, x
+
+
+def test_config4_graph_f32_whole_architecture_step():
+    """Student beta is shifted on both sides so that no pre-activation sits on a rectifier kink (as
+    in the float32 whole-graph test of the weight round)."""
+    wl, d, o, x = _whole_step_case("f32", 64, 3.0)
+    losses = o.relay_arch_step(x, LR_ALPHA)
+    assert np.all(np.abs(d.losses.cpu().numpy() - losses) / losses < TOL_F32)
+    for b in range(wl.B):
+        ops = mix_ops(wl, b)
+        assert len(ops) == 4
+        for j, n in ops:
+            ref = o.get_alpha(b, j, n, orc.ALPHA_GRAD)
+            got = d.read_alpha(b, j, n, pbd.PBD_GRAD)
+            assert np.max(np.abs(got - ref)) < TOL_F32 * np.max(np.abs(ref)), (b, j, got, ref)
+            assert max_rel(d.read_alpha(b, j, n, pbd.PBD_PROB), o.get_alpha(b, j, n, orc.ALPHA_PROB)) < TOL_F32
+
+
+def test_config4_graph_bf16_whole_architecture_step():
+    """bf16 MFMA path at the real graph.  Losses: 2e-2 against both oracles.  The gradient of alpha is a
+    difference of inner products that nearly agree (every candidate approximates the same target) taken
+    after up to twelve batch-normalised layers over a few hundred values each, so bf16 storage rounding
+    alone moves it by 10-60 % at this depth (oracle with bf16 storage vs plain fp64 oracle, printed
+    below).  Elementwise bf16 parity of the round is pinned at layer depth by test_bf16_two_round_step
+    and the executor on this graph by the float32 test above; here the bound per block is: relative L2
+    distance to the bf16-storage oracle over the block's 24 architecture gradients below the larger of
+    2e-2 and twice that storage noise."""
+    wl, d, o16, x = _whole_step_case("bf16", 96, None)
+    o64 = make_oracle(wl)
+    l16 = o16.relay_arch_step(x, LR_ALPHA)
+    l64 = o64.relay_arch_step(x, LR_ALPHA)
+    lg = d.losses.cpu().numpy()
+    assert np.all(np.abs(lg - l64) / l64 < TOL_BF16), (lg, l64)
+    assert np.all(np.abs(lg - l16) / l16 < TOL_BF16), (lg, l16)
+    report = []
+    for b in range(wl.B):
+        cat = lambda f: np.concatenate([f(j, n) for j, n in mix_ops(wl, b)])
+        r16 = cat(lambda j, n: o16.get_alpha(b, j, n, orc.ALPHA_GRAD))
+        r64 = cat(lambda j, n: o64.get_alpha(b, j, n, orc.ALPHA_GRAD))
+        got = cat(lambda j, n: d.read_alpha(b, j, n, pbd.PBD_GRAD))
+        err = float(np.linalg.norm(got - r16) / np.linalg.norm(r16))
+        noise = float(np.linalg.norm(r64 - r16) / np.linalg.norm(r16))
+        report.append((b, round(err, 4), round(noise, 4)))
+    print("per block: dalpha distance to the bf16-storage oracle, storage noise:", report, flush=True)
+    for b, err, noise in report:
+        assert err < max(TOL_BF16, 2.0 * noise), report
+
+
+def test_full_size_architecture_step_properties():
+    """Config 4 at its full batch in the benchmark's launch configuration (bf16, captured graph):
+    two runs give the same bits; the split calls in reverse block order give the same bits as the
+    whole step; the gradient of alpha has no component along (1,...,1); p stays a distribution; the
+    weights are untouched; no weight-gradient or update kernel runs in the round."""
+    import torch
+    wl = W.mbv2_supernet()
+    x = torch.from_numpy(W.make_input(wl)).cuda()
+
+    def state(d):
+        return np.concatenate([d.read_alpha(b, j, n, kind) for b in range(wl.B) for j, n in mix_ops(wl, b)
+                               for kind in (pbd.PBD_PARAM, pbd.PBD_GRAD, pbd.PBD_MOMENTUM, pbd.PBD_PROB)])
+
+    a = parity.make_distiller(wl)
+    w0 = _weights(a, wl, 2)
+    a.distill_arch_step(x, LR_ALPHA); a.distill_arch_step(x, LR_ALPHA); a.sync()
+    assert a.uses_graph()
+    sa, la = state(a), a.losses.cpu().numpy().copy()
+    w1 = _weights(a, wl, 2)
+    assert all(np.array_equal(w0[k], w1[k]) for k in w0)
+    for b in range(wl.B):
+        for j, n in mix_ops(wl, b):
+            g = a.read_alpha(b, j, n, pbd.PBD_GRAD)
+            p = a.read_alpha(b, j, n, pbd.PBD_PROB)
+            assert np.max(np.abs(g)) > 0 and abs(float(g.sum())) < 1e-5 * np.max(np.abs(g))
+            assert abs(float(p.sum()) - 1.0) < 1e-6 and np.all(p > 0)
+    del a
+    torch.cuda.empty_cache()
+    b_ = parity.make_distiller(wl)
+    lb = np.zeros_like(la)
+    for step in range(2):
+        b_.teacher_relay(x)
+        for i in range(wl.B, 0, -1):
+            b_.arch_step(i, LR_ALPHA)
+        b_.sync()
+        lb = b_.losses.cpu().numpy().copy()
+    assert np.array_equal(sa, state(b_)) and np.array_equal(la, lb)
+    b_.set_profile(True); b_.reset_profile()
+    b_.teacher_relay(x)
+    for i in range(1, wl.B + 1):
+        b_.arch_step(i, LR_ALPHA)
+    names = {p["name"] for p in b_.get_profile() if p["net"] == pbd.PBD_STUDENT}
+    b_.set_profile(False)
+    assert "mix_dot" in names
+    assert not any(n.startswith(("wgrad", "dw_wgrad", "sgd", "sum_partials", "transpose")) for n in names), names
+
+
+def test_architecture_round_errors():
+    import torch
+    wl = supernet()
+    d = parity.make_distiller(wl, wl.batch, "f32")
+    (j, n), _ = mix_ops(wl)
+    with pytest.raises(pbd.PbdError) as e:
+        d.read_alpha(0, j, n)                       # undefined until loaded or trained
+    assert e.value.code == -4
+    assert np.allclose(d.read_alpha(0, j, n, pbd.PBD_PROB), wl.student[0].ops[j].p)
+    with pytest.raises(pbd.PbdError) as e:
+        d.load_alpha(0, j, np.zeros(n + 1))
+    assert e.value.code == -2
+    with pytest.raises(pbd.PbdError) as e:
+        d.load_alpha(0, 0, np.zeros(n))             # op 0 is a convolution
+    assert e.value.code == -1
+    with pytest.raises(pbd.PbdError) as e:
+        d.load_alpha(0, j, np.array([0.0, np.inf, 0.0]))
+    assert e.value.code == -1
+    with pytest.raises(pbd.PbdError) as e:
+        d.arch_step(1, LR_ALPHA, pbd.pbd_tensor(), pbd.pbd_tensor())
+    assert e.value.code == -4                       # no relay yet
+    # descriptor weights that are no distribution cannot seed alpha
+    t, s = W.Block(), W.Block()
+    t.cba(0, 8, 3)
+    s.mix([s.cba(0, 8, 3), s.cba(0, 8, 1)], [0.7, 0.7])
+    bad = W.Workload("bad_mix", 2, (8, 6, 6), [t], [s], "f32", lr=0.05)
+    db = parity.make_distiller(bad, 2, "f32")
+    db.teacher_relay(torch.from_numpy(W.make_input(bad)).cuda())
+    with pytest.raises(pbd.PbdError) as e:
+        db.arch_step(1, LR_ALPHA)
+    assert e.value.code == -4 and "sum" in str(e.value)
+    db.load_alpha(0, 2, [0.0, 0.0])                 # after which the round runs
+    db.arch_step(1, LR_ALPHA)
+    db.sync()
+    assert np.isfinite(float(db.losses[0].item()))

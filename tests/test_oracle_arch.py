@@ -5,31 +5,9 @@ import pytest
 import torch
 
 import torch_ref
-from helpers import make_oracle, max_rel, pattern_workloads
+from helpers import make_oracle, max_rel, mix_ops, supernet, twin_candidates
 from oracle import pbd_oracle as orc
 from paper_2301_12443_amd import workloads as W
-
-
-def supernet():
-    return next(w for w in pattern_workloads() if w.name == "p_supernet")
-
-
-def mix_ops(wl, b=0):
-    return [(j, len(op.inputs)) for j, op in enumerate(wl.student[b].ops) if op.type == W.OP_MIX]
-
-
-def twin_candidates(n=3, act=W.ACT_NONE):
-    """A mix of n candidates of one shape (dense 3x3 -> 1x1), then a rectified residual sum."""
-    t, s = W.Block(), W.Block()
-    t.cba(0, 8, 3)
-    outs = []
-    for _ in range(n):
-        v = s.cba(0, 16, 3)
-        outs.append(s.cba(v, 8, 1, act=W.ACT_NONE))
-    m = s.mix(outs, [1.0 / n] * n)
-    v = s.cba(m, 8, 3)
-    s.add(m, v, act=act)
-    return W.Workload("twins", 3, (8, 6, 6), [t], [s], "f32", lr=0.05)
 
 
 def test_alpha_gradient_matches_finite_differences():
