@@ -276,24 +276,35 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, 
   }
 }
 
-// Finalize kernels run 16 channels x 16 lanes per block: lane l adds chunks l, l+16, ... in order
-// and the 16 lane sums are then added in order (fixed association, independent of scheduling).
+// Finalize kernels run 8 channels x 32 lanes per block (thread = lane * 8 + channel): lane l adds
+// chunks l, l+32, ... in order, the 8 lanes of a channel inside one wave are added by a butterfly and
+// the 4 waves in a fixed order (fixed association, independent of scheduling).  Few chunks per lane
+// keep the chain of dependent loads short: these kernels sit between two passes over the tensor.
+constexpr int kFinalizeChannels = 8;
 __device__ __forceinline__ void finalize_sums(const float* __restrict__ part, int chunks, int Cp, int c,
                                               int lane, double& s1, double& s2) {
-  __shared__ double red1[16][17], red2[16][17];
-  const int cl = threadIdx.x & 15;
+  __shared__ double red1[4][kFinalizeChannels], red2[4][kFinalizeChannels];
+  const int cl = threadIdx.x & (kFinalizeChannels - 1);
   double a = 0.0, b = 0.0;
-  if (c < Cp)
-    for (int k = lane; k < chunks; k += 16) {
+  if (c < Cp) {
+#pragma unroll 4
+    for (int k = lane; k < chunks; k += 32) {
       a += (double)part[(long)k * 2 * Cp + c];
       b += (double)part[(long)k * 2 * Cp + Cp + c];
     }
-  red1[lane][cl] = a;
-  red2[lane][cl] = b;
-  __syncthreads();
-  s1 = 0.0; s2 = 0.0;
+  }
 #pragma unroll
-  for (int l = 0; l < 16; ++l) { s1 += red1[l][cl]; s2 += red2[l][cl]; }
+  for (int off = kFinalizeChannels; off < 64; off <<= 1) {
+    a += __shfl_xor(a, off, 64);
+    b += __shfl_xor(b, off, 64);
+  }
+  if ((threadIdx.x & 63) < kFinalizeChannels) {
+    red1[threadIdx.x >> 6][cl] = a;
+    red2[threadIdx.x >> 6][cl] = b;
+  }
+  __syncthreads();
+  s1 = (red1[0][cl] + red1[1][cl]) + (red1[2][cl] + red1[3][cl]);
+  s2 = (red2[0][cl] + red2[1][cl]) + (red2[2][cl] + red2[3][cl]);
 }
 
 // mean, biased variance -> inv std; running statistics
@@ -302,7 +313,7 @@ template <class T>
 __global__ void bn_finalize_kernel(const float* __restrict__ part, const T* __restrict__ y, int chunks,
                                    int Cp, double m, float* mean, float* invstd, float* rmean,
                                    float* rvar, float eps, float rho) {
-  const int c = blockIdx.x * 16 + (threadIdx.x & 15), lane = threadIdx.x >> 4;
+  const int c = blockIdx.x * kFinalizeChannels + (threadIdx.x & (kFinalizeChannels - 1)), lane = threadIdx.x >> 3;
   double s1, s2;
   finalize_sums(part, chunks, Cp, c, lane, s1, s2);
   if (c >= Cp || lane != 0) return;
@@ -386,7 +397,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 // k2 = dbeta/m, k3 = dgamma/m of  dy = gamma*invstd*(dpre - k2 - xhat*k3)
 __global__ void bn_bwd_finalize_kernel(const float* __restrict__ part, int chunks, int Cp, double m,
                                        float* g_gamma, float* g_beta, float* k2, float* k3) {
-  const int c = blockIdx.x * 16 + (threadIdx.x & 15), lane = threadIdx.x >> 4;
+  const int c = blockIdx.x * kFinalizeChannels + (threadIdx.x & (kFinalizeChannels - 1)), lane = threadIdx.x >> 3;
   double sb, sg;
   finalize_sums(part, chunks, Cp, c, lane, sb, sg);
   if (c >= Cp || lane != 0) return;

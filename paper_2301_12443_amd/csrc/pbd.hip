@@ -860,7 +860,7 @@ template <class T> struct Exec {
             ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_stats_kernel<T>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st, y, red(), M, op.cout_p, g);
           }
-          launch(c, bn_finalize_kernel<T>, (op.cout_p + 15) / 16, 256, 0, st, 
+          launch(c, bn_finalize_kernel<T>, op.cout_p / kFinalizeChannels, 256, 0, st, 
               red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
               wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
           {
@@ -934,7 +934,7 @@ template <class T> struct Exec {
                 dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
                 op.d.act, g);
           }
-          launch(c, bn_bwd_finalize_kernel, (op.cout_p + 15) / 16, 256, 0, st, red(), g.chunks, op.cout_p, (double)M,
+          launch(c, bn_bwd_finalize_kernel, op.cout_p / kFinalizeChannels, 256, 0, st, red(), g.chunks, op.cout_p, (double)M,
                                                                            grad + op.e_gamma, grad + op.e_beta,
                                                                            wsf(op.s_k2), wsf(op.s_k3));
           {
