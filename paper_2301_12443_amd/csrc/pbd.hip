@@ -864,7 +864,7 @@ template <class T> struct Exec {
               red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
               wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
           {
-            const ColGrid ga = col_grid(M, op.cout_p, 32, 2048);
+            const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);   // elementwise pass: many short workgroups
             ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st, y, z, wsf(op.s_mean), wsf(op.s_invstd),
                                                                        master + op.e_gamma, master + op.e_beta, M,
@@ -938,7 +938,7 @@ template <class T> struct Exec {
                                                                            grad + op.e_gamma, grad + op.e_beta,
                                                                            wsf(op.s_k2), wsf(op.s_k3));
           {
-            const ColGrid ga = col_grid(M, op.cout_p, 16, 2048);
+            const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);
             ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_bwd_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st, 
                 dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
