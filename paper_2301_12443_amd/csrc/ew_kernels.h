@@ -154,29 +154,31 @@ struct ColGrid {
   long rows_per_chunk;
 };
 
-// in-block reduction of NV floats per thread over the row lanes: a fixed binary tree (lane r adds
-// lane r + stride for stride = rl/2, rl/4, ... 1), so the association never depends on scheduling
+// in-block reduction of NV floats per thread over the row lanes.  Threads are numbered
+// row_lane * cvl + cv_lane, so the lanes of a wave that share a channel vector are cvl apart: a
+// butterfly (lane ^ cvl, ^ 2 cvl, ... ^ 32) adds them without leaving the registers, then the four
+// waves' sums meet in LDS and are added as (w0 + w1) + (w2 + w3).  The association is fixed, so
+// the result never depends on scheduling.  smem: at least 4 * cvl * NV floats.
 template <int NV>
 __device__ __forceinline__ void block_col_reduce(float (&acc)[NV], float* smem, int cvl, int cv_lane,
                                                  int row_lane, float* out /*[NV]*/, bool& owner) {
-  const int rl = 256 / cvl;
   owner = row_lane == 0;
-  // smem layout [row_lane][cv_lane][NV]
-  float* mine = smem + (row_lane * cvl + cv_lane) * NV;
+  for (int off = cvl; off < 64; off <<= 1) {
 #pragma unroll
-  for (int k = 0; k < NV; ++k) mine[k] = acc[k];
-  __syncthreads();
-  for (int stride = rl >> 1; stride > 0; stride >>= 1) {
-    if (row_lane < stride) {
-      const float* other = smem + ((row_lane + stride) * cvl + cv_lane) * NV;
-#pragma unroll
-      for (int k = 0; k < NV; ++k) mine[k] += other[k];
-    }
-    __syncthreads();
+    for (int k = 0; k < NV; ++k) acc[k] += __shfl_xor(acc[k], off, 64);
   }
-  if (owner) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane < cvl) {
+    float* mine = smem + (wave * cvl + lane) * NV;
 #pragma unroll
-    for (int k = 0; k < NV; ++k) out[k] = mine[k];
+    for (int k = 0; k < NV; ++k) mine[k] = acc[k];
+  }
+  __syncthreads();
+  if (owner) {   // wave 0, lane == cv_lane
+    const float* w0 = smem + cv_lane * NV;
+    const int ws = cvl * NV;
+#pragma unroll
+    for (int k = 0; k < NV; ++k) out[k] = (w0[k] + w0[ws + k]) + (w0[2 * ws + k] + w0[3 * ws + k]);
   }
   __syncthreads();
 }
