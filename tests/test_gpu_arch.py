@@ -220,7 +220,7 @@ def test_config4_graph_bf16_whole_architecture_step():
 def test_full_size_architecture_step_properties():
     """Config 4 at its full batch in the benchmark's launch configuration (bf16, captured graph):
     two runs give the same bits; the split calls in reverse block order give the same bits as the
-    whole step; the gradient of alpha has no component along (1,...,1); p stays a distribution; the
+    whole step; the gradient of alpha has no component along (1,...,1) beyond float32 rounding; p stays a distribution; the
     weights are untouched; no weight-gradient or update kernel runs in the round."""
     import torch
     wl = W.mbv2_supernet()
@@ -241,7 +241,9 @@ def test_full_size_architecture_step_properties():
         for j, n in mix_ops(wl, b):
             g = a.read_alpha(b, j, n, pbd.PBD_GRAD)
             p = a.read_alpha(b, j, n, pbd.PBD_PROB)
-            assert np.max(np.abs(g)) > 0 and abs(float(g.sum())) < 1e-5 * np.max(np.abs(g))
+            # sum_j dalpha_j = (1 - sum p) x sum_k p_k g_k: p sums to one only to float32 rounding and the
+            # mean of g is some 10^2 times the gradient that is left after subtracting it
+            assert np.max(np.abs(g)) > 0 and abs(float(g.sum())) < 1e-3 * np.max(np.abs(g))
             assert abs(float(p.sum()) - 1.0) < 1e-6 and np.all(p > 0)
     del a
     torch.cuda.empty_cache()
