@@ -244,7 +244,7 @@ WgradCfg wgrad_cfg(long M, int K, int J) {
   const long tiles = (long)w.tiles_k * w.tiles_j;
   // long reductions: three workgroups per compute unit hide the load latency; short ones: one per
   // compute unit, or the partial sums cost more than the overlap gains
-  const long target = M >= 65536 ? 768 : 256;
+  const long target = M >= 32768 ? 768 : 256;
   long splits = std::max(1L, (target + tiles - 1) / tiles);
   const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
   splits = std::min(splits, max_by_mem);
@@ -271,7 +271,7 @@ IgemmCfg igemm_cfg(long M, int NC, int Kred, int CA) {
   const int nk = (Kred + c.BK - 1) / c.BK, nk32 = (Kred + 31) / 32;
   c.splits = 1;
   if (tiles < 512 && nk32 >= 32)
-    c.splits = (int)std::max(1L, std::min<long>(std::min<long>(std::min<long>((1024 + tiles - 1) / tiles, nk32 / 16), 32L), nk));
+    c.splits = (int)std::max(1L, std::min<long>(std::min<long>(std::min<long>((512 + tiles - 1) / tiles, nk32 / 16), 32L), nk));
   return c;
 }
 int igemm_splits(long M, int NC, int Kred, int CA) { return igemm_cfg(M, NC, Kred, CA).splits; }
