@@ -2,7 +2,7 @@
 
 A step = pbd_distill_step: cast x, teacher relay T_1..T_B (each block once, activations kept in
 HBM), then for every student block forward, MSE loss + gradient, backward and the SGD-momentum
-update.  Prints ONE JSON line (see README for the fields)."""
+update.  Prints ONE JSON line."""
 import argparse
 import json
 import os
@@ -35,28 +35,49 @@ HBM_TRAFFIC_PER_LAUNCH = {
 def roofline_from_profile(prof, steps):
     """Aggregate the library's per-launch HIP-event timings by kernel class; report the class that
     takes the most time against the roofline that bounds it."""
-    agg = {}
+    ridge_mfma = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    ridge_alu = PEAK_FP32_VALU_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+
+    def bound_of(p):
+        # contractions (implicit GEMM, weight gradient) run on the matrix cores; depthwise kernels do
+        # their multiply-adds on the vector ALUs; everything else only moves bytes.  A launch counts
+        # against the compute peak only when its own arithmetic intensity lies above the ridge.
+        ai = p["flops"] / p["bytes"] if p["bytes"] else 0.0
+        if p["name"].startswith(("igemm_", "wgrad_")) and ai >= ridge_mfma:
+            return "mfma"
+        if p["name"].startswith("dw_") and ai >= ridge_alu:
+            return "alu"
+        return "hbm"
+
+    agg, groups = {}, {}
     for p in prof:
         a = agg.setdefault(p["name"], dict(ms=0.0, bytes=0.0, flops=0.0, n=0))
         a["ms"] += p["ms"]; a["bytes"] += p["bytes"]; a["flops"] += p["flops"]; a["n"] += 1
-    name, a = max(agg.items(), key=lambda kv: kv[1]["ms"])
+        g = groups.setdefault((p["name"], bound_of(p)), dict(ms=0.0, bytes=0.0, flops=0.0, n=0))
+        g["ms"] += p["ms"]; g["bytes"] += p["bytes"]; g["flops"] += p["flops"]; g["n"] += 1
+    # the kernel class with the most time; of its launches, those on the side of the ridge where most
+    # of that time is spent
+    name = max(agg.items(), key=lambda kv: kv[1]["ms"])[0]
+    bound, a = max(((k[1], v) for k, v in groups.items() if k[0] == name), key=lambda kv: kv[1]["ms"])
     avg_s = a["ms"] / a["n"] * 1e-3
-    ai = a["flops"] / a["bytes"] if a["bytes"] else 0.0
-    # contractions (implicit GEMM, weight gradient) run on the matrix cores; depthwise kernels do
-    # their multiply-adds on the vector ALUs; everything else only moves bytes
-    if name.startswith(("igemm_", "wgrad_")) and ai >= PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
-        achieved, peak, unit, bound = a["flops"] / a["n"] / avg_s / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s", "mfma"
-    elif name.startswith("dw_") and ai >= PEAK_FP32_VALU_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
-        achieved, peak, unit, bound = a["flops"] / a["n"] / avg_s / 1e12, PEAK_FP32_VALU_TFLOPS, "TFLOP/s", "alu"
+    if bound == "mfma":
+        achieved, peak, unit = a["flops"] / a["n"] / avg_s / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+    elif bound == "alu":
+        achieved, peak, unit = a["flops"] / a["n"] / avg_s / 1e12, PEAK_FP32_VALU_TFLOPS, "TFLOP/s"
     else:
-        achieved, peak, unit, bound = a["bytes"] / a["n"] / avg_s / 1e9, PEAK_HBM_GBS, "GB/s", "hbm"
+        achieved, peak, unit = a["bytes"] / a["n"] / avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
     classes = {k: dict(ms_per_step=round(v["ms"] / steps, 4), launches_per_step=v["n"] // steps,
                        gbs=round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] else 0.0,
                        tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] else 0.0)
                for k, v in sorted(agg.items(), key=lambda kv: -kv[1]["ms"])}
+    # the whole step against its algorithmic work: every profiled launch's bytes and flops, once
+    totals = dict(algorithmic_bytes=round(sum(v["bytes"] for v in agg.values()) / steps),
+                  algorithmic_flops=round(sum(v["flops"] for v in agg.values()) / steps),
+                  launches=sum(v["n"] for v in agg.values()) // steps,
+                  kernel_ms=round(sum(v["ms"] for v in agg.values()) / steps, 4))
     return dict(bound=bound, achieved=round(achieved, 2), peak=peak, unit=unit, frac=round(achieved / peak, 4),
                 traffic=None, kernel=name, avg_launch_us=round(avg_s * 1e6, 2),
-                launches_per_step=a["n"] // steps), classes
+                launches_per_step=a["n"] // steps, class_launches_per_step=agg[name]["n"] // steps), classes, totals
 
 
 def measure_peaks(torch):
@@ -124,7 +145,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU relay step only: run with --gpus 1 "
-              "(this build has no multi-GPU path; DESIGN.md says how it would shard)", file=sys.stderr)
+              "(this build has no multi-GPU path)", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -169,8 +190,9 @@ def main():
             d.distill_step(x, wl.lr)
     prof = d.get_profile()
     d.set_profile(False)
-    roof, classes = roofline_from_profile(prof, psteps)
-    roof["traffic"] = HBM_TRAFFIC_PER_LAUNCH.get(args.config, {}).get(roof["kernel"])
+    roof, classes, totals = roofline_from_profile(prof, psteps)
+    if roof["launches_per_step"] == roof["class_launches_per_step"]:   # the counters were averaged over the whole class
+        roof["traffic"] = HBM_TRAFFIC_PER_LAUNCH.get(args.config, {}).get(roof["kernel"])
     if args.classes:
         for k, v in classes.items():
             print(f"{k:24s} {v}", file=sys.stderr)
@@ -198,6 +220,13 @@ def main():
                                       args.mode, "teacher relay + student fwd/MSE/bwd/SGD-momentum"), "lr": wl.lr},
         "roofline": roof,
     }
+    # step level: unfused algorithmic bytes and flops of one step over the measured step time (how far
+    # the whole step is from moving its tensors once at the HBM peak / doing its MACs at the MFMA peak)
+    step_s = dt / args.steps
+    rec["step_level"] = dict(totals, GBs=round(totals["algorithmic_bytes"] / step_s / 1e9, 1),
+                             TFLOPs=round(totals["algorithmic_flops"] / step_s / 1e12, 2),
+                             hbm_frac=round(totals["algorithmic_bytes"] / step_s / 1e9 / PEAK_HBM_GBS, 4),
+                             mfma_frac=round(totals["algorithmic_flops"] / step_s / 1e12 / PEAK_BF16_TFLOPS, 4))
     if args.peaks:
         rec["calibration"] = measure_peaks(torch)
     if not args.no_cpu_baseline:
