@@ -148,37 +148,61 @@ __global__ void bn_fold_kernel(const float* gamma, const float* beta, const floa
 // (column slabs, row chunks).  Each block writes one ordered partial.
 // ---------------------------------------------------------------------------
 struct ColGrid {
-  int cvl;        // channel-vector lanes per block (power of two <= 32)
+  int cvl;        // channel-vector lanes per block (<= 32); 256 / cvl row lanes, the rest of the block idles
   int slabs;      // ceil(ncv / cvl)
   int chunks;     // row chunks (gridDim.y)
   long rows_per_chunk;
 };
 
 // in-block reduction of NV floats per thread over the row lanes.  Threads are numbered
-// row_lane * cvl + cv_lane, so the lanes of a wave that share a channel vector are cvl apart: a
-// butterfly (lane ^ cvl, ^ 2 cvl, ... ^ 32) adds them without leaving the registers, then the four
-// waves' sums meet in LDS and are added as (w0 + w1) + (w2 + w3).  The association is fixed, so
-// the result never depends on scheduling.  smem: at least 4 * cvl * NV floats.
+// row_lane * cvl + cv_lane (row lanes 0 .. 256/cvl - 1 take part).  The association is fixed in both
+// forms, so the result never depends on scheduling.  smem: at least 256 * NV floats.
+//  * cvl a power of two: the lanes of a wave that share a channel vector are cvl apart, so a butterfly
+//    (lane ^ cvl, ^ 2 cvl, ... ^ 32) adds them without leaving the registers; the four waves' sums then
+//    meet in LDS and are added as (w0 + w1) + (w2 + w3).
+//  * any other cvl (channel counts such as 48, 96, 144): every thread leaves its sums in LDS as
+//    [row_lane][cv_lane][NV]; thread o adds column o over the row lanes in order.
 template <int NV>
 __device__ __forceinline__ void block_col_reduce(float (&acc)[NV], float* smem, int cvl, int cv_lane,
                                                  int row_lane, float* out /*[NV]*/, bool& owner) {
   owner = row_lane == 0;
-  for (int off = cvl; off < 64; off <<= 1) {
+  if ((cvl & (cvl - 1)) == 0) {
+    for (int off = cvl; off < 64; off <<= 1) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) acc[k] += __shfl_xor(acc[k], off, 64);
+      for (int k = 0; k < NV; ++k) acc[k] += __shfl_xor(acc[k], off, 64);
+    }
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (lane < cvl) {
+      float* mine = smem + (wave * cvl + lane) * NV;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) mine[k] = acc[k];
+    }
+    __syncthreads();
+    if (owner) {   // wave 0, lane == cv_lane
+      const float* w0 = smem + cv_lane * NV;
+      const int ws = cvl * NV;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) out[k] = (w0[k] + w0[ws + k]) + (w0[2 * ws + k] + w0[3 * ws + k]);
+    }
+    __syncthreads();
+    return;
   }
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  if (lane < cvl) {
-    float* mine = smem + (wave * cvl + lane) * NV;
+  const int rl = 256 / cvl, nout = cvl * NV;
+  if (row_lane < rl) {
+    float* mine = smem + (row_lane * cvl + cv_lane) * NV;
 #pragma unroll
     for (int k = 0; k < NV; ++k) mine[k] = acc[k];
   }
   __syncthreads();
-  if (owner) {   // wave 0, lane == cv_lane
-    const float* w0 = smem + cv_lane * NV;
-    const int ws = cvl * NV;
+  for (int o = threadIdx.x; o < nout; o += 256) {
+    float sum = smem[o];
+    for (int r = 1; r < rl; ++r) sum += smem[r * nout + o];
+    smem[o] = sum;       // column o of row 0 is read by this thread only
+  }
+  __syncthreads();
+  if (owner) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) out[k] = (w0[k] + w0[ws + k]) + (w0[2 * ws + k] + w0[3 * ws + k]);
+    for (int k = 0; k < NV; ++k) out[k] = smem[cv_lane * NV + k];
   }
   __syncthreads();
 }
@@ -195,7 +219,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
   const int cv = blockIdx.x * g.cvl + cv_lane;
-  if (cv >= ncv) return;
+  if (cv >= ncv || row_lane >= rl) return;
   const long r0 = blockIdx.y * g.rows_per_chunk;
   const long r1 = min(M, r0 + g.rows_per_chunk);
   float mu[8], a[8], b[8];
@@ -240,7 +264,7 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, 
   float acc[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
-  if (cv < ncv) {
+  if (cv < ncv && row_lane < rl) {
     float piv[8];
     IO<T>::ld(y + (long)cv * 8, piv);
     long r = r0 + row_lane;
@@ -345,7 +369,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
   float acc[16];
 #pragma unroll
   for (int k = 0; k < 16; ++k) acc[k] = 0.f;
-  if (cv < ncv) {
+  if (cv < ncv && row_lane < rl) {
     float av[8], bv[8], mv[8], iv[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
@@ -418,7 +442,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
   const int cv = blockIdx.x * g.cvl + cv_lane;
-  if (cv >= ncv) return;
+  if (cv >= ncv || row_lane >= rl) return;
   const long r0 = blockIdx.y * g.rows_per_chunk;
   const long r1 = min(M, r0 + g.rows_per_chunk);
   float mu[8], a[8], b[8], is[8], c2[8], c3[8];
@@ -1392,7 +1416,7 @@ __global__ __launch_bounds__(256) void dw_wgrad_kernel(const T* __restrict__ dy,
   for (int a = 0; a < ROWS; ++a)
 #pragma unroll
     for (int t = 0; t < KMAX * 8; ++t) acc[a][t] = 0.f;
-  if (cv < ncv && r0 + row_lane < r1) {
+  if (cv < ncv && row_lane < rl && r0 + row_lane < r1) {
     // (n, p, q) of this thread's first row, then advanced by rl rows per step without divisions
     long pix = r0 + row_lane;
     int q = (int)(pix % Q); pix /= Q;

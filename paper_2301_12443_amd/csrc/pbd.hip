@@ -191,10 +191,11 @@ size_t tensor_bytes(const pbd_ctx* c, Shape s) {
 ColGrid col_grid(long M, int Cp, int rows_per_thread = 8, int max_blocks = 512) {
   ColGrid g;
   const int ncv = Cp / 8;
-  int cvl = 1;
-  while (cvl < ncv && cvl < 32) cvl *= 2;
-  g.cvl = cvl;
-  g.slabs = (ncv + cvl - 1) / cvl;
+  // as few column slabs as 32 lanes allow, then lanes = vectors per slab: no idle lanes for channel
+  // counts that are not powers of two (48, 96, 144, 576 ...), at most 256 % cvl idle threads per block
+  g.slabs = (ncv + 31) / 32;
+  g.cvl = (ncv + g.slabs - 1) / g.slabs;
+  const int cvl = g.cvl;
   const int rl = 256 / cvl;
   long chunks = (M + (long)rl * rows_per_thread - 1) / ((long)rl * rows_per_thread);
   const long cap = std::max(1, max_blocks / g.slabs);
