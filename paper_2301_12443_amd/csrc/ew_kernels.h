@@ -1219,6 +1219,7 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
   constexpr int IH = TH + K - 1, IW = TW + K - 1, NIN = WS + K - 1, pad = K / 2;
   constexpr int TOTAL = IH * IW * CVB, NLOAD = (TOTAL + 255) / 256;
   __shared__ __attribute__((aligned(16))) unsigned char tile[IH * IW * PIXB];
+  __shared__ __attribute__((aligned(16))) float wl[K * K * CVB * 8];   // the block's filters, unpacked once
   const int tid = threadIdx.x;
   int t = blockIdx.x;
   const int tw = t % tiles_w; t /= tiles_w;
@@ -1236,6 +1237,23 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
     const int h = h0 - pad + ih, ww = w0 - pad + iw;
     const bool ok = c < TOTAL && (unsigned)h < (unsigned)H && (unsigned)ww < (unsigned)W && cv0 + cvl < ncv;
     raw[i] = buffer_load16(xr, ok ? (unsigned)(((n * H + h) * W + ww) * ncv + cv0 + cvl) * 16u : kOutOfRange);
+  }
+  constexpr int NW = (K * K * CVB + 255) / 256;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    const int c = tid + i * 256;
+    if (c < K * K * CVB) {
+      const int tap = c / CVB, wcv = cv0 + c % CVB;
+      float f[8];
+      if (wcv < ncv) IO<bf16_t>::ld(w + ((long)tap * ncv + wcv) * 8, f);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = 0.f;
+      }
+      float* dstw = &wl[((FLIP ? K * K - 1 - tap : tap) * CVB + c % CVB) * 8];
+      *reinterpret_cast<float4*>(dstw) = make_float4(f[0], f[1], f[2], f[3]);
+      *reinterpret_cast<float4*>(dstw + 4) = make_float4(f[4], f[5], f[6], f[7]);
+    }
   }
 #pragma unroll
   for (int i = 0; i < NLOAD; ++i) {
@@ -1261,8 +1279,10 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
     float f[K][8];
 #pragma unroll
     for (int tt = 0; tt < K; ++tt) {
-      const int tap = FLIP ? (K - 1 - r) * K + (K - 1 - tt) : r * K + tt;
-      IO<bf16_t>::ld(w + ((long)tap * ncv + cv) * 8, f[tt]);
+      const float* wr = &wl[((r * K + tt) * CVB + cvl) * 8];
+      const float4 lo = *reinterpret_cast<const float4*>(wr), hi = *reinterpret_cast<const float4*>(wr + 4);
+      f[tt][0] = lo.x; f[tt][1] = lo.y; f[tt][2] = lo.z; f[tt][3] = lo.w;
+      f[tt][4] = hi.x; f[tt][5] = hi.y; f[tt][6] = hi.z; f[tt][7] = hi.w;
     }
 #pragma unroll
     for (int j = 0; j < NIN; ++j) {
