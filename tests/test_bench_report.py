@@ -1,0 +1,60 @@
+"""Host logic of the benchmark's report: which kernel class is reported, against which roofline."""
+import pytest
+
+import bench
+
+
+def _entry(name, ms, nbytes, flops=0.0):
+    return dict(name=name, ms=ms, bytes=nbytes, flops=flops, net=1, block=0, op=0)
+
+
+def test_bandwidth_bound_class_is_reported_against_hbm():
+    steps = 2
+    prof = []
+    for _ in range(steps):
+        prof += [_entry("bn_bwd_reduce", 0.020, 40e6)] * 3          # 60 us per step: the most time
+        prof += [_entry("igemm_fwd_128x128_store", 0.050, 10e6, 2e10)]
+    roof, classes, totals = bench.roofline_from_profile(prof, steps)
+    assert roof["kernel"] == "bn_bwd_reduce" and roof["bound"] == "hbm" and roof["unit"] == "GB/s"
+    assert roof["launches_per_step"] == roof["class_launches_per_step"] == 3
+    assert roof["avg_launch_us"] == pytest.approx(20.0)
+    assert roof["achieved"] == pytest.approx(40e6 / 20e-6 / 1e9)     # bytes of one launch over its duration
+    assert roof["frac"] == pytest.approx(roof["achieved"] / bench.PEAK_HBM_GBS, abs=1e-4)
+    assert classes["bn_bwd_reduce"]["ms_per_step"] == pytest.approx(0.060)
+    assert totals["launches"] == 4
+    assert totals["algorithmic_bytes"] == pytest.approx(3 * 40e6 + 10e6)
+    assert totals["algorithmic_flops"] == pytest.approx(2e10)
+    assert totals["kernel_ms"] == pytest.approx(0.110)
+
+
+def test_contraction_counts_against_mfma_only_above_the_ridge():
+    ridge = bench.PEAK_BF16_TFLOPS * 1e12 / (bench.PEAK_HBM_GBS * 1e9)          # flop per byte
+    hi = _entry("wgrad_128x128", 0.200, 100e6, 100e6 * ridge * 4)               # 3x3 layer: well above
+    lo = _entry("wgrad_128x128", 0.100, 400e6, 400e6 * ridge / 4)               # 1x1 layer: below
+    roof, _, _ = bench.roofline_from_profile([hi, hi, lo], 1)
+    assert roof["kernel"] == "wgrad_128x128" and roof["bound"] == "mfma" and roof["unit"] == "TFLOP/s"
+    assert (roof["launches_per_step"], roof["class_launches_per_step"]) == (2, 3)
+    assert roof["achieved"] == pytest.approx(hi["flops"] / 200e-6 / 1e12, rel=1e-3)
+    assert roof["peak"] == bench.PEAK_BF16_TFLOPS
+    # the same class with most of its time below the ridge is a bandwidth figure
+    roof, _, _ = bench.roofline_from_profile([hi, lo, lo, lo], 1)
+    assert roof["bound"] == "hbm" and roof["launches_per_step"] == 3
+    assert roof["achieved"] == pytest.approx(400e6 / 100e-6 / 1e9)
+
+
+def test_depthwise_counts_against_the_vector_alu_peak():
+    ridge = bench.PEAK_FP32_VALU_TFLOPS * 1e12 / (bench.PEAK_HBM_GBS * 1e9)
+    k7 = _entry("dw_fwd_tile_k7", 0.070, 100e6, 100e6 * ridge * 2.5)
+    k3 = _entry("dw_fwd_tile_k3", 0.030, 100e6, 100e6 * ridge * 0.4)
+    roof, _, _ = bench.roofline_from_profile([k7, k3], 1)
+    assert roof["kernel"] == "dw_fwd_tile_k7" and roof["bound"] == "alu" and roof["peak"] == bench.PEAK_FP32_VALU_TFLOPS
+    roof, _, _ = bench.roofline_from_profile([k3], 1)
+    assert roof["bound"] == "hbm"
+
+
+def test_more_than_one_gpu_is_refused(monkeypatch, capsys):
+    monkeypatch.setattr("sys.argv", ["bench.py", "--gpus", "2"])
+    with pytest.raises(SystemExit) as e:
+        bench.main()
+    assert e.value.code == 2
+    assert "single-GPU" in capsys.readouterr().err
