@@ -1,4 +1,6 @@
-"""Descriptor pins: Table I's teacher columns and textbook totals."""
+"""Descriptor pins: Table I's teacher columns (tests/golden/table1_teachers.txt) and textbook totals."""
+import os
+
 import numpy as np
 
 from paper_2301_12443_amd import workloads as W
@@ -9,11 +11,22 @@ def _totals(blocks, in_shape):
     return sum(d + w for d, w, _ in r), sum(p for *_, p in r)
 
 
+def _table1(model, dataset):
+    """(params in millions, flops, unit multiplier, operations per multiply-accumulate) of one printed row."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "table1_teachers.txt")
+    for line in open(path):
+        f = line.split()
+        if f and not line.startswith("#") and f[0] == model and f[1] == dataset:
+            return float(f[2]), float(f[3]), {"M": 1e6, "B": 1e9}[f[4]], int(f[5])
+    raise KeyError((model, dataset))
+
+
 def test_vgg16_cifar_matches_table1():
     wl = W.vgg16_dsconv()
     macs, params = _totals(wl.teacher, wl.in_shape)
-    assert round(2 * macs / 1e9, 2) == 0.63                 # Table I counts 2 x MACs: 0.63 B
-    assert round((params + 512 * 10 + 10) / 1e6, 2) == 14.72   # + FC-10 head: 14.72 M
+    p_m, flops, unit, per_mac = _table1("VGG-16", "Cifar-10")
+    assert round(per_mac * macs / unit, 2) == flops            # 0.63 B
+    assert round((params + 512 * 10 + 10) / 1e6, 2) == p_m     # + FC-10 head: 14.72 M
     assert W.activation_shapes(wl) == [(3, 32, 32), (64, 16, 16), (128, 8, 8), (256, 4, 4), (512, 1, 1)]
 
 
@@ -22,8 +35,9 @@ def test_mobilenetv2_imagenet_matches_table1():
     macs, params = _totals(wl.teacher, wl.in_shape)
     head_macs = 320 * 1280 * 49 + 1280 * 1000                # 1x1 -> 1280 head at 7x7, FC-1000
     head_params = 320 * 1280 + 2 * 1280 + 1280 * 1000 + 1000
-    assert abs((macs + head_macs) / 1e6 - 300.77) < 0.05    # Table I: 300.77 M (MACs)
-    assert round((params + head_params) / 1e6, 2) == 3.50    # Table I: 3.50 M
+    p_m, flops, unit, per_mac = _table1("MobileNetV2", "ImageNet")
+    assert abs(per_mac * (macs + head_macs) / unit - flops) < 0.05    # 300.77 M
+    assert round((params + head_params) / 1e6, 2) == p_m              # 3.50 M
     macs_b = [d + w for d, w, _ in W.macs_and_params(wl.student, wl.in_shape)]
     assert macs_b[0] == max(macs_b)                          # Sec. VII-A: block 0 is the heaviest at 224^2
     sizes = [int(np.prod(s)) for s in W.activation_shapes(wl)[1:]]
