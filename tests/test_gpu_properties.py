@@ -94,6 +94,32 @@ def test_teacher_without_relaying_gives_the_same_step():
         b.student_step(2, wl.lr)
 
 
+@pytest.mark.parametrize("name", ["mbv2_mbconv_k5e4", "resnet50_x1.5"])
+def test_full_size_teacher_relay_on_sampled_images(name):
+    """The relayed activations at the full batch and image size of configs 3-5 (config 4 shares config 3's
+    teacher), checked on sampled images: the frozen teacher uses its running statistics (Sec. II-A), so
+    image n of every A_i depends on image n of the input alone and the oracle can compute it at batch 1.
+    Tolerances as for the reduced-batch runs: 2e-2 against the oracle with bf16 storage, 4e-2 against
+    plain fp64 (storage noise of a 50-layer chain)."""
+    import torch
+    from helpers import make_oracle, max_rel
+    wl = W.CONFIGS[name]()
+    x = W.make_input(wl)
+    d = parity.make_distiller(wl)
+    d.distill_step(torch.from_numpy(x).cuda(), wl.lr)      # the launch configuration the benchmark times
+    d.sync()
+    assert d.uses_graph()
+    got = [d.read_act(i) for i in range(wl.B + 1)]
+    o16, o64 = make_oracle(wl, batch=1, storage="bf16"), make_oracle(wl, batch=1)
+    for n in (0, wl.batch // 2 + 1, wl.batch - 1)[:3 if name.startswith("mbv2") else 2]:
+        print(f"[{name}] oracle on image {n}", flush=True)
+        a16, a64 = o16.teacher_relay(x[n:n + 1]), o64.teacher_relay(x[n:n + 1])
+        for i in range(wl.B + 1):
+            g = got[i][n].ravel()
+            assert max_rel(g, a16[i]) < 2e-2, (n, i)
+            assert max_rel(g, a64[i]) < 4e-2, (n, i)
+
+
 def test_relay_views_and_shared_input():
     """S_i reads the very buffer T_i read: the view of A_{i-1} handed out by the relay."""
     import torch
