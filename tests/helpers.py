@@ -133,3 +133,15 @@ def twin_candidates(n=3, act=W.ACT_NONE):
     v = s.cba(m, 8, 3)
     s.add(m, v, act=act)
     return W.Workload("twins", 3, (8, 6, 6), [t], [s], "f32", lr=0.05)
+
+
+def skip_mix():
+    """A mix whose first candidate is the block's input itself, then a mix over a single candidate."""
+    t, s = W.Block(), W.Block()
+    t.cba(0, 8, 3)
+    a = s.cba(0, 8, 3, act=W.ACT_NONE)
+    v = s.cba(0, 16, 1); b = s.cba(v, 8, 3, act=W.ACT_NONE)
+    m = s.mix([0, a, b], [0.2, 0.5, 0.3])
+    c = s.cba(m, 8, 3)
+    s.mix([c], [1.0])
+    return W.Workload("skip_mix", 4, (8, 6, 6), [t], [s], "f32", lr=0.05)

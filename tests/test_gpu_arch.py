@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import parity
-from helpers import make_oracle, max_rel, mix_ops, supernet, twin_candidates
+from helpers import make_oracle, max_rel, mix_ops, skip_mix, supernet, twin_candidates
 from oracle import pbd_oracle as orc
 from paper_2301_12443_amd import pbd, workloads as W
 
@@ -23,6 +23,12 @@ LR_ALPHA = 0.3
 def _weights(d, wl, b):
     return {k: d.read_tensor(pbd.PBD_PARAM, 1, b, k[0], k[1], shape).copy()
             for k, shape in W.param_shapes(wl, W.NET_STUDENT, b).items() if k[1] <= W.P_BETA}
+
+
+def _err(got, ref, den):
+    """max|got - ref| over den; the absolute error where the reference has no scale (den == 0)."""
+    e = float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)))
+    return e / den if den > 0 else e
 
 
 def _two_round_steps(wl, precision, steps, alpha0=None, storage=None, kink_floor=0.0, order=None, noise=False):
@@ -65,14 +71,14 @@ def _two_round_steps(wl, precision, steps, alpha0=None, storage=None, kink_floor
             for j, n in mix_ops(wl, b):
                 ref = o.get_alpha(b, j, n, orc.ALPHA_GRAD)
                 den = np.max(np.abs(ref))
-                errs[f"{tag}.op{j}.dalpha"] = float(np.max(np.abs(d.read_alpha(b, j, n, pbd.PBD_GRAD) - ref)) / den)
+                errs[f"{tag}.op{j}.dalpha"] = _err(d.read_alpha(b, j, n, pbd.PBD_GRAD), ref, den)
                 if o64 is not None:
-                    errs[f"{tag}.op{j}.dalpha.noise"] = float(np.max(np.abs(o64.get_alpha(b, j, n, orc.ALPHA_GRAD) - ref)) / den)
+                    errs[f"{tag}.op{j}.dalpha.noise"] = _err(o64.get_alpha(b, j, n, orc.ALPHA_GRAD), ref, den)
                 refm = o.get_alpha(b, j, n, orc.ALPHA_MOMENTUM)
-                errs[f"{tag}.op{j}.alpha_mom"] = float(np.max(np.abs(d.read_alpha(b, j, n, pbd.PBD_MOMENTUM) - refm)) / np.max(np.abs(refm)))
+                errs[f"{tag}.op{j}.alpha_mom"] = _err(d.read_alpha(b, j, n, pbd.PBD_MOMENTUM), refm, np.max(np.abs(refm)))
                 refa = o.get_alpha(b, j, n)
                 # alpha moves by lr x momentum: measured against that step (alpha itself may be near 0)
-                errs[f"{tag}.op{j}.alpha"] = float(np.max(np.abs(d.read_alpha(b, j, n) - refa)) /
+                errs[f"{tag}.op{j}.alpha"] = _err(d.read_alpha(b, j, n), refa,
                                                   max(np.max(np.abs(refa)), LR_ALPHA * np.max(np.abs(refm))))
                 errs[f"{tag}.op{j}.p"] = max_rel(d.read_alpha(b, j, n, pbd.PBD_PROB), o.get_alpha(b, j, n, orc.ALPHA_PROB))
             after = _weights(d, wl, b)
@@ -121,6 +127,25 @@ def test_f32_mix_widths_and_rectified_residual(n):
     rng = np.random.default_rng(n)
     alpha0 = {(0, j): rng.normal(0.0, 0.5, m).astype(np.float32) for j, m in mix_ops(wl)}
     _assert_all(_two_round_steps(wl, "f32", 2, alpha0=alpha0, kink_floor=KINK_FLOOR), TOL_F32)
+
+
+def test_f32_identity_candidate_and_single_candidate():
+    """A mix whose first candidate is the block's input itself (a skip connection competing with
+    convolutions: its inner product enters the softmax gradient, but A_{i-1} gets no gradient), followed
+    by a mix over a single candidate (p = 1 whatever alpha is: its gradient must vanish)."""
+    wl = skip_mix()
+    (j3, n3), (j1, n1) = mix_ops(wl)
+    assert (n3, n1) == (3, 1)
+    errs = _two_round_steps(wl, "f32", 2, kink_floor=KINK_FLOOR)
+    _assert_all(errs, TOL_F32)       # (the single-candidate mix: 0 against 0, absolute)
+    import torch
+    d = parity.make_distiller(wl, wl.batch, "f32")
+    d.teacher_relay(torch.from_numpy(W.make_input(wl)).cuda())
+    d.arch_step(1, LR_ALPHA)
+    d.sync()
+    assert np.all(d.read_alpha(0, j1, 1, pbd.PBD_GRAD) == 0.0) and np.all(d.read_alpha(0, j1, 1, pbd.PBD_PROB) == 1.0)
+    assert np.all(d.read_alpha(0, j1, 1) == 0.0) and np.all(d.read_alpha(0, j1, 1, pbd.PBD_MOMENTUM) == 0.0)
+    assert np.max(np.abs(d.read_alpha(0, j3, 3, pbd.PBD_GRAD))) > 0
 
 
 def test_bf16_two_round_step():

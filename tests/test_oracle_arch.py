@@ -5,14 +5,14 @@ import pytest
 import torch
 
 import torch_ref
-from helpers import make_oracle, max_rel, mix_ops, supernet, twin_candidates
+from helpers import make_oracle, max_rel, mix_ops, skip_mix, supernet, twin_candidates
 from oracle import pbd_oracle as orc
 from paper_2301_12443_amd import workloads as W
 
 
 def test_alpha_gradient_matches_finite_differences():
     """Central differences of loss_i over every architecture parameter."""
-    for wl in (supernet(), twin_candidates(4, W.ACT_RELU)):
+    for wl in (supernet(), twin_candidates(4, W.ACT_RELU), skip_mix()):
         o = make_oracle(wl)
         rng = np.random.default_rng(3)
         acts = o.teacher_relay(W.make_input(wl))
@@ -22,7 +22,7 @@ def test_alpha_gradient_matches_finite_differences():
         o.student_step(1, acts[0], acts[1], 0.0, orc.MODE_ARCH_GRADS)
         for j, a in alphas.items():
             g = o.get_alpha(0, j, a.size, orc.ALPHA_GRAD)
-            assert np.max(np.abs(g)) > 1e-6                       # the check below is not vacuous
+            assert a.size == 1 or np.max(np.abs(g)) > 1e-6      # the check below is not vacuous
             for k in range(a.size):
                 errs = []
                 for h in (1e-5, 1e-6, 1e-7):
