@@ -178,8 +178,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   constexpr int A_LOADS = BM / RPP;
   constexpr int B_LOADS = (BN + RPP - 1) / RPP;  // 16-byte chunks of the weight tile per thread
   static_assert(!(BK == 64) || UNI, "the 64-wide K step needs uniform taps");
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * PITCH];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * PITCH];
+  // one LDS block: the two stages of both operand tiles during the reduction, then the output tile on
+  // its way to coalesced stores
+  __shared__ __attribute__((aligned(16))) bf16_t smem[2 * (BM + BN) * PITCH];
+  bf16_t (*As)[BM * PITCH] = reinterpret_cast<bf16_t (*)[BM * PITCH]>(smem);
+  bf16_t (*Bs)[BN * PITCH] = reinterpret_cast<bf16_t (*)[BN * PITCH]>(smem + 2 * BM * PITCH);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
@@ -367,10 +370,54 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     iteration(kt, S0{});
     if (kt + 1 < nk) iteration(kt + 1, S1{});
   }
-  if (kIdleWaves && wn > 0) return;
-
   // epilogue: lane holds pixel (lane%32) and channels 8*(v/4) + 4*(lane/32) + v%4 of each 32x32 tile
   const bool full = m0 + BM <= g.M && n0 + BN <= g.NC;
+  if constexpr ((EPI == EPI_STORE || EPI == EPI_AFFINE_ACT) && !kIdleWaves) {
+    // bf16 results go through LDS (the operand tiles are dead after the last barrier of the loop) and
+    // leave as 16-byte chunks, consecutive lanes on consecutive chunks of a row: whole cache lines
+    // instead of 32 rows x 16 bytes per store instruction
+    constexpr int OP = BN * 2 + 16;                  // bytes per staged row; the pad spreads rows over banks
+    static_assert(BM * OP <= 2 * (BM + BN) * PITCH * 2, "the output tile must fit in the operand tiles' LDS");
+    unsigned char* stage = reinterpret_cast<unsigned char*>(smem);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int lrow = wm * TM * 32 + i * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lcol = wn * TN * 32 + j * 32 + 8 * q + 4 * (lane >> 5);
+          float o[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
+          if (EPI == EPI_AFFINE_ACT) {
+            const int col = min(n0 + lcol, g.NC - 4);   // columns past NC are never stored
+            const float4 ea = *reinterpret_cast<const float4*>(ep_a + col);
+            const float4 eb = *reinterpret_cast<const float4*>(ep_b + col);
+            o[0] = apply_act(fmaf(o[0], ea.x, eb.x), act); o[1] = apply_act(fmaf(o[1], ea.y, eb.y), act);
+            o[2] = apply_act(fmaf(o[2], ea.z, eb.z), act); o[3] = apply_act(fmaf(o[3], ea.w, eb.w), act);
+          }
+          uint2 pk;
+          pk.x = pack_bf2(o[0], o[1]);
+          pk.y = pack_bf2(o[2], o[3]);
+          *reinterpret_cast<uint2*>(stage + lrow * OP + lcol * 2) = pk;
+        }
+    }
+    __syncthreads();
+    constexpr int CPROW = BN / 8;                    // 16-byte chunks per row
+    constexpr int NCHUNK = BM * CPROW;
+    static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
+#pragma unroll
+    for (int k = 0; k < NCHUNK / 256; ++k) {
+      const int cidx = tid + k * 256;
+      const int lrow = cidx / CPROW, c16 = cidx % CPROW;
+      const int row = m0 + lrow, col = n0 + c16 * 8;
+      if (full || (row < g.M && col < g.NC))         // NC % 8 == 0: a chunk is in or out as a whole
+        *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = *reinterpret_cast<const uint4*>(stage + lrow * OP + c16 * 16);
+    }
+    return;
+  }
+  if (kIdleWaves && wn > 0) return;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int row = m0 + wm * TM * 32 + i * 32 + (lane & 31);
