@@ -417,6 +417,47 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     }
     return;
   }
+  // accumulating launches add in fp32 before the one rounding: the tile is staged as fp32 where the
+  // operand tiles' LDS has room for it (every tile shape but 256 x 128 and the 32-wide K step's 128 x 128)
+  constexpr int OPF = BN * 4 + 16;
+  if constexpr (EPI == EPI_ACCUM && !kIdleWaves && BM * OPF <= 2 * (BM + BN) * PITCH * 2) {
+    unsigned char* stage = reinterpret_cast<unsigned char*>(smem);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int lrow = wm * TM * 32 + i * 32 + (lane & 31);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int lcol = wn * TN * 32 + j * 32 + 8 * q + 4 * (lane >> 5);
+          *reinterpret_cast<float4*>(stage + lrow * OPF + lcol * 4) =
+              make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+    }
+    __syncthreads();
+    constexpr int CPROW = BN / 8;
+    constexpr int NCHUNK = BM * CPROW;
+    static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
+#pragma unroll
+    for (int k = 0; k < NCHUNK / 256; ++k) {
+      const int cidx = tid + k * 256;
+      const int lrow = cidx / CPROW, c16 = cidx % CPROW;
+      const int row = m0 + lrow, col = n0 + c16 * 8;
+      if (full || (row < g.M && col < g.NC)) {
+        bf16_t* dst = Out + (size_t)row * g.NC + col;
+        const float4 lo = *reinterpret_cast<const float4*>(stage + lrow * OPF + c16 * 32);
+        const float4 hi = *reinterpret_cast<const float4*>(stage + lrow * OPF + c16 * 32 + 16);
+        const uint4 old = *reinterpret_cast<const uint4*>(dst);
+        uint4 pk;
+        pk.x = pack_bf2(lo.x + bf_lo(old.x), lo.y + bf_hi(old.x));
+        pk.y = pack_bf2(lo.z + bf_lo(old.y), lo.w + bf_hi(old.y));
+        pk.z = pack_bf2(hi.x + bf_lo(old.z), hi.y + bf_hi(old.z));
+        pk.w = pack_bf2(hi.z + bf_lo(old.w), hi.w + bf_hi(old.w));
+        *reinterpret_cast<uint4*>(dst) = pk;
+      }
+    }
+    return;
+  }
   if (kIdleWaves && wn > 0) return;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
