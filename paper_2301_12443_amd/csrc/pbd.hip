@@ -487,7 +487,10 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
-    const IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred, g.CA);
+    IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred, g.CA);
+    // an accumulating 256-row tile cannot stage its fp32 results in LDS: 128 rows store whole cache lines
+    if (epi == EPI_ACCUM && cfg.BM == 256) cfg.BM = 128;
+    if (epi == EPI_ACCUM && cfg.BK == 32 && cfg.BM == 128 && cfg.BN == 128) cfg.BN = 64;   // (128 x 128 needs the 64-wide K step's LDS)
     const int nk = (g.Kred + cfg.BK - 1) / cfg.BK;
     g.ksteps_per_split = (nk + cfg.splits - 1) / cfg.splits;
     g.tiles_m = (g.M + cfg.BM - 1) / cfg.BM;
