@@ -138,6 +138,10 @@ struct IgemmArgs {
   int ksteps_per_split;  // reduction steps of IG_BK handled by one K slice (split-K)
   unsigned a_bytes, b_bytes;  // sizes of the A tensor and of the weight matrix
   int tiles_m, tiles_n, splits;   // the 1-D grid holds tiles_m * tiles_n * splits workgroups
+  // residual join fused into the store (EPI_STORE / EPI_AFFINE_ACT through LDS): out = act(result + res),
+  // the result rounded to bf16 first, exactly as a stored tensor read back by a separate add would be
+  const void* res;
+  int res_act;
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
@@ -412,8 +416,17 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
       const int cidx = tid + k * 256;
       const int lrow = cidx / CPROW, c16 = cidx % CPROW;
       const int row = m0 + lrow, col = n0 + c16 * 8;
-      if (full || (row < g.M && col < g.NC))         // NC % 8 == 0: a chunk is in or out as a whole
-        *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = *reinterpret_cast<const uint4*>(stage + lrow * OP + c16 * 16);
+      if (full || (row < g.M && col < g.NC)) {       // NC % 8 == 0: a chunk is in or out as a whole
+        uint4 v = *reinterpret_cast<const uint4*>(stage + lrow * OP + c16 * 16);
+        if (g.res) {
+          const uint4 rv = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.res) + (size_t)row * g.NC + col);
+          v.x = pack_bf2(apply_act(bf_lo(v.x) + bf_lo(rv.x), g.res_act), apply_act(bf_hi(v.x) + bf_hi(rv.x), g.res_act));
+          v.y = pack_bf2(apply_act(bf_lo(v.y) + bf_lo(rv.y), g.res_act), apply_act(bf_hi(v.y) + bf_hi(rv.y), g.res_act));
+          v.z = pack_bf2(apply_act(bf_lo(v.z) + bf_lo(rv.z), g.res_act), apply_act(bf_hi(v.z) + bf_hi(rv.z), g.res_act));
+          v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(rv.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(rv.w), g.res_act));
+        }
+        *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = v;
+      }
     }
     return;
   }

@@ -465,15 +465,44 @@ template <class T> struct Exec {
   static bool short_column(long M) { return M <= (long)kSmallThreads * kSmallRows; }
 
   // ---- convolution forward (dense) --------------------------------------
-  void conv_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act) {
+  // Can a two-input add that is the only reader of this convolution's output ride in its store?  Only the
+  // MFMA kernel's LDS-staged store does it: no split-K, and not the 64 x 32 tile (whose idle waves skip it).
+  bool fuses_residual(const OpPlan& op) const {
+    if (!mfma() || op.dw) return false;
+    const IgemmCfg cfg = igemm_cfg((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
+    return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);
+  }
+  // For op j of a block: the index of an add op that (a) is the only reader of j's output, (b) has two
+  // inputs, the other one computed before j, and (c) follows a layer without activation; else -1.
+  static int residual_reader(const BlockPlan& bp, int j) {
+    const OpD& o = bp.ops[j].d;
+    if (o.type != OP_CBA || o.act != ACT_NONE) return -1;
+    int reader = -1, uses = 0;
+    for (int k = j + 1; k < (int)bp.ops.size(); ++k) {
+      const OpD& q = bp.ops[k].d;
+      const int nin = q.type == OP_ADD || q.type == OP_MIX ? q.nin : 1;
+      for (int i = 0; i < nin; ++i)
+        if (q.in[i] == j + 1) { ++uses; reader = k; }
+    }
+    if (uses != 1 || j + 2 == (int)bp.shapes.size()) return -1;      // (a block's last value is read by the loss)
+    const OpD& q = bp.ops[reader].d;
+    if (q.type != OP_ADD || q.nin != 2) return -1;
+    const int other = q.in[0] == j + 1 ? q.in[1] : q.in[0];
+    return other <= j ? reader : -1;
+  }
+  // res (optional): a residual join fused into the store, y = res_act(conv result + res); only where
+  // fuses_residual(op) holds
+  void conv_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act,
+                const T* res = nullptr, int res_act = 0) {
     const int N = c->o.batch;
     const double flops = 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k * op.in.c;
-    const double bytes = bytes_of(op.in) + bytes_of(op.out) + (double)op.wn * sizeof(T);
+    const double bytes = bytes_of(op.in) + bytes_of(op.out) * (res ? 2 : 1) + (double)op.wn * sizeof(T);
     if (mfma()) {
       if constexpr (sizeof(T) == 2) {
         IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                     op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0,
                     (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2), (unsigned)(op.wn * 2)};
+        g.res = res; g.res_act = res_act;
         launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE,
                         bytes, flops);
       }
@@ -735,15 +764,23 @@ template <class T> struct Exec {
       if (v + 1 == (int)bp.shapes.size()) return relay(b + 1);
       return ws(c->r_tscr + bp.val[v]);
     };
+    std::vector<char> fused(bp.ops.size(), 0);      // adds that rode in their producer's store
     for (size_t j = 0; j < bp.ops.size(); ++j) {
       const OpPlan& op = bp.ops[j];
       opi = (int)j;
+      if (fused[j]) continue;
       T* out = value((int)j + 1);
       const T* x = value(op.d.in[0]);
       if (op.d.type == OP_CBA) {
         const T* w = ws(op.t_w);
+        const int rd = residual_reader(bp, (int)j);
         if (op.dw) dw_fwd(op, x, w, out, wsf(op.t_a), wsf(op.t_b), op.d.act);
-        else conv_fwd(op, x, w, out, wsf(op.t_a), wsf(op.t_b), op.d.act);
+        else if (rd >= 0 && fuses_residual(op)) {
+          const OpD& q = bp.ops[rd].d;
+          conv_fwd(op, x, w, value(rd + 1), wsf(op.t_a), wsf(op.t_b), op.d.act,
+                   value(q.in[0] == (int)j + 1 ? q.in[1] : q.in[0]), q.act);
+          fused[rd] = 1;
+        } else conv_fwd(op, x, w, out, wsf(op.t_a), wsf(op.t_b), op.d.act);
       } else if (op.d.type == OP_POOL) {
         pool_fwd(op, x, out, nullptr);
       } else {
