@@ -122,7 +122,9 @@ int pbd_read_act(pbd_ctx* ctx, int32_t i, float* host, size_t n);
 /* Copy value v of student block b (0 = its input, j+1 = output of op j) as saved by
  * the last step of that block, float32 NCHW.  When the blocks' scratch does not fit side by
  * side in the workspace they share one region and the values are valid only until another
- * block is stepped (PBD_ESTATE afterwards).  Testing aid; waits. */
+ * block is stepped (PBD_ESTATE afterwards).  The output of a layer without activation whose only reader is
+ * a two-input add is never written (the add is fused into the layer's normalisation pass; PBD_ESTATE);
+ * read the add's output instead.  Testing aid; waits. */
 int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
 
 /* Teacher relay (Algorithm 1, load + T.forward; Sec. IV-A, Sec. VII-A).  x_dev:

@@ -209,13 +209,20 @@ __device__ __forceinline__ void block_col_reduce(float (&acc)[NV], float* smem, 
 
 // training-mode BN + activation:  z = act((y - mean) * (gamma*invstd) + beta).
 // Column-grid launch: a thread keeps its 8 channels' coefficients in registers and streams rows.
+// what a value reads back as after it was stored in T
+template <class T> __device__ __forceinline__ float as_stored(float v);
+template <> __device__ __forceinline__ float as_stored<float>(float v) { return v; }
+template <> __device__ __forceinline__ float as_stored<bf16_t>(float v) { return bf_lo(pack_bf2(v, 0.f)); }
+
+// res (optional): a residual add fused into the pass, z = res_act(stored(act(bn(y))) + res): the same
+// numbers as storing the normalised tensor and adding in a second kernel, without that tensor
 template <class T>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, T* __restrict__ z,
                                                        const float* __restrict__ mean,
                                                        const float* __restrict__ invstd,
                                                        const float* __restrict__ gamma,
                                                        const float* __restrict__ beta, long M, int Cp,
-                                                       int act, ColGrid g) {
+                                                       int act, ColGrid g, const T* __restrict__ res, int res_act) {
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
   const int cv = blockIdx.x * g.cvl + cv_lane;
@@ -237,6 +244,12 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
     for (int u = 0; u < 4; ++u) {
 #pragma unroll
       for (int k = 0; k < 8; ++k) v[u][k] = apply_act(fmaf(v[u][k] - mu[k], a[k], b[k]), act);
+      if (res) {
+        float s[8];
+        IO<T>::ld(res + ((r + u * rl) * ncv + cv) * 8, s);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[u][k] = apply_act(as_stored<T>(v[u][k]) + s[k], res_act);
+      }
       IO<T>::st(z + ((r + u * rl) * ncv + cv) * 8, v[u]);
     }
   }
@@ -245,6 +258,12 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
     IO<T>::ld(y + (r * ncv + cv) * 8, v);
 #pragma unroll
     for (int k = 0; k < 8; ++k) v[k] = apply_act(fmaf(v[k] - mu[k], a[k], b[k]), act);
+    if (res) {
+      float s[8];
+      IO<T>::ld(res + (r * ncv + cv) * 8, s);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = apply_act(as_stored<T>(v[k]) + s[k], res_act);
+    }
     IO<T>::st(z + (r * ncv + cv) * 8, v);
   }
 }

@@ -448,6 +448,27 @@ inline void launch(pbd_ctx* c, void (*kern)(KA...), dim3 grid, dim3 block, size_
   }(std::forward<A>(a)...);
 }
 
+// For op j of a block: the index of an add op that (a) is the only reader of j's output, (b) has two
+// inputs, the other one computed before j, and (c) follows a layer without activation; else -1.
+int residual_reader(const BlockPlan& bp, int j) {
+  const OpD& o = bp.ops[j].d;
+  if (o.type != OP_CBA || o.act != ACT_NONE) return -1;
+  int reader = -1, uses = 0;
+  for (int k = j + 1; k < (int)bp.ops.size(); ++k) {
+    const OpD& q = bp.ops[k].d;
+    const int nin = q.type == OP_ADD || q.type == OP_MIX ? q.nin : 1;
+    for (int i = 0; i < nin; ++i)
+      if (q.in[i] == j + 1) { ++uses; reader = k; }
+  }
+  if (uses != 1 || j + 2 == (int)bp.shapes.size()) return -1;      // (a block's last value is read by the loss)
+  const OpD& q = bp.ops[reader].d;
+  if (q.type != OP_ADD || q.nin != 2) return -1;
+  const int other = q.in[0] == j + 1 ? q.in[1] : q.in[0];
+  return other <= j ? reader : -1;
+}
+// few enough rows for the whole-column BN kernels (one block per 8-channel slab)
+inline bool short_column(long M) { return M <= (long)kSmallThreads * kSmallRows; }
+
 template <class T> struct Exec {
   pbd_ctx* c;
   hipStream_t st;
@@ -461,8 +482,6 @@ template <class T> struct Exec {
   float* red() const { return wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
-  // few enough rows for the whole-column kernels (one block per 8-channel slab)
-  static bool short_column(long M) { return M <= (long)kSmallThreads * kSmallRows; }
 
   // ---- convolution forward (dense) --------------------------------------
   // Can a two-input add that is the only reader of this convolution's output ride in its store?  Only the
@@ -471,24 +490,6 @@ template <class T> struct Exec {
     if (!mfma() || op.dw) return false;
     const IgemmCfg cfg = igemm_cfg((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
     return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);
-  }
-  // For op j of a block: the index of an add op that (a) is the only reader of j's output, (b) has two
-  // inputs, the other one computed before j, and (c) follows a layer without activation; else -1.
-  static int residual_reader(const BlockPlan& bp, int j) {
-    const OpD& o = bp.ops[j].d;
-    if (o.type != OP_CBA || o.act != ACT_NONE) return -1;
-    int reader = -1, uses = 0;
-    for (int k = j + 1; k < (int)bp.ops.size(); ++k) {
-      const OpD& q = bp.ops[k].d;
-      const int nin = q.type == OP_ADD || q.type == OP_MIX ? q.nin : 1;
-      for (int i = 0; i < nin; ++i)
-        if (q.in[i] == j + 1) { ++uses; reader = k; }
-    }
-    if (uses != 1 || j + 2 == (int)bp.shapes.size()) return -1;      // (a block's last value is read by the loss)
-    const OpD& q = bp.ops[reader].d;
-    if (q.type != OP_ADD || q.nin != 2) return -1;
-    const int other = q.in[0] == j + 1 ? q.in[1] : q.in[0];
-    return other <= j ? reader : -1;
   }
   // res (optional): a residual join fused into the store, y = res_act(conv result + res); only where
   // fuses_residual(op) holds
@@ -894,9 +895,11 @@ template <class T> struct Exec {
     auto mix_state = [&](const OpPlan& op) -> float* { return wsf(bp.mix) + (size_t)op.mix_slot * kMixState; };
 
     // ---- forward ----------------------------------------------------------
+    std::vector<char> fused(bp.ops.size(), 0);      // adds that rode in their producer's normalisation pass
     for (size_t j = 0; j < bp.ops.size(); ++j) {
       const OpPlan& op = bp.ops[j];
       opi = (int)j;
+      if (fused[j]) continue;
       T* z = value((int)j + 1);
       const T* x = value(op.d.in[0]);
       if (op.d.type == OP_CBA) {
@@ -920,10 +923,22 @@ template <class T> struct Exec {
               wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
           {
             const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);   // elementwise pass: many short workgroups
-            ProfScope ps(c, "bn_apply", 2 * bytes_of(op.out), 0, net, blk, opi);
+            // a residual add that only reads this layer's output rides along: the normalised tensor itself
+            // is never written (the backward pass needs y and the sum, not it)
+            const int rd = residual_reader(bp, (int)j);
+            const T* res = nullptr;
+            int res_act = 0;
+            if (rd >= 0) {
+              const OpD& q = bp.ops[rd].d;
+              res = value(q.in[0] == (int)j + 1 ? q.in[1] : q.in[0]);
+              res_act = q.act;
+              z = value(rd + 1);
+              fused[rd] = 1;
+            }
+            ProfScope ps(c, res ? "bn_apply_add" : "bn_apply", (res ? 3 : 2) * bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st, y, z, wsf(op.s_mean), wsf(op.s_invstd),
                                                                        master + op.e_gamma, master + op.e_beta, M,
-                                                                       op.cout_p, op.d.act, ga);
+                                                                       op.cout_p, op.d.act, ga, res, res_act);
           }
         }
       } else if (op.d.type == OP_POOL) {
@@ -1498,6 +1513,8 @@ int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
   if (!bp.stepped) return fail(c, PBD_ESTATE, "block %d holds no saved values (not stepped, or scratch reused)", b);
   const Shape s = bp.shapes[v];
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
+  if (v > 0 && !short_column((long)c->o.batch * s.h * s.w) && residual_reader(bp, v - 1) >= 0)
+    return fail(c, PBD_ESTATE, "value %d of block %d is not kept: the residual add that reads it is fused into its normalisation", v, b);
   const char* dev = v == 0 ? c->ws + c->r_relay + c->act_off[b] : c->ws + bp.scr_off + bp.val[v];
   return download_act(c, dev, s, host);
 }
