@@ -142,6 +142,9 @@ struct IgemmArgs {
   // the result rounded to bf16 first, exactly as a stored tensor read back by a separate add would be
   const void* res;
   int res_act;
+  // batch-norm statistics of the stored result from the same pass (EPI_STORE): per row tile and channel the
+  // sums of y and y^2 over the tile's rows, stats[tile_m][2][NC] (fp32; summed further in double)
+  float* stats;
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel
@@ -411,6 +414,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     constexpr int CPROW = BN / 8;                    // 16-byte chunks per row
     constexpr int NCHUNK = BM * CPROW;
     static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
+    static_assert(256 % CPROW == 0, "a thread keeps its chunk column over the rows it stores");
+    float s1[8], s2[8];                              // column sums of this thread's chunks (g.stats)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s1[e] = s2[e] = 0.f;
 #pragma unroll
     for (int k = 0; k < NCHUNK / 256; ++k) {
       const int cidx = tid + k * 256;
@@ -418,6 +425,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
       const int row = m0 + lrow, col = n0 + c16 * 8;
       if (full || (row < g.M && col < g.NC)) {       // NC % 8 == 0: a chunk is in or out as a whole
         uint4 v = *reinterpret_cast<const uint4*>(stage + lrow * OP + c16 * 16);
+        if (EPI == EPI_STORE && g.stats) {
+          const float f[8] = {bf_lo(v.x), bf_hi(v.x), bf_lo(v.y), bf_hi(v.y), bf_lo(v.z), bf_hi(v.z), bf_lo(v.w), bf_hi(v.w)};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { s1[e] += f[e]; s2[e] = fmaf(f[e], f[e], s2[e]); }
+        }
         if (g.res) {
           const uint4 rv = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.res) + (size_t)row * g.NC + col);
           v.x = pack_bf2(apply_act(bf_lo(v.x) + bf_lo(rv.x), g.res_act), apply_act(bf_hi(v.x) + bf_hi(rv.x), g.res_act));
@@ -426,6 +438,30 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
           v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(rv.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(rv.w), g.res_act));
         }
         *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = v;
+      }
+    }
+    if (EPI == EPI_STORE && g.stats) {
+      // threads with equal tid % CPROW hold the same 8 channels: butterfly inside the wave, then the four
+      // waves in order through LDS (a fixed association)
+#pragma unroll
+      for (int off = CPROW; off < 64; off <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { s1[e] += __shfl_xor(s1[e], off, 64); s2[e] += __shfl_xor(s2[e], off, 64); }
+      __syncthreads();                               // the staged tile has been read by everyone
+      float* red = reinterpret_cast<float*>(smem);   // [wave][chunk column][16]
+      if (lane < CPROW) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { red[(wave * CPROW + lane) * 16 + e] = s1[e]; red[(wave * CPROW + lane) * 16 + 8 + e] = s2[e]; }
+      }
+      __syncthreads();
+      const int col = n0 + tid * 8;
+      if (tid < CPROW && col < g.NC) {
+        float* dst = g.stats + (size_t)tile_m * 2 * g.NC + col;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float t = (red[tid * 16 + e] + red[(CPROW + tid) * 16 + e]) + (red[(2 * CPROW + tid) * 16 + e] + red[(3 * CPROW + tid) * 16 + e]);
+          dst[(e >> 3) * g.NC + (e & 7)] = t;
+        }
       }
     }
     return;

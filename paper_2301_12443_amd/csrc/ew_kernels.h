@@ -363,13 +363,25 @@ __global__ void bn_finalize_kernel(const float* __restrict__ part, const T* __re
   finalize_sums(part, chunks, Cp, c, lane, s1, s2);
   if (c >= Cp || lane != 0) return;
   const double shift = s1 / m;
-  const double mu = (double)(float)y[c] + shift;
+  const double mu = (y ? (double)(float)y[c] : 0.0) + shift;     // y: the pivot row the sums were shifted by, if any
   double var = s2 / m - shift * shift;
   if (var < 0.0) var = 0.0;
   mean[c] = (float)mu;
   invstd[c] = (float)(1.0 / sqrt(var + (double)eps));
   rmean[c] = (1.f - rho) * rmean[c] + rho * (float)mu;
   rvar[c] = (1.f - rho) * rvar[c] + rho * (float)(var * m / (m - 1.0));
+}
+
+// out[g][i] = sum of part[k][i] over the `per` chunks of group g, in order: shortens the list of partial
+// sums that a finalize kernel walks through when a convolution's row tiles delivered thousands of them
+constexpr int kStatGroupsMax = 1024;   // partial sums a batch-norm finalize walks through at most
+__global__ void regroup_partials_kernel(const float* __restrict__ part, float* __restrict__ out, int chunks, int n, int per) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int k0 = blockIdx.y * per, k1 = min(chunks, k0 + per);
+  float s = 0.f;
+  for (int k = k0; k < k1; ++k) s += part[(long)k * n + i];
+  out[(long)blockIdx.y * n + i] = s;
 }
 
 // BN backward, stage 1: with xhat = (y - mean)*invstd, pre = gamma*xhat + beta and

@@ -378,6 +378,8 @@ int plan(pbd_ctx* c) {
         } else if (bf && !c->o.force_direct) {
           const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
           need_red((size_t)w.splits * op.wn * 4);
+          // per-row-tile batch-norm sums from the convolution's store (64-row tiles at most), and their regrouping
+          need_red(((size_t)(M + 63) / 64 + kStatGroupsMax + 1) * 2 * op.cout_p * 4);
           const long Min = (long)c->o.batch * op.in.h * op.in.w;
           need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p) * M * op.d.c_out * 4);
           need_red((size_t)igemm_splits(Min, op.cin_p, op.d.k * op.d.k * op.d.c_out, op.d.c_out) * Min * op.cin_p * 4);
@@ -491,10 +493,19 @@ template <class T> struct Exec {
     const IgemmCfg cfg = igemm_cfg((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
     return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);
   }
+  // Row tiles whose staged store also delivers the batch-norm sums of the convolution's output (0: the
+  // layer takes its statistics in a pass of its own).  Same conditions as fuses_residual, whole channel
+  // vectors, and a column long enough for the chunked normalisation path.
+  int fused_stats_tiles(const OpPlan& op) const {
+    const long M = (long)c->o.batch * op.out.h * op.out.w;
+    if (!fuses_residual(op) || op.d.c_out % 8 != 0 || short_column(M)) return 0;
+    const IgemmCfg cfg = igemm_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
+    return (int)((M + cfg.BM - 1) / cfg.BM);
+  }
   // res (optional): a residual join fused into the store, y = res_act(conv result + res); only where
-  // fuses_residual(op) holds
+  // fuses_residual(op) holds.  stats (optional): per row tile sums of y and y^2, where fused_stats_tiles(op) > 0
   void conv_fwd(const OpPlan& op, const T* x, const T* w, T* y, const float* a, const float* b, int act,
-                const T* res = nullptr, int res_act = 0) {
+                const T* res = nullptr, int res_act = 0, float* stats = nullptr) {
     const int N = c->o.batch;
     const double flops = 2.0 * N * op.out.h * op.out.w * op.d.c_out * op.d.k * op.d.k * op.in.c;
     const double bytes = bytes_of(op.in) + bytes_of(op.out) * (res ? 2 : 1) + (double)op.wn * sizeof(T);
@@ -503,7 +514,7 @@ template <class T> struct Exec {
         IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                     op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0,
                     (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2), (unsigned)(op.wn * 2)};
-        g.res = res; g.res_act = res_act;
+        g.res = res; g.res_act = res_act; g.stats = stats;
         launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE,
                         bytes, flops);
       }
@@ -904,8 +915,9 @@ template <class T> struct Exec {
       const T* x = value(op.d.in[0]);
       if (op.d.type == OP_CBA) {
         T* y = ws(scr + op.y);
+        const int stat_tiles = op.dw ? 0 : fused_stats_tiles(op);
         if (op.dw) dw_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0);
-        else conv_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0);
+        else conv_fwd(op, x, wc + op.e_w, y, nullptr, nullptr, 0, nullptr, 0, stat_tiles ? red() : nullptr);
         const long M = (long)N * op.out.h * op.out.w;
         if (short_column(M)) {
           ProfScope ps(c, "bn_small_fwd", 3 * bytes_of(op.out), 0, net, blk, opi);
@@ -913,13 +925,28 @@ template <class T> struct Exec {
                  master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean), wsf(op.s_rvar), (int)M,
                  op.cout_p, c->o.bn_eps, c->o.bn_momentum, op.d.act, (unsigned)(M * op.cout_p * sizeof(T)));
         } else {
-          const ColGrid g = bn_stats_grid(M, op.cout_p);
-          {
+          const float* part = red();
+          const T* pivot = y;                       // the pass of its own shifts by the first row
+          int chunks = stat_tiles;
+          if (stat_tiles) {
+            // the convolution's store left one pair of sums per row tile (no pivot); thousands of them are
+            // first summed in groups so that the finalize kernel's walk stays short
+            pivot = nullptr;
+            if (chunks > kStatGroupsMax) {
+              const int per = (chunks + kStatGroupsMax - 1) / kStatGroupsMax, n = 2 * op.cout_p;
+              float* out = red() + (size_t)chunks * n;
+              const int groups = (chunks + per - 1) / per;
+              launch(c, regroup_partials_kernel, dim3((n + 255) / 256, groups), 256, 0, st, part, out, chunks, n, per);
+              part = out; chunks = groups;
+            }
+          } else {
+            const ColGrid g = bn_stats_grid(M, op.cout_p);
             ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_stats_kernel<T>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st, y, red(), M, op.cout_p, g);
+            chunks = g.chunks;
           }
           launch(c, bn_finalize_kernel<T>, op.cout_p / kFinalizeChannels, 256, 0, st, 
-              red(), y, g.chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
+              part, pivot, chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
               wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
           {
             const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);   // elementwise pass: many short workgroups

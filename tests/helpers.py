@@ -109,6 +109,11 @@ def layer_workloads():
     t.cba(0, 384, 3)
     v = s.cba(0, 384, 1); s.cba(v, 384, 3)
     wl("l_deepK3x3", (256, 7, 7), t, s, 32)
+    # long columns: 147456 rows = 1152 row tiles, more partial sums than one normalisation finalize walks
+    t, s = W.Block(), W.Block()
+    t.cba(0, 16, 3)
+    v = s.cba(0, 40, 1); s.cba(v, 16, 3)
+    wl("l_long_column", (24, 64, 64), t, s, 36)
     return out
 
 
