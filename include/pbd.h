@@ -178,6 +178,22 @@ int pbd_arch_step(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pbd_t
  * pbd_distill_step (the two rounds are captured separately). */
 int pbd_distill_arch_step(pbd_ctx* ctx, const float* x_dev, float lr_alpha, float* losses_dev);
 
+/* The whole step as one stage of a pipeline over batches (Sec. IV-A, teacher relaying, and Sec. IV-B,
+ * decoupled updates: no student waits for another, so the teacher may go on to the next batch while
+ * the students still train on the last one; Fig. 2d shows the schedule over devices, this is its
+ * one-device form).  The call hands in batch k: the teacher relays it into the spare copy of the
+ * activation store while, next to it, every student block trains on batch k-1 from the other copy, with
+ * the learning rate that was passed along with batch k-1.  losses_dev (device float32[B]) receives the
+ * losses of batch k-1; the first call after pbd_bind or pbd_pipeline_flush only runs the teacher and
+ * leaves losses_dev alone.  pbd_pipeline_flush trains the students on the batch still waiting (nothing
+ * if none) and writes its losses.  K calls and a flush leave the same parameters, statistics and losses,
+ * bit for bit, as K calls of pbd_distill_step on the same batches.  x_dev is consumed by the call (it is
+ * cast into the store).  Graph capture as for pbd_distill_step (one graph per copy).  While a batch waits,
+ * the one-step calls (relay, prefix, student, architecture and whole steps) return PBD_ESTATE, the views
+ * and pbd_read_act show the waiting batch, and pbd_read_value has nothing to show until the flush. */
+int pbd_pipeline_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
+int pbd_pipeline_flush(pbd_ctx* ctx, float* losses_dev);
+
 /* Architecture parameters of student block b (from 0), op index op (a type-4 op with n inputs).
  * pbd_load_alpha copies n float32 from host and sets p = softmax(alpha); momentum is kept.
  * pbd_read_alpha copies alpha (PBD_PARAM), its last gradient (PBD_GRAD), its momentum (PBD_MOMENTUM)
@@ -186,8 +202,8 @@ int pbd_distill_arch_step(pbd_ctx* ctx, const float* x_dev, float lr_alpha, floa
 int pbd_load_alpha(pbd_ctx* ctx, int32_t b, int32_t op, const float* host, size_t n);
 int pbd_read_alpha(pbd_ctx* ctx, int32_t kind, int32_t b, int32_t op, float* host, size_t n);
 
-/* 1 if pbd_distill_step or pbd_distill_arch_step currently replays a captured HIP graph, 0 if they
- * launch directly. */
+/* 1 if pbd_distill_step, pbd_distill_arch_step or pbd_pipeline_step currently replays a captured HIP
+ * graph, 0 if they launch directly. */
 int pbd_uses_graph(const pbd_ctx* ctx);
 
 /* Wait for the bound stream; reports asynchronous failures. */

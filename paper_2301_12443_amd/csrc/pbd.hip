@@ -86,7 +86,7 @@ struct pbd_ctx {
   std::vector<size_t> act_off;          // byte offsets (relay region)
   size_t esz = 4;                       // bytes per tensor element
   // regions (byte offsets from the workspace base)
-  size_t r_param = 0, r_relay = 0, r_tscr = 0, r_tred = 0, total = 0;
+  size_t r_param = 0, r_relay = 0, r_relay2 = 0, r_tscr = 0, r_tred = 0, total = 0;
   bool concurrent = false;              // student blocks own disjoint scratch and may overlap
   std::vector<hipStream_t> side;        // one stream per student block (graph capture branches)
   std::vector<hipEvent_t> ev_fork, ev_join;
@@ -99,6 +99,16 @@ struct pbd_ctx {
   size_t lr_off = 0, loss_off = 0;      // device scalars: learning rate, per-block losses
   hipGraphExec_t gexec[2] = {nullptr, nullptr};   // the captured step: [0] weight round, [1] architecture round
   bool graph_tried[2] = {false, false};
+  // pipelined steps (pbd_pipeline_step): the relay store exists twice; `front` is the copy the teacher
+  // wrote last (the one the views and read-backs show), `pending` says that its batch still waits for
+  // the students.  gpipe[q]: captured body with the teacher writing copy q and the students reading 1-q.
+  int front = 0;
+  bool pending = false;
+  float pending_lr = 0.f;
+  hipGraphExec_t gpipe[2] = {nullptr, nullptr};
+  bool gpipe_tried[2] = {false, false};
+  hipGraphExec_t gdrain[2] = {nullptr, nullptr};  // the students alone, reading copy q (pbd_pipeline_flush)
+  bool gdrain_tried[2] = {false, false};
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
   hipEvent_t pend_start = nullptr, pend_stop = nullptr;   // events waiting for the next launch
@@ -344,6 +354,8 @@ int plan(pbd_ctx* c) {
   size_t r = 0;
   for (Shape s : c->act) { c->act_off.push_back(r); r += tensor_bytes(c, s); }
   cur += r;
+  c->r_relay2 = cur;      // second copy: the teacher fills one while the students still read the other
+  cur += r;
   // teacher scratch: every value of the largest block except its output (-> relay)
   size_t tmax = 0;
   for (BlockPlan& bp : c->net[0]) {
@@ -476,11 +488,14 @@ template <class T> struct Exec {
   hipStream_t st;
   int net = 0, blk = 0, opi = 0;
   size_t red_off;
-  explicit Exec(pbd_ctx* ctx) : c(ctx), st(ctx->stream), red_off(ctx->r_tred) {}
+  int tset, sset;      // copy of the relay store the teacher writes / the students read
+  explicit Exec(pbd_ctx* ctx) : c(ctx), st(ctx->stream), red_off(ctx->r_tred), tset(ctx->front), sset(ctx->front) {}
 
   T* ws(size_t off) const { return reinterpret_cast<T*>(c->ws + off); }
   float* wsf(size_t off) const { return reinterpret_cast<float*>(c->ws + off); }
-  T* relay(int i) const { return ws(c->r_relay + c->act_off[i]); }
+  T* relay_in(int i, int set) const { return ws((set ? c->r_relay2 : c->r_relay) + c->act_off[i]); }
+  T* trelay(int i) const { return relay_in(i, tset); }
+  T* srelay(int i) const { return relay_in(i, sset); }
   float* red() const { return wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
@@ -772,8 +787,8 @@ template <class T> struct Exec {
     BlockPlan& bp = c->net[0][b];
     net = PBD_TEACHER; blk = b;
     auto value = [&](int v) -> T* {
-      if (v == 0) return relay(b);
-      if (v + 1 == (int)bp.shapes.size()) return relay(b + 1);
+      if (v == 0) return trelay(b);
+      if (v + 1 == (int)bp.shapes.size()) return trelay(b + 1);
       return ws(c->r_tscr + bp.val[v]);
     };
     std::vector<char> fused(bp.ops.size(), 0);      // adds that rode in their producer's store
@@ -834,7 +849,7 @@ template <class T> struct Exec {
       const long nvec = (long)c->o.batch * s.h * s.w * round8(s.c) / 8;
       net = PBD_TEACHER; blk = -1; opi = -1;
       ProfScope ps(c, "cast_input", (double)c->o.batch * s.c * s.h * s.w * 4 + bytes_of(s), 0, net, blk, opi);
-      launch(c, cast_input_kernel<T>, grid_for(nvec), 256, 0, st, x_dev, relay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
+      launch(c, cast_input_kernel<T>, grid_for(nvec), 256, 0, st, x_dev, trelay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
     }
   }
   void relay_all(const float* x_dev) { relay_prefix(x_dev, c->B); }
@@ -868,6 +883,29 @@ template <class T> struct Exec {
     }
     c->relayed_upto = c->B;
   }
+  // One stage of the pipeline over steps (Sec. IV-A and IV-B: with the updates decoupled, the teacher
+  // goes on to the next batch while the students still train on the last one): the teacher relays the
+  // new batch into copy `tset` of the store; the students train on the batch in copy `sset`.  Nothing
+  // of one depends on the other, so with `fork` every student block and the teacher chain start together.
+  void pipe_body(bool fork, bool teacher = true) {
+    hipStream_t main = st;
+    if (fork) {
+      (void)hipEventRecord(c->ev_fork[0], main);
+      for (int b = 0; b < c->B; ++b) {
+        (void)hipStreamWaitEvent(c->side[b], c->ev_fork[0], 0);
+        st = c->side[b];
+        student_block(b, wsf(c->loss_off) + b);
+        (void)hipEventRecord(c->ev_join[b], st);
+      }
+      st = main;
+    }
+    if (teacher)
+      for (int b = 0; b < c->B; ++b) teacher_block(b);
+    for (int b = 0; b < c->B; ++b) {
+      if (fork) (void)hipStreamWaitEvent(main, c->ev_join[b], 0);
+      else student_block(b, wsf(c->loss_off) + b);
+    }
+  }
 
   // =========================================================================
   // student block b = i-1: forward, loss, backward, update
@@ -897,7 +935,7 @@ template <class T> struct Exec {
     const int N = c->o.batch;
     const size_t scr = bp.scr_off;
     red_off = bp.red_off;
-    auto value = [&](int v) -> T* { return v == 0 ? relay(b) : ws(scr + bp.val[v]); };
+    auto value = [&](int v) -> T* { return v == 0 ? srelay(b) : ws(scr + bp.val[v]); };
     auto dvalue = [&](int v) -> T* { return ws(scr + bp.dval[v]); };
     T* wc = ws(bp.wc);
     float* grad = wsf(bp.grad);
@@ -990,7 +1028,7 @@ template <class T> struct Exec {
       const int nb = (int)std::min<long>(kMseBlocks, (nvec + 255) / 256);
       opi = -1;
       ProfScope ps(c, "mse_loss_grad", 3 * bytes_of(s), 0, net, blk, opi);
-      launch(c, mse_kernel<T>, nb, 256, 0, st, value(nval - 1), relay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
+      launch(c, mse_kernel<T>, nb, 256, 0, st, value(nval - 1), srelay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
       launch(c, mse_final_kernel, 1, 256, 0, st, red(), nb, 1.0 / (double)numel, loss_dev);
     }
 
@@ -1239,10 +1277,21 @@ template <class F> int dispatch(pbd_ctx* c, F&& f) {
   return after_launches(c);
 }
 
+// A_i in the copy of the relay store that the teacher wrote last
+char* relay_ptr(pbd_ctx* c, int i) { return c->ws + (c->front ? c->r_relay2 : c->r_relay) + c->act_off[i]; }
+
+// the calls that run one step at a time refuse to work while a pipelined batch is in flight
+int check_idle(pbd_ctx* c) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (c->pending) return fail(c, PBD_ESTATE, "a pipelined batch waits for its students (call pbd_pipeline_flush first)");
+  return PBD_OK;
+}
+
 int check_view(pbd_ctx* c, const pbd_tensor* t, int i, const char* what) {
   if (!t) return fail(c, PBD_EINVAL, "%s is null", what);
   const Shape s = c->act[i];
-  if (t->ptr != c->ws + c->r_relay + c->act_off[i] || t->n != c->o.batch || t->c != s.c || t->h != s.h ||
+  if (t->ptr != relay_ptr(c, i) || t->n != c->o.batch || t->c != s.c || t->h != s.h ||
       t->w != s.w || t->c_phys != round8(s.c) || t->dtype != c->o.precision)
     return fail(c, PBD_ESHAPE, "%s is not the relayed activation A_%d", what, i);
   return PBD_OK;
@@ -1284,15 +1333,30 @@ int define_alpha(pbd_ctx* c, int b) {
 
 void fill_view(pbd_ctx* c, int i, pbd_tensor* t) {
   const Shape s = c->act[i];
-  t->ptr = c->ws + c->r_relay + c->act_off[i];
+  t->ptr = relay_ptr(c, i);
   t->n = c->o.batch; t->c = s.c; t->h = s.h; t->w = s.w;
   t->c_phys = round8(s.c);
   t->dtype = c->o.precision;
 }
 
+// One stream and two events per student block for the forked capture; false if they cannot be had.
+bool side_streams(pbd_ctx* c) {
+  bool ok = c->concurrent;
+  if (ok && c->side.empty()) {
+    for (int b = 0; b < c->B && ok; ++b) {
+      hipStream_t s2; hipEvent_t e1, e2;
+      ok = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&e1, hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&e2, hipEventDisableTiming) == hipSuccess;
+      if (ok) { c->side.push_back(s2); c->ev_fork.push_back(e1); c->ev_join.push_back(e2); }
+    }
+  }
+  return ok && (int)c->side.size() == c->B;
+}
+
 // The whole step in one of its two rounds (r = 0: weights, 1: architecture parameters).
 int whole_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev, int r) {
-  int rc = check_ready(c);
+  int rc = check_idle(c);
   if (rc) return rc;
   if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
   if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
@@ -1304,22 +1368,13 @@ int whole_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev, int 
   // graph and replayed: ~300 small launches per step would otherwise be bound by launch cost.
   // Capture needs a real stream and no profiling events; otherwise the kernels are launched directly.
   const bool want_graph = c->stream != nullptr && !c->prof_on && !c->o.no_graph;
+  c->front = 0;        // the captured body addresses the first copy of the relay store
   rc = dispatch(c, [&](auto& e) { e.set_lr(lr); e.prepare(x_dev); });
   if (rc) return rc;
   if (want_graph && !c->gexec[r] && !c->graph_tried[r]) {
     c->graph_tried[r] = true;
     hipGraph_t graph = nullptr;
-    bool fork = c->concurrent;
-    if (fork && c->side.empty()) {
-      for (int b = 0; b < c->B && fork; ++b) {
-        hipStream_t s2; hipEvent_t e1, e2;
-        fork = hipStreamCreateWithFlags(&s2, hipStreamNonBlocking) == hipSuccess &&
-               hipEventCreateWithFlags(&e1, hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&e2, hipEventDisableTiming) == hipSuccess;
-        if (fork) { c->side.push_back(s2); c->ev_fork.push_back(e1); c->ev_join.push_back(e2); }
-      }
-    }
-    fork = fork && (int)c->side.size() == c->B;
+    const bool fork = side_streams(c);
     if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
       dispatch(c, [&](auto& e) { e.step_body(fork, r == 1); });
       hipError_t ee = hipStreamEndCapture(c->stream, &graph);
@@ -1339,6 +1394,89 @@ int whole_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev, int 
     if (rc) return rc;
   }
   HIP_TRY(c, hipMemcpyAsync(losses_dev, c->ws + c->loss_off, (size_t)c->B * 4, hipMemcpyDeviceToDevice, c->stream));
+  return after_launches(c);
+}
+
+// The students' half of a pipelined step on the batch in the front copy, block after block.
+int pipeline_drain(pbd_ctx* c, float* losses_dev) {
+  const bool want_graph = c->stream != nullptr && !c->prof_on && !c->o.no_graph;
+  const int q = c->front;
+  int rc = dispatch(c, [&](auto& e) {
+    e.set_lr(c->pending_lr);
+    for (int b = 0; b < c->B; ++b) {
+      e.net = PBD_STUDENT; e.blk = b;
+      if (c->net[1][b].dirty) e.refresh_compute_copies(c->net[1][b]);
+    }
+  });
+  if (rc) return rc;
+  if (want_graph && !c->gdrain[q] && !c->gdrain_tried[q]) {
+    c->gdrain_tried[q] = true;
+    hipGraph_t graph = nullptr;
+    const bool fork = side_streams(c);
+    if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
+      dispatch(c, [&](auto& e) { e.pipe_body(fork, false); });
+      hipError_t ee = hipStreamEndCapture(c->stream, &graph);
+      if (ee == hipSuccess && graph && hipGraphInstantiate(&c->gdrain[q], graph, nullptr, nullptr, 0) != hipSuccess)
+        c->gdrain[q] = nullptr;
+      if (graph) (void)hipGraphDestroy(graph);
+    }
+    (void)hipGetLastError();
+  }
+  if (want_graph && c->gdrain[q]) {
+    HIP_TRY(c, hipGraphLaunch(c->gdrain[q], c->stream));
+  } else {
+    rc = dispatch(c, [&](auto& e) { e.pipe_body(false, false); });
+    if (rc) return rc;
+  }
+  HIP_TRY(c, hipMemcpyAsync(losses_dev, c->ws + c->loss_off, (size_t)c->B * 4, hipMemcpyDeviceToDevice, c->stream));
+  c->pending = false;
+  for (BlockPlan& bp : c->net[1]) bp.stepped = c->concurrent;
+  c->net[1].back().stepped = true;
+  return after_launches(c);
+}
+
+int pipeline_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
+  if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
+  if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
+  const bool had = c->pending;
+  const int tset = had ? 1 - c->front : c->front;
+  if (!had) {
+    // first batch: only the teacher has work
+    rc = dispatch(c, [&](auto& e) { e.relay_all(x_dev); });
+    if (rc) return rc;
+  } else {
+    const bool want_graph = c->stream != nullptr && !c->prof_on && !c->o.no_graph;
+    rc = dispatch(c, [&](auto& e) { e.tset = tset; e.sset = 1 - tset; e.set_lr(c->pending_lr); e.prepare(x_dev); });
+    if (rc) return rc;
+    if (want_graph && !c->gpipe[tset] && !c->gpipe_tried[tset]) {
+      c->gpipe_tried[tset] = true;
+      hipGraph_t graph = nullptr;
+      const bool fork = side_streams(c);
+      if (hipStreamBeginCapture(c->stream, hipStreamCaptureModeRelaxed) == hipSuccess) {
+        dispatch(c, [&](auto& e) { e.tset = tset; e.sset = 1 - tset; e.pipe_body(fork); });
+        hipError_t ee = hipStreamEndCapture(c->stream, &graph);
+        if (ee == hipSuccess && graph && hipGraphInstantiate(&c->gpipe[tset], graph, nullptr, nullptr, 0) != hipSuccess)
+          c->gpipe[tset] = nullptr;
+        if (graph) (void)hipGraphDestroy(graph);
+      }
+      (void)hipGetLastError();
+    }
+    if (want_graph && c->gpipe[tset]) {
+      HIP_TRY(c, hipGraphLaunch(c->gpipe[tset], c->stream));
+    } else {
+      rc = dispatch(c, [&](auto& e) { e.tset = tset; e.sset = 1 - tset; e.pipe_body(false); });
+      if (rc) return rc;
+    }
+    HIP_TRY(c, hipMemcpyAsync(losses_dev, c->ws + c->loss_off, (size_t)c->B * 4, hipMemcpyDeviceToDevice, c->stream));
+  }
+  c->front = tset;
+  c->relayed_upto = c->B;
+  c->pending = true;
+  c->pending_lr = lr;
+  for (BlockPlan& bp : c->net[1]) bp.stepped = false;    // their saved values belong to the batch before
   return after_launches(c);
 }
 
@@ -1412,6 +1550,8 @@ int pbd_create(const int32_t* words, int32_t nwords, const double* pool, int32_t
 void pbd_destroy(pbd_ctx* c) {
   if (!c) return;
   for (hipGraphExec_t g : c->gexec) if (g) (void)hipGraphExecDestroy(g);
+  for (hipGraphExec_t g : c->gpipe) if (g) (void)hipGraphExecDestroy(g);
+  for (hipGraphExec_t g : c->gdrain) if (g) (void)hipGraphExecDestroy(g);
   for (hipStream_t s2 : c->side) (void)hipStreamDestroy(s2);
   for (hipEvent_t e : c->ev_fork) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->ev_join) (void)hipEventDestroy(e);
@@ -1436,7 +1576,13 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
   for (int r = 0; r < 2; ++r) {
     if (c->gexec[r]) { (void)hipGraphExecDestroy(c->gexec[r]); c->gexec[r] = nullptr; }
     c->graph_tried[r] = false;
+    if (c->gpipe[r]) { (void)hipGraphExecDestroy(c->gpipe[r]); c->gpipe[r] = nullptr; }
+    c->gpipe_tried[r] = false;
+    if (c->gdrain[r]) { (void)hipGraphExecDestroy(c->gdrain[r]); c->gdrain[r] = nullptr; }
+    c->gdrain_tried[r] = false;
   }
+  c->front = 0;
+  c->pending = false;
   c->bound = true;
   c->relayed_upto = 0;
   c->fold_dirty = true;
@@ -1527,7 +1673,7 @@ int pbd_read_act(pbd_ctx* c, int32_t i, float* host, size_t n) {
   if (c->relayed_upto < std::max(i, 1)) return fail(c, PBD_ESTATE, "the teacher has not produced A_%d yet", i);
   const Shape s = c->act[i];
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "A_%d has %zu elements, %zu asked", i, (size_t)c->o.batch * s.c * s.h * s.w, n);
-  return download_act(c, c->ws + c->r_relay + c->act_off[i], s, host);
+  return download_act(c, relay_ptr(c, i), s, host);
 }
 
 int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
@@ -1542,12 +1688,12 @@ int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
   if (v > 0 && !short_column((long)c->o.batch * s.h * s.w) && residual_reader(bp, v - 1) >= 0)
     return fail(c, PBD_ESTATE, "value %d of block %d is not kept: the residual add that reads it is fused into its normalisation", v, b);
-  const char* dev = v == 0 ? c->ws + c->r_relay + c->act_off[b] : c->ws + bp.scr_off + bp.val[v];
+  const char* dev = v == 0 ? relay_ptr(c, b) : c->ws + bp.scr_off + bp.val[v];
   return download_act(c, dev, s, host);
 }
 
 int pbd_teacher_relay(pbd_ctx* c, const float* x_dev, pbd_tensor* A) {
-  int rc = check_ready(c);
+  int rc = check_idle(c);
   if (rc) return rc;
   if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
   rc = dispatch(c, [&](auto& e) { e.relay_all(x_dev); });
@@ -1557,7 +1703,7 @@ int pbd_teacher_relay(pbd_ctx* c, const float* x_dev, pbd_tensor* A) {
 }
 
 int pbd_teacher_prefix(pbd_ctx* c, const float* x_dev, int32_t upto, pbd_tensor* A) {
-  int rc = check_ready(c);
+  int rc = check_idle(c);
   if (rc) return rc;
   if (!x_dev) return fail(c, PBD_EINVAL, "x_dev is null");
   if (upto < 1 || upto > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", upto, c->B);
@@ -1568,7 +1714,7 @@ int pbd_teacher_prefix(pbd_ctx* c, const float* x_dev, int32_t upto, pbd_tensor*
 }
 
 int pbd_student_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr, float* loss_dev) {
-  int rc = check_ready(c);
+  int rc = check_idle(c);
   if (rc) return rc;
   if (i < 1 || i > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", i, c->B);
   if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
@@ -1587,8 +1733,20 @@ int pbd_distill_arch_step(pbd_ctx* c, const float* x_dev, float lr_alpha, float*
   return whole_step(c, x_dev, lr_alpha, losses_dev, 1);
 }
 
-int pbd_arch_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr_alpha, float* loss_dev) {
+int pbd_pipeline_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev) {
+  return pipeline_step(c, x_dev, lr, losses_dev);
+}
+
+int pbd_pipeline_flush(pbd_ctx* c, float* losses_dev) {
   int rc = check_ready(c);
+  if (rc) return rc;
+  if (!c->pending) return PBD_OK;
+  if (!losses_dev) return fail(c, PBD_EINVAL, "losses_dev is null");
+  return pipeline_drain(c, losses_dev);
+}
+
+int pbd_arch_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr_alpha, float* loss_dev) {
+  int rc = check_idle(c);
   if (rc) return rc;
   if (i < 1 || i > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", i, c->B);
   if (!std::isfinite(lr_alpha)) return fail(c, PBD_EINVAL, "learning rate is not finite");
@@ -1644,7 +1802,7 @@ int pbd_read_alpha(pbd_ctx* c, int32_t kind, int32_t b, int32_t opi, float* host
   return PBD_OK;
 }
 
-int pbd_uses_graph(const pbd_ctx* c) { return c && (c->gexec[0] || c->gexec[1]) ? 1 : 0; }
+int pbd_uses_graph(const pbd_ctx* c) { return c && (c->gexec[0] || c->gexec[1] || c->gpipe[0] || c->gpipe[1]) ? 1 : 0; }
 
 int pbd_sync(pbd_ctx* c) {
   int rc = check_ready(c);
