@@ -26,8 +26,8 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # the figures are carried here and apply to the workload they were measured on only.
 HBM_TRAFFIC_PER_LAUNCH = {
     "vgg16_dsconv": {
-        "bn_bwd_reduce": 30542986, "bn_bwd_apply": 45054093, "bn_apply": 30080577, "bn_stats": 15496419,
-        "dw_wgrad_tile_k3": 27358435, "sum_partials": 7974621, "bn_small_bwd": 7976987, "bn_small_fwd": 5246914,
+        "bn_bwd_reduce": 30547082, "bn_bwd_apply": 45063308, "bn_apply": 30130751, "bn_stats": 12420551,
+        "dw_wgrad_tile_k3": 27366059, "sum_partials": 7974621, "bn_small_bwd": 7991322, "bn_small_fwd": 5250496,
     },
 }
 

@@ -114,3 +114,33 @@ def test_calls_that_do_not_mix_with_a_batch_in_flight():
     d.pipeline_flush(); d.sync()
     d.read_value(0, 1)
     d.distill_step(x, wl.lr); d.sync()
+
+
+def test_full_size_pipelined_steps_equal_whole_steps():
+    """Configuration 2 at its full batch, in the launch configuration the benchmark times (graph replay of
+    the pipelined body): four batches leave bit for bit the losses, weights, momenta and running statistics
+    of four whole steps - and the whole step at this size is held against the oracle elsewhere."""
+    wl = W.vgg16_dsconv()
+    k = 4
+    xs = _batches(wl, k)
+    plain, piped = _distiller(wl, None), _distiller(wl, None)
+    want, got = [], []
+    for x in xs:
+        plain.distill_step(x, wl.lr)
+        plain.sync()
+        want.append(plain.losses.cpu().numpy().copy())
+    for s, x in enumerate(xs):
+        piped.pipeline_step(x, wl.lr)
+        piped.sync()
+        if s:
+            got.append(piped.losses.cpu().numpy().copy())
+    piped.pipeline_flush()
+    piped.sync()
+    got.append(piped.losses.cpu().numpy().copy())
+    assert piped.uses_graph()
+    assert np.array_equal(np.array(got), np.array(want))
+    for i in range(wl.B + 1):
+        assert np.array_equal(piped.read_act(i), plain.read_act(i)), i
+    a, b = _state(plain, wl), _state(piped, wl)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
