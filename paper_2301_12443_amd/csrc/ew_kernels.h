@@ -1180,6 +1180,11 @@ __global__ __launch_bounds__(256) void dw_slide_kernel(const T* __restrict__ x, 
     const int p = (int)(seg % P);
     const int n = (int)(seg / P);
     const int q0 = qs * WS, w0 = q0 * STRIDE - pad;
+    float ea[8], eb[8];                // folded BN terms, fetched ahead of the taps they follow
+    if (a) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { ea[e] = a[cv * 8 + e]; eb[e] = b[cv * 8 + e]; }
+    }
     float acc[WS][8];
 #pragma unroll
     for (int o = 0; o < WS; ++o)
@@ -1219,7 +1224,7 @@ __global__ __launch_bounds__(256) void dw_slide_kernel(const T* __restrict__ x, 
       T* out = dst + ((((long)n * P + p) * Q + q0 + o) * ncv + cv) * 8;
       if (a) {  // folded inference-mode BN + activation (teacher)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[o][e] = apply_act(fmaf(acc[o][e], a[cv * 8 + e], b[cv * 8 + e]), act);
+        for (int e = 0; e < 8; ++e) acc[o][e] = apply_act(fmaf(acc[o][e], ea[e], eb[e]), act);
       }
       if (accumulate) {
         float old[8];
@@ -1296,6 +1301,11 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
   const int cvl = tid % CVB, seg = (tid / CVB) % (TW / WS), th = tid / (CVB * (TW / WS));
   const int cv = cv0 + cvl;
   if (cv >= ncv) return;
+  float ea[8], eb[8];                  // folded BN terms, fetched ahead of the taps they follow
+  if (a) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { ea[e] = a[cv * 8 + e]; eb[e] = b[cv * 8 + e]; }
+  }
   float acc[WS][8];
 #pragma unroll
   for (int o = 0; o < WS; ++o)
@@ -1337,7 +1347,7 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
     bf16_t* out = dst + ((((long)n * H + h) * W + ww) * ncv + cv) * 8;
     if (a) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[o][e] = apply_act(fmaf(acc[o][e], a[cv * 8 + e], b[cv * 8 + e]), act);
+      for (int e = 0; e < 8; ++e) acc[o][e] = apply_act(fmaf(acc[o][e], ea[e], eb[e]), act);
     }
     if (accumulate) {
       float old[8];
