@@ -202,6 +202,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int chunk = tid % CPR, prow = tid / CPR;
   const int sh = g.stride == 2 ? 1 : 0, smask = g.stride - 1;
+  // the tile's folded batch-norm terms wait in LDS from the start, so that the store at the end does not
+  // begin with a round trip to memory (columns past NC repeat the last four: they are never stored)
+  __shared__ __attribute__((aligned(16))) float ep_s[EPI == EPI_AFFINE_ACT ? 2 * BN : 4];
+  if (EPI == EPI_AFFINE_ACT && tid < BN / 4) {
+    const int col = min(n0 + tid * 4, g.NC - 4);
+    *reinterpret_cast<float4*>(ep_s + tid * 4) = *reinterpret_cast<const float4*>(ep_a + col);
+    *reinterpret_cast<float4*>(ep_s + BN + tid * 4) = *reinterpret_cast<const float4*>(ep_b + col);
+  }
 
   // The A rows this thread stages, decoded once.  All offsets are 32-bit element indices
   // (create rejects tensors of 2^31 elements or more), and the per-step work is a handful of adds.
@@ -386,6 +394,22 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
     constexpr int OP = BN * 2 + 16;                  // bytes per staged row; the pad spreads rows over banks
     static_assert(BM * OP <= 2 * (BM + BN) * PITCH * 2, "the output tile must fit in the operand tiles' LDS");
     unsigned char* stage = reinterpret_cast<unsigned char*>(smem);
+    constexpr int CPROW = BN / 8;                    // 16-byte chunks per row
+    constexpr int NCHUNK = BM * CPROW;
+    static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
+    // a fused residual is fetched now, ahead of the staging, where the registers allow (8 chunks per thread)
+    constexpr bool kResEarly = NCHUNK / 256 <= 8;
+    uint4 rv[kResEarly ? NCHUNK / 256 : 1];
+    if (kResEarly && g.res) {
+#pragma unroll
+      for (int k = 0; k < NCHUNK / 256; ++k) {
+        const int cidx = tid + k * 256;
+        const int row = m0 + cidx / CPROW, col = n0 + (cidx % CPROW) * 8;
+        rv[k] = (full || (row < g.M && col < g.NC))
+                    ? *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.res) + (size_t)row * g.NC + col)
+                    : make_uint4(0, 0, 0, 0);
+      }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int lrow = wm * TM * 32 + i * 32 + (lane & 31);
@@ -398,9 +422,8 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
           if (EPI == EPI_AFFINE_ACT) {
-            const int col = min(n0 + lcol, g.NC - 4);   // columns past NC are never stored
-            const float4 ea = *reinterpret_cast<const float4*>(ep_a + col);
-            const float4 eb = *reinterpret_cast<const float4*>(ep_b + col);
+            const float4 ea = *reinterpret_cast<const float4*>(ep_s + lcol);
+            const float4 eb = *reinterpret_cast<const float4*>(ep_s + BN + lcol);
             o[0] = apply_act(fmaf(o[0], ea.x, eb.x), act); o[1] = apply_act(fmaf(o[1], ea.y, eb.y), act);
             o[2] = apply_act(fmaf(o[2], ea.z, eb.z), act); o[3] = apply_act(fmaf(o[3], ea.w, eb.w), act);
           }
@@ -411,9 +434,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
         }
     }
     __syncthreads();
-    constexpr int CPROW = BN / 8;                    // 16-byte chunks per row
-    constexpr int NCHUNK = BM * CPROW;
-    static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
     static_assert(256 % CPROW == 0, "a thread keeps its chunk column over the rows it stores");
     float s1[8], s2[8];                              // column sums of this thread's chunks (g.stats)
 #pragma unroll
@@ -431,11 +451,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
           for (int e = 0; e < 8; ++e) { s1[e] += f[e]; s2[e] = fmaf(f[e], f[e], s2[e]); }
         }
         if (g.res) {
-          const uint4 rv = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.res) + (size_t)row * g.NC + col);
-          v.x = pack_bf2(apply_act(bf_lo(v.x) + bf_lo(rv.x), g.res_act), apply_act(bf_hi(v.x) + bf_hi(rv.x), g.res_act));
-          v.y = pack_bf2(apply_act(bf_lo(v.y) + bf_lo(rv.y), g.res_act), apply_act(bf_hi(v.y) + bf_hi(rv.y), g.res_act));
-          v.z = pack_bf2(apply_act(bf_lo(v.z) + bf_lo(rv.z), g.res_act), apply_act(bf_hi(v.z) + bf_hi(rv.z), g.res_act));
-          v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(rv.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(rv.w), g.res_act));
+          const uint4 r_ = kResEarly ? rv[kResEarly ? k : 0]
+                                     : *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.res) + (size_t)row * g.NC + col);
+          v.x = pack_bf2(apply_act(bf_lo(v.x) + bf_lo(r_.x), g.res_act), apply_act(bf_hi(v.x) + bf_hi(r_.x), g.res_act));
+          v.y = pack_bf2(apply_act(bf_lo(v.y) + bf_lo(r_.y), g.res_act), apply_act(bf_hi(v.y) + bf_hi(r_.y), g.res_act));
+          v.z = pack_bf2(apply_act(bf_lo(v.z) + bf_lo(r_.z), g.res_act), apply_act(bf_hi(v.z) + bf_hi(r_.z), g.res_act));
+          v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(r_.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(r_.w), g.res_act));
         }
         *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = v;
       }
@@ -471,6 +492,19 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
   constexpr int OPF = BN * 4 + 16;
   if constexpr (EPI == EPI_ACCUM && !kIdleWaves && BM * OPF <= 2 * (BM + BN) * PITCH * 2) {
     unsigned char* stage = reinterpret_cast<unsigned char*>(smem);
+    constexpr int CPROW = BN / 8;
+    constexpr int NCHUNK = BM * CPROW;
+    static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
+    static_assert(NCHUNK / 256 <= 8, "the values to add to are held in registers while the tile is staged");
+    // what the tile adds to is fetched now, ahead of the staging: the stores then wait for LDS only
+    uint4 old[NCHUNK / 256];
+#pragma unroll
+    for (int k = 0; k < NCHUNK / 256; ++k) {
+      const int cidx = tid + k * 256;
+      const int row = m0 + cidx / CPROW, col = n0 + (cidx % CPROW) * 8;
+      old[k] = (full || (row < g.M && col < g.NC)) ? *reinterpret_cast<const uint4*>(Out + (size_t)row * g.NC + col)
+                                                    : make_uint4(0, 0, 0, 0);
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int lrow = wm * TM * 32 + i * 32 + (lane & 31);
@@ -484,9 +518,6 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
         }
     }
     __syncthreads();
-    constexpr int CPROW = BN / 8;
-    constexpr int NCHUNK = BM * CPROW;
-    static_assert(NCHUNK % 256 == 0, "chunks divide evenly over the block");
 #pragma unroll
     for (int k = 0; k < NCHUNK / 256; ++k) {
       const int cidx = tid + k * 256;
@@ -496,12 +527,11 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
         bf16_t* dst = Out + (size_t)row * g.NC + col;
         const float4 lo = *reinterpret_cast<const float4*>(stage + lrow * OPF + c16 * 32);
         const float4 hi = *reinterpret_cast<const float4*>(stage + lrow * OPF + c16 * 32 + 16);
-        const uint4 old = *reinterpret_cast<const uint4*>(dst);
         uint4 pk;
-        pk.x = pack_bf2(lo.x + bf_lo(old.x), lo.y + bf_hi(old.x));
-        pk.y = pack_bf2(lo.z + bf_lo(old.y), lo.w + bf_hi(old.y));
-        pk.z = pack_bf2(hi.x + bf_lo(old.z), hi.y + bf_hi(old.z));
-        pk.w = pack_bf2(hi.z + bf_lo(old.w), hi.w + bf_hi(old.w));
+        pk.x = pack_bf2(lo.x + bf_lo(old[k].x), lo.y + bf_hi(old[k].x));
+        pk.y = pack_bf2(lo.z + bf_lo(old[k].y), lo.w + bf_hi(old[k].y));
+        pk.z = pack_bf2(hi.x + bf_lo(old[k].z), hi.y + bf_hi(old[k].z));
+        pk.w = pack_bf2(hi.z + bf_lo(old[k].w), hi.w + bf_hi(old[k].w));
         *reinterpret_cast<uint4*>(dst) = pk;
       }
     }
