@@ -1190,8 +1190,8 @@ __global__ __launch_bounds__(256) void dw_slide_kernel(const T* __restrict__ x, 
     for (int o = 0; o < WS; ++o)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[o][e] = 0.f;
-#pragma unroll 1
-    for (int r = 0; r < K; ++r) {      // one filter row at a time bounds the registers
+#pragma unroll(K == 3 ? 3 : 1)
+    for (int r = 0; r < K; ++r) {      // 5x5 and 7x7: one filter row at a time bounds the registers
       const int h = p * STRIDE + r - pad;
       const bool row_ok = (unsigned)h < (unsigned)H;
       const unsigned rowoff = (unsigned)((n * H + h) * W + w0) * (unsigned)ncv + (unsigned)cv;
