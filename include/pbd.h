@@ -194,6 +194,15 @@ int pbd_distill_arch_step(pbd_ctx* ctx, const float* x_dev, float lr_alpha, floa
 int pbd_pipeline_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
 int pbd_pipeline_flush(pbd_ctx* ctx, float* losses_dev);
 
+/* Order in which pbd_pipeline_step captures its B+1 independent branches into the graph: a permutation of
+ * 0..B, where b < B is student block b (from 0) and B is the teacher's relay (Sec. IV-B: no block depends
+ * on another, so every order computes the same bits).  The order decides how the replayed branches share
+ * the GPU's hardware queues and moves the step time by a few per cent; the best one depends on the
+ * workload, so a caller times a few and keeps the fastest.  Default: 0, 1, .., B.  n must be B+1
+ * (PBD_EINVAL otherwise, also for a non-permutation); PBD_ESTATE while a batch waits.  Host-only apart
+ * from a wait for the stream when a captured graph has to go. */
+int pbd_set_pipeline_order(pbd_ctx* ctx, const int32_t* order, int32_t n);
+
 /* Architecture parameters of student block b (from 0), op index op (a type-4 op with n inputs).
  * pbd_load_alpha copies n float32 from host and sets p = softmax(alpha); momentum is kept.
  * pbd_read_alpha copies alpha (PBD_PARAM), its last gradient (PBD_GRAD), its momentum (PBD_MOMENTUM)

@@ -22,7 +22,7 @@ STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
 
 SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
            "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
-           "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_distill_step", "pbd_pipeline_step", "pbd_pipeline_flush", "pbd_uses_graph", "pbd_sync",
+           "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_distill_step", "pbd_pipeline_step", "pbd_pipeline_flush", "pbd_set_pipeline_order", "pbd_uses_graph", "pbd_sync",
            "pbd_arch_step", "pbd_distill_arch_step", "pbd_load_alpha", "pbd_read_alpha",
            "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
 
@@ -82,6 +82,7 @@ def lib():
         L.pbd_distill_arch_step.argtypes = L.pbd_distill_step.argtypes
         L.pbd_pipeline_step.argtypes = L.pbd_distill_step.argtypes
         L.pbd_pipeline_flush.argtypes = [C.c_void_p, C.c_void_p]
+        L.pbd_set_pipeline_order.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.c_int32]
         L.pbd_load_alpha.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
         L.pbd_read_alpha.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, fp, C.c_size_t]
         L.pbd_uses_graph.argtypes = [C.c_void_p]
@@ -205,6 +206,11 @@ class Distiller:
 
     def pipeline_flush(self):
         self._check(lib().pbd_pipeline_flush(self.h, self.losses.data_ptr()))
+
+    def set_pipeline_order(self, order):
+        """Capture order of the pipelined step's branches: a permutation of 0..B (B = the teacher)."""
+        arr = (C.c_int32 * len(order))(*order)
+        self._check(lib().pbd_set_pipeline_order(self.h, arr, len(order)))
 
     def arch_step(self, i, lr_alpha, a_prev=None, a_i=None):
         """Architecture round of block i (1-based): alpha trained, weights frozen."""

@@ -144,3 +144,45 @@ def test_full_size_pipelined_steps_equal_whole_steps():
     a, b = _state(plain, wl), _state(piped, wl)
     for key in a:
         assert np.array_equal(a[key], b[key]), key
+
+
+def test_capture_order_of_the_branches_changes_no_bit():
+    """The branches of the pipelined step are independent (Sec. IV-B): whatever order they are captured in,
+    the losses and the trained state are the same bits."""
+    wl = pattern_workloads()[0]
+    k = 3
+    xs = _batches(wl, k)
+    ref = None
+    B = wl.B
+    for order in (None, list(range(B, -1, -1)), [B] + list(range(B)), list(range(B - 1, -1, -1)) + [B]):
+        d = _distiller(wl, "bf16")
+        if order is not None:
+            d.set_pipeline_order(order)
+        losses = []
+        for s, x in enumerate(xs):
+            d.pipeline_step(x, wl.lr)
+            d.sync()
+            if s:
+                losses.append(d.losses.cpu().numpy().copy())
+            if s == 0 and order is not None:
+                with pytest.raises(pbd.PbdError):      # not while a batch waits
+                    d.set_pipeline_order(order)
+        d.pipeline_flush(); d.sync()
+        losses.append(d.losses.cpu().numpy().copy())
+        assert d.uses_graph()
+        got = (np.array(losses), _state(d, wl))
+        if ref is None:
+            ref = got
+        else:
+            assert np.array_equal(got[0], ref[0]), order
+            for key in ref[1]:
+                assert np.array_equal(got[1][key], ref[1][key]), (order, key)
+    d = _distiller(wl, "bf16")
+    for bad in ([0] * (B + 1), list(range(B)), list(range(1, B + 2))):
+        with pytest.raises(pbd.PbdError):
+            d.set_pipeline_order(bad)
+    # a new order after graphs exist: captured again, same bits as before
+    d.pipeline_step(xs[0], wl.lr); d.pipeline_step(xs[1], wl.lr); d.pipeline_flush(); d.sync()
+    d.set_pipeline_order(list(range(B, -1, -1)))
+    d.pipeline_step(xs[2], wl.lr); d.pipeline_flush(); d.sync()
+    assert np.array_equal(d.losses.cpu().numpy(), ref[0][-1])
