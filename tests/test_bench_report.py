@@ -58,3 +58,36 @@ def test_more_than_one_gpu_is_refused(monkeypatch, capsys):
         bench.main()
     assert e.value.code == 2
     assert "single-GPU" in capsys.readouterr().err
+
+
+def test_capture_order_tuning_keeps_the_fastest_permutation():
+    """The tuner tries permutations of the B+1 branches only, always from an empty pipeline, and leaves
+    the fastest one set."""
+    import time
+    from types import SimpleNamespace
+
+    class FakeDistiller:
+        def __init__(self, slow_unless):
+            self.order, self.pending, self.tried, self.fast = None, False, [], slow_unless
+
+        def set_pipeline_order(self, order):
+            assert not self.pending
+            self.order = list(order)
+            self.tried.append(self.order)
+
+        def pipeline_step(self, x, lr):
+            self.pending = True
+            if self.order != self.fast:
+                time.sleep(0.0005)
+
+        def pipeline_flush(self):
+            self.pending = False
+
+    wl = SimpleNamespace(B=4, lr=0.1)
+    torch = SimpleNamespace(cuda=SimpleNamespace(synchronize=lambda: None))
+    d = FakeDistiller(slow_unless=[1, 0, 2, 3, 4])
+    best = bench.tune_pipeline_order(d, None, wl, torch, tries=10)
+    assert best == [1, 0, 2, 3, 4] == d.order and not d.pending
+    assert d.tried[0] == [0, 1, 2, 3, 4]                       # the default is among the candidates
+    assert all(sorted(o) == [0, 1, 2, 3, 4] for o in d.tried)
+    assert len({tuple(o) for o in d.tried[:-1]}) == len(d.tried) - 1 == wl.B + 3
