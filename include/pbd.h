@@ -190,7 +190,8 @@ int pbd_distill_arch_step(pbd_ctx* ctx, const float* x_dev, float lr_alpha, floa
  * bit for bit, as K calls of pbd_distill_step on the same batches.  x_dev is consumed by the call (it is
  * cast into the store).  Graph capture as for pbd_distill_step (one graph per copy).  While a batch waits,
  * the one-step calls (relay, prefix, student, architecture and whole steps) return PBD_ESTATE, the views
- * and pbd_read_act show the waiting batch, and pbd_read_value has nothing to show until the flush. */
+ * and pbd_read_act show the waiting batch, and pbd_read_value has nothing to show until the flush.
+ * Parameters loaded while a batch waits are the ones its students then train from. */
 int pbd_pipeline_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
 int pbd_pipeline_flush(pbd_ctx* ctx, float* losses_dev);
 
