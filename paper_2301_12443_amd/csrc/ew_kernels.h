@@ -1050,17 +1050,34 @@ __global__ void cast_params_kernel(const float* __restrict__ w, bf16_t* __restri
 // Transposed weight copies for backward-data: src [K][RS][C] -> dst [C][RS][K].
 struct TransposeEntry { long src, dst; int K, RS, C; };
 template <class T>
-__global__ void transpose_weights_kernel(const T* __restrict__ wc, T* __restrict__ wt,
-                                         const TransposeEntry* __restrict__ table) {
+__global__ __launch_bounds__(256) void transpose_weights_kernel(const T* __restrict__ wc, T* __restrict__ wt,
+                                                                const TransposeEntry* __restrict__ table) {
+  // 64 x 64 tiles of one filter tap through LDS: rows of 64 consecutive c are read, rows of 64 consecutive k
+  // written, both whole cache lines per wave
+  __shared__ T tile[64][65];
   const TransposeEntry e = table[blockIdx.y];
-  const long n = (long)e.K * e.RS * e.C;
-  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
-    // i enumerates the destination so that stores are contiguous
-    const int k = (int)(i % e.K);
-    const long t = i / e.K;
-    const int rs = (int)(t % e.RS);
-    const int c = (int)(t / e.RS);
-    wt[e.dst + i] = wc[e.src + ((long)k * e.RS + rs) * e.C + c];
+  const int tk = (e.K + 63) / 64, tc = (e.C + 63) / 64;
+  const long ntiles = (long)tk * tc * e.RS;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (long t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const int k0 = (int)(t % tk) * 64;
+    const long r = t / tk;
+    const int c0 = (int)(r % tc) * 64, rs = (int)(r / tc);
+    T v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {                  // all sixteen loads in flight
+      const int k = k0 + ty + 4 * j, c = c0 + tx;
+      v[j] = (k < e.K && c < e.C) ? wc[e.src + ((long)k * e.RS + rs) * e.C + c] : T(0);
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) tile[ty + 4 * j][tx] = v[j];
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int c = c0 + ty + 4 * j, k = k0 + tx;
+      if (k < e.K && c < e.C) wt[e.dst + ((long)c * e.RS + rs) * e.K + k] = tile[tx][ty + 4 * j];
+    }
+    __syncthreads();
   }
 }
 
