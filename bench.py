@@ -26,8 +26,8 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # the figures are carried here and apply to the workload they were measured on only.
 HBM_TRAFFIC_PER_LAUNCH = {
     "vgg16_dsconv": {
-        "bn_bwd_reduce": 30547082, "bn_bwd_apply": 45063308, "bn_apply": 30135871, "bn_stats": 12421573,
-        "dw_wgrad_tile_k3": 27366745, "sum_partials": 7974621, "bn_small_bwd": 7994394, "bn_small_fwd": 5250497,
+        "bn_bwd_reduce": 30546058, "bn_bwd_apply": 45063308, "bn_apply": 30114369, "bn_stats": 12422596,
+        "dw_wgrad_tile_k3": 27355086, "sum_partials": 7972637, "bn_small_bwd": 7983131, "bn_small_fwd": 5250496,
     },
 }
 
