@@ -21,15 +21,63 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 
 # HBM bytes per launch (mean over a kernel class's launches in one step) from rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE runs of this script, each scaled by what the same counter reads for a
-# 256 MiB copy (fetch x2.000, write x1.000); commands and the full table are in
-# profiles/vgg16_dsconv_step_hbm_traffic.md.  Counters cannot be read from inside the process, so
-# the figures are carried here and apply to the workload they were measured on only.
+# 256 MiB copy (fetch x2.000, write x1.000).  Counters cannot be read from inside the process: the
+# figures are CARRIED from the counter runs whose commands and full tables are in the named file
+# under profiles/ (the record says so under roofline.traffic_source), and apply only to the workload
+# and the kernel build they were measured on.
 HBM_TRAFFIC_PER_LAUNCH = {
-    "vgg16_dsconv": {
+    "vgg16_dsconv": ("profiles/vgg16_dsconv_step_hbm_traffic.md", {
         "bn_bwd_reduce": 30546058, "bn_bwd_apply": 45063308, "bn_apply": 30114369, "bn_stats": 12422596,
         "dw_wgrad_tile_k3": 27355086, "sum_partials": 7972637, "bn_small_bwd": 7983131, "bn_small_fwd": 5250496,
-    },
+    }),
 }
+
+# Batch of the oracle's timed step per configuration: the direct-loop CPU oracle at the full batch of the
+# 224 x 224 configurations would take many minutes, so it is timed at a reduced batch on the same graph and
+# image size (its samples/s do not depend on the batch to first order: every loop is linear in it).
+CPU_BASELINE_BATCH = {"tiny_cnn": 8, "vgg16_dsconv": 256, "mbv2_mbconv_k5e4": 8, "mbv2_supernet": 2, "resnet50_x1.5": 2}
+
+CONV_PREFIXES = ("igemm_", "wgrad_")
+# the bandwidth-bound families: normalisation, depthwise, joins, pooling, loss, update, casts, partial sums
+EW_PREFIXES = ("bn_", "dw_", "join_", "maxpool_", "mse_", "sgd_", "cast_", "sum_partials", "splitk_", "transpose_", "mix_")
+
+
+def family_fractions(prof, steps):
+    """The two halves of the metric besides samples/s: the convolutions (implicit GEMM forward / backward-data
+    and backward-weight launches) as a time-weighted TFLOP/s against the bf16 MFMA peak, and the bandwidth-bound
+    families (normalisation, depthwise, joins, pooling, loss, update) as GB/s of algorithmic bytes against the
+    HBM peak.  Convolutions are given three ways: all launches, those whose own arithmetic intensity is above
+    the MFMA ridge (the matrix-core-bound ones, which the 50 % target is about) and those below it (bandwidth-
+    bound 1x1 layers and stems, as GB/s)."""
+    ridge = PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    acc = {k: dict(ms=0.0, bytes=0.0, flops=0.0, n=0) for k in ("conv", "conv_hi", "conv_lo", "ew")}
+    for p in prof:
+        keys = []
+        if p["name"].startswith(CONV_PREFIXES):
+            keys = ["conv", "conv_hi" if p["bytes"] and p["flops"] / p["bytes"] >= ridge else "conv_lo"]
+        elif p["name"].startswith(EW_PREFIXES):
+            keys = ["ew"]
+        for k in keys:
+            a = acc[k]
+            a["ms"] += p["ms"]; a["bytes"] += p["bytes"]; a["flops"] += p["flops"]; a["n"] += 1
+
+    def tf(a):
+        return a["flops"] / (a["ms"] * 1e-3) / 1e12 if a["ms"] else 0.0
+
+    def gb(a):
+        return a["bytes"] / (a["ms"] * 1e-3) / 1e9 if a["ms"] else 0.0
+
+    def conv_entry(a):
+        return dict(ms_per_step=round(a["ms"] / steps, 4), launches_per_step=a["n"] // steps,
+                    TFLOPs=round(tf(a), 2), frac_of_mfma_peak=round(tf(a) / PEAK_BF16_TFLOPS, 4),
+                    GBs=round(gb(a), 1), frac_of_hbm_peak=round(gb(a) / PEAK_HBM_GBS, 4))
+    conv = conv_entry(acc["conv"])
+    conv["above_ridge"] = conv_entry(acc["conv_hi"])
+    conv["below_ridge"] = conv_entry(acc["conv_lo"])
+    e = acc["ew"]
+    ew = dict(ms_per_step=round(e["ms"] / steps, 4), launches_per_step=e["n"] // steps, GBs=round(gb(e), 1),
+              frac_of_hbm_peak=round(gb(e) / PEAK_HBM_GBS, 4))
+    return conv, ew
 
 
 def roofline_from_profile(prof, steps):
@@ -102,29 +150,35 @@ def measure_peaks(torch):
 
 
 def cpu_baseline(wl):
-    """The oracle as it stands (fp32 instance, OpenMP), timed on the host cores on the same workload."""
+    """The oracle as it stands (fp32 instance, OpenMP), timed on the host cores on the same graph and image
+    size; at the full batch where that takes seconds, else at the reduced batch of CPU_BASELINE_BATCH."""
     from oracle import pbd_oracle as orc
     from paper_2301_12443_amd import workloads as W
+    batch = min(wl.batch, CPU_BASELINE_BATCH.get(wl.name, wl.batch))
     words, pool = W.pack(wl)
-    o = orc.Oracle(words, pool, wl.batch, precision=32, momentum=wl.momentum)
+    o = orc.Oracle(words, pool, batch, precision=32, momentum=wl.momentum)
     for net, b, j, slot, arr in W.iter_params(wl):
         o.set_param(net, b, j, slot, arr)
-    x = W.make_input(wl)
+    x = W.make_input(wl, batch=batch)
     o.relay_step(x, wl.lr)                      # first-touch
     t0 = time.time()
     n = 2
     for _ in range(n):
         o.relay_step(x, wl.lr)
     dt = (time.time() - t0) / n
-    return dict(value=round(wl.batch / dt, 1), unit="samples/s", cores=orc.num_threads(), kind="oracle",
-                sample=f"fp32 oracle relay_step, full batch {wl.batch}, mean of {n} steps after 1 warm-up")
+    what = f"full batch {batch}" if batch == wl.batch else f"batch {batch} of the configured {wl.batch} (same graph, same {wl.in_shape[1]} x {wl.in_shape[2]} images)"
+    return dict(value=round(batch / dt, 2), unit="samples/s", cores=orc.num_threads(), kind="oracle",
+                sample=f"fp32 oracle relay_step, {what}, mean of {n} steps after 1 warm-up, {dt:.2f} s per step")
 
 
-def tune_pipeline_order(d, x, wl, torch, tries=20):
+W_NAMES = ("tiny_cnn", "vgg16_dsconv", "mbv2_mbconv_k5e4", "mbv2_supernet", "resnet50_x1.5")
+
+
+def tune_pipeline_order(d, x, wl, torch, tries=None):
     """Untimed, before the warm-up: the B+1 branches of the pipelined step are independent, so the order in
     which they are captured changes no result, only how the replayed graph shares the hardware queues.  A few
     orders (each student block first, the students in reverse, the teacher first) are timed over `tries`
-    steps each and the fastest is kept."""
+    steps each and the fastest is kept.  tries=None: as many steps as fit in about 0.3 s, between 5 and 20."""
     B = wl.B
     base = list(range(B))
     cands = [base + [B]] + [[b] + [v for v in base if v != b] + [B] for b in range(1, B)]
@@ -132,10 +186,13 @@ def tune_pipeline_order(d, x, wl, torch, tries=20):
     best = None
     for order in cands:
         d.set_pipeline_order(order)
+        t0 = time.perf_counter()
         for _ in range(3):
             d.pipeline_step(x, wl.lr)
         d.pipeline_flush()
         torch.cuda.synchronize()
+        if tries is None:       # (the first three steps include the capture: an upper bound of the step time)
+            tries = max(5, min(20, int(0.3 / max((time.perf_counter() - t0) / 3, 1e-6))))
         t0 = time.perf_counter()
         for _ in range(tries):
             d.pipeline_step(x, wl.lr)
@@ -153,7 +210,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", default="vgg16_dsconv")
+    ap.add_argument("--config", default="resnet50_x1.5", choices=sorted(W_NAMES),
+                    help="workload; the default is the largest single-GPU configuration (ResNet-50 -> x1.5 inner widths, "
+                         "batch 256, 224 x 224, bf16)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--mode", choices=["pipelined", "relay", "redundant", "arch", "two_round"], default="pipelined",
                     help="pipelined: pbd_pipeline_step, the whole step with the teacher's relay of batch k+1 running "
@@ -222,6 +281,24 @@ def main():
     losses = d.losses.cpu().numpy()
     assert all(l == l and l > 0 for l in losses), losses
 
+    # One step at a time: median over pbd_distill_step calls, each bracketed by two HIP events recorded on the
+    # library's own stream (the stream its kernels run on), beside the mean of the pipelined steps above.
+    one_step = None
+    if args.mode in ("pipelined", "relay"):
+        nev = max(20, min(args.steps, 50))
+        for _ in range(3):
+            d.distill_step(x, wl.lr)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nev)]
+        for e0, e1 in evs:
+            e0.record(d._stream)
+            d.distill_step(x, wl.lr)
+            e1.record(d._stream)
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+        med = ms[len(ms) // 2]
+        one_step = dict(call="pbd_distill_step", timed_calls=nev, median_ms=round(med, 4), min_ms=round(ms[0], 4),
+                        samples_per_s=round(wl.batch / (med * 1e-3), 1), timer="HIP events on the library's stream")
+
     # per-kernel timings with HIP events on the library's stream (separate, profiled steps)
     psteps = 20
     d.set_profile(True); d.reset_profile()
@@ -233,8 +310,11 @@ def main():
     prof = d.get_profile()
     d.set_profile(False)
     roof, classes, totals = roofline_from_profile(prof, psteps)
-    if roof["launches_per_step"] == roof["class_launches_per_step"]:   # the counters were averaged over the whole class
-        roof["traffic"] = HBM_TRAFFIC_PER_LAUNCH.get(args.config, {}).get(roof["kernel"])
+    conv, elementwise = family_fractions(prof, psteps)
+    src, table = HBM_TRAFFIC_PER_LAUNCH.get(args.config, (None, {}))
+    if roof["kernel"] in table and roof["launches_per_step"] == roof["class_launches_per_step"]:
+        roof["traffic"] = table[roof["kernel"]]          # counters were averaged over the whole class
+        roof["traffic_source"] = f"carried from the rocprofv3 --pmc runs recorded in {src}, not measured in this run"
     if args.classes:
         for k, v in classes.items():
             print(f"{k:24s} {v}", file=sys.stderr)
@@ -247,7 +327,7 @@ def main():
         torch.cuda.synchronize()
 
     rec = {
-        "metric": {"pipelined": "distillation samples/sec/GPU (full relay step)",
+        "metric": {"pipelined": "distillation samples/sec/GPU (full relay step) + % MFMA peak on convs",
                    "relay": "distillation samples/sec/GPU (full relay step, one step at a time)",
                    "redundant": "distillation samples/sec/GPU (teacher re-run per block, no relay; direct launches)",
                    "arch": "distillation samples/sec/GPU (relay + architecture round only)",
@@ -265,7 +345,13 @@ def main():
                                   "timed from an empty pipeline to an empty pipeline" if args.mode == "pipelined" else ""),
                    "lr": wl.lr, **({"pipeline_order": order} if order else {})},
         "roofline": roof,
+        # the metric's second half: convolutions against the bf16 MFMA peak, and the bandwidth-bound
+        # families against the HBM peak (time-weighted over the profiled steps' launches)
+        "conv": conv,
+        "elementwise": elementwise,
     }
+    if one_step:
+        rec["one_step"] = one_step
     # step level: unfused algorithmic bytes and flops of one step over the measured step time (how far
     # the whole step is from moving its tensors once at the HBM peak / doing its MACs at the MFMA peak)
     step_s = dt / args.steps

@@ -191,7 +191,11 @@ int pbd_distill_arch_step(pbd_ctx* ctx, const float* x_dev, float lr_alpha, floa
  * cast into the store).  Graph capture as for pbd_distill_step (one graph per copy).  While a batch waits,
  * the one-step calls (relay, prefix, student, architecture and whole steps) return PBD_ESTATE, the views
  * and pbd_read_act show the waiting batch, and pbd_read_value has nothing to show until the flush.
- * Parameters loaded while a batch waits are the ones its students then train from. */
+ * Parameters loaded while a batch waits are the ones its students then train from.
+ * Which learning rate trains which batch: the one handed in WITH that batch, one call later.
+ *     pbd_pipeline_step(ctx, x0, lr0, L);   // relays x0; no student work; L untouched
+ *     pbd_pipeline_step(ctx, x1, lr1, L);   // relays x1; students train on x0 with lr0; L = losses of x0
+ *     pbd_pipeline_flush(ctx, L);           // students train on x1 with lr1; L = losses of x1 */
 int pbd_pipeline_step(pbd_ctx* ctx, const float* x_dev, float lr, float* losses_dev);
 int pbd_pipeline_flush(pbd_ctx* ctx, float* losses_dev);
 

@@ -420,6 +420,8 @@ struct NetBase {
   virtual long value_numel(int b, int v) = 0;
   virtual double kink_margin(int b) = 0;
   virtual void get_value(int b, int v, double* out) = 0;
+  virtual long saved_numel(int b, int j, int which) = 0;
+  virtual void get_saved(int b, int j, int which, double* out) = 0;
   virtual int set_alpha(int b, int j, const double* a, int n) = 0;
   virtual int get_alpha(int kind, int b, int j, double* out, int n) = 0;
   virtual void relay_arch_step(const double* x, double lr, double* losses) = 0;
@@ -874,6 +876,22 @@ struct Net final : NetBase {
   void get_value(int b, int v, double* out) override {
     for (size_t k = 0; k < val[b][v].size(); ++k) out[k] = (double)val[b][v][k];
   }
+  // read-only view of what the last forward of student block b kept for op j.  which 0: the
+  // convolution's output, 1: the normalised tensor before the activation (the sum, for an add),
+  // 2: batch mean, 3: biased batch variance
+  const std::vector<R>* saved_ref(int b, int j, int which) {
+    if (b < 0 || b >= d.B || j < 0 || j >= (int)saved[b].size()) return nullptr;
+    const Saved& s = saved[b][j];
+    return which == 0 ? &s.conv : which == 1 ? &s.pre : which == 2 ? &s.mean : which == 3 ? &s.var : nullptr;
+  }
+  long saved_numel(int b, int j, int which) override {
+    const std::vector<R>* t = saved_ref(b, j, which);
+    return t ? (long)t->size() : -1;
+  }
+  void get_saved(int b, int j, int which, double* out) override {
+    const std::vector<R>* t = saved_ref(b, j, which);
+    if (t) for (size_t k = 0; k < t->size(); ++k) out[k] = (double)(*t)[k];
+  }
 };
 
 }  // namespace
@@ -924,6 +942,12 @@ int orc_get_alpha(void* h, int kind, int b, int j, double* out, int n) {
 double orc_kink_margin(void* h, int b) { return static_cast<NetBase*>(h)->kink_margin(b); }
 long orc_value_numel(void* h, int b, int v) { return static_cast<NetBase*>(h)->value_numel(b, v); }
 void orc_get_value(void* h, int b, int v, double* out) { static_cast<NetBase*>(h)->get_value(b, v, out); }
+long orc_saved_numel(void* h, int b, int j, int which) { return static_cast<NetBase*>(h)->saved_numel(b, j, which); }
+void orc_get_saved(void* h, int b, int j, int which, double* out) { static_cast<NetBase*>(h)->get_saved(b, j, which, out); }
+// the storage rounding of the bf16 mode on its own, so that it can be pinned against a library conversion
+void orc_round_bf16(const double* in, double* out, long n) {
+  for (long i = 0; i < n; ++i) out[i] = round_bf16(in[i]);
+}
 int orc_num_threads() {
 #ifdef _OPENMP
   return omp_get_max_threads();

@@ -63,6 +63,10 @@ def lib():
         L.orc_value_numel.restype = C.c_long
         L.orc_value_numel.argtypes = [C.c_void_p, C.c_int, C.c_int]
         L.orc_get_value.argtypes = [C.c_void_p, C.c_int, C.c_int, _dp]
+        L.orc_saved_numel.restype = C.c_long
+        L.orc_saved_numel.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
+        L.orc_get_saved.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, _dp]
+        L.orc_round_bf16.argtypes = [_dp, _dp, C.c_long]
         L.orc_kink_margin.restype = C.c_double
         L.orc_kink_margin.argtypes = [C.c_void_p, C.c_int]
         L.orc_num_threads.restype = C.c_int
@@ -94,6 +98,14 @@ def _f64(a):
 
 def num_threads() -> int:
     return lib().orc_num_threads()
+
+
+def round_bf16(a):
+    """The bf16 mode's storage rounding (nearest even, through float32), elementwise."""
+    a = _f64(a)
+    out = np.empty_like(a)
+    lib().orc_round_bf16(_d(a), _d(out), a.size)
+    return out
 
 
 # --------------------------------------------------------------------------
@@ -299,6 +311,18 @@ class Oracle:
     def kink_margin(self, b):
         """Smallest distance of block b's last forward from a ReLU / ReLU6 / max-pool kink."""
         return lib().orc_kink_margin(self.h, b)
+
+    SAVED_CONV, SAVED_PRE, SAVED_MEAN, SAVED_VAR = 0, 1, 2, 3
+
+    def saved(self, b, j, which):
+        """What the last forward of student block b kept for op j: the convolution output, the tensor
+        before the activation, the batch mean or the biased batch variance."""
+        n = lib().orc_saved_numel(self.h, b, j, which)
+        if n < 0:
+            raise ValueError("no such saved tensor")
+        out = np.empty(n)
+        lib().orc_get_saved(self.h, b, j, which, _d(out))
+        return out
 
     def value(self, b, v):
         n = lib().orc_value_numel(self.h, b, v)

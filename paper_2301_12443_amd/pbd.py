@@ -174,9 +174,29 @@ class Distiller:
         self._check(lib().pbd_read_value(self.h, b, v, _fp(out), out.size))
         return out.reshape(shape)
 
+    def _check_x(self, x_dev):
+        """The C ABI takes a bare device pointer for x and reads batch * C0 * H0 * W0 float32 from it, so
+        everything it cannot check is checked here, before any launch: a float32, contiguous tensor of shape
+        (batch, C0, H0, W0) on the device the context is bound to."""
+        import torch
+        if self._ws is None:
+            raise PbdError(-4, "no workspace bound (call bind first)")
+        want = (self.batch, *self.wl.in_shape)
+        if not isinstance(x_dev, torch.Tensor):
+            raise PbdError(-1, f"x must be a torch tensor, got {type(x_dev).__name__}")
+        if x_dev.dtype != torch.float32:
+            raise PbdError(-1, f"x must be float32, got {x_dev.dtype}")
+        if tuple(x_dev.shape) != want:
+            raise PbdError(-2, f"x must have shape {want}, got {tuple(x_dev.shape)}")
+        if not x_dev.is_contiguous():
+            raise PbdError(-1, "x must be contiguous (NCHW)")
+        if not x_dev.is_cuda or x_dev.device != self._ws.device:
+            raise PbdError(-1, f"x must live on {self._ws.device}, got {x_dev.device}")
+        return x_dev.data_ptr()
+
     def teacher_relay(self, x_dev):
         """x_dev: float32 NCHW CUDA tensor.  Returns the B+1 borrowed views A_0..A_B."""
-        assert x_dev.is_cuda and x_dev.dtype.is_floating_point and x_dev.is_contiguous()
+        self._check_x(x_dev)
         views = (pbd_tensor * (self.B + 1))()
         self._check(lib().pbd_teacher_relay(self.h, x_dev.data_ptr(), views))
         self.views = views
@@ -184,7 +204,7 @@ class Distiller:
 
     def teacher_prefix(self, x_dev, upto):
         """The teacher without relaying: T_1..T_upto from x.  Returns the views A_0..A_upto."""
-        assert x_dev.is_cuda and x_dev.dtype.is_floating_point and x_dev.is_contiguous()
+        self._check_x(x_dev)
         views = (pbd_tensor * (self.B + 1))()
         self._check(lib().pbd_teacher_prefix(self.h, x_dev.data_ptr(), upto, views))
         self.views = views
@@ -198,11 +218,11 @@ class Distiller:
                                            self.losses.data_ptr() + 4 * (i - 1)))
 
     def distill_step(self, x_dev, lr):
-        self._check(lib().pbd_distill_step(self.h, x_dev.data_ptr(), lr, self.losses.data_ptr()))
+        self._check(lib().pbd_distill_step(self.h, self._check_x(x_dev), lr, self.losses.data_ptr()))
 
     def pipeline_step(self, x_dev, lr):
         """Hand in a batch: the teacher relays it while the students train on the batch before."""
-        self._check(lib().pbd_pipeline_step(self.h, x_dev.data_ptr(), lr, self.losses.data_ptr()))
+        self._check(lib().pbd_pipeline_step(self.h, self._check_x(x_dev), lr, self.losses.data_ptr()))
 
     def pipeline_flush(self):
         self._check(lib().pbd_pipeline_flush(self.h, self.losses.data_ptr()))
@@ -220,7 +240,7 @@ class Distiller:
                                         self.losses.data_ptr() + 4 * (i - 1)))
 
     def distill_arch_step(self, x_dev, lr_alpha):
-        self._check(lib().pbd_distill_arch_step(self.h, x_dev.data_ptr(), lr_alpha, self.losses.data_ptr()))
+        self._check(lib().pbd_distill_arch_step(self.h, self._check_x(x_dev), lr_alpha, self.losses.data_ptr()))
 
     def load_alpha(self, b, j, alpha):
         a = np.ascontiguousarray(alpha, dtype=np.float32).ravel()

@@ -16,7 +16,7 @@ def make_distiller(wl, batch=None, precision=None, force_direct=False):
 
 
 def compare_step(wl, batch=None, precision=None, force_direct=False, steps=1, order=None, log=None,
-                 storage=None, kink_floor=0.0, beta_shift=None, noise=False):
+                 storage=None, kink_floor=0.0, beta_shift=None, noise=False, gamma=None):
     """Returns {name: error} for activations, losses, gradients, weights, momentum, running stats.
 
     noise=True (with a storage-rounded oracle): also steps a plain fp64 oracle and reports, as
@@ -27,14 +27,16 @@ def compare_step(wl, batch=None, precision=None, force_direct=False, steps=1, or
     o = make_oracle(wl, batch=batch, storage=storage)
     o64 = make_oracle(wl, batch=batch) if noise else None
     assert not (noise and (kink_floor or beta_shift is not None))
-    if beta_shift is not None:
-        # move every student pre-activation away from the rectifier kinks (same on both sides)
+    if beta_shift is not None or gamma is not None:
+        # move every student pre-activation away from the rectifier kinks (same on both sides):
+        # pre-activations are gamma * x-hat + beta, i.e. ~ N(beta_shift, gamma^2) per channel
         for b in range(wl.B):
             for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
-                if slot == W.P_BETA:
-                    beta = np.full(shape, beta_shift, dtype=np.float32)
-                    o.set_param(W.NET_STUDENT, b, j, slot, beta)
-                    d.load_param(W.NET_STUDENT, b, j, slot, beta)
+                fill = beta_shift if slot == W.P_BETA else gamma if slot == W.P_GAMMA else None
+                if fill is not None:
+                    arr = np.full(shape, fill, dtype=np.float32)
+                    o.set_param(W.NET_STUDENT, b, j, slot, arr)
+                    d.load_param(W.NET_STUDENT, b, j, slot, arr)
     errs = {}
     for step in range(steps):
         x = W.make_input(wl, batch=batch, step=step)

@@ -91,3 +91,34 @@ def test_workspace_sizes_and_unbound_calls():
     assert b"pbd_bind" in pbd.lib().pbd_last_error(d.h)
     assert pbd.lib().pbd_distill_step(d.h, None, 0.1, None) == -4
     assert pbd.lib().pbd_sync(None) == -1
+
+
+def test_binding_rejects_a_wrong_input_tensor_before_any_launch():
+    """The ABI carries no size for x_dev (a bare device pointer to batch x C0 x H0 x W0 float32), so the
+    binding checks dtype, shape, device and contiguity itself and raises before the library is called."""
+    import torch
+    wl = W.tiny_cnn()
+    d = pbd.Distiller(wl)
+    with pytest.raises(pbd.PbdError, match="PBD_ESTATE"):
+        d.distill_step(torch.zeros(8, 3, 32, 32), wl.lr)
+    d._ws = torch.empty(1, dtype=torch.uint8)        # stands in for a bound workspace (no GPU here)
+    d.losses = torch.zeros(wl.B)
+    good = torch.zeros(wl.batch, *wl.in_shape, dtype=torch.float32)
+    calls = [lambda x: d.teacher_relay(x), lambda x: d.teacher_prefix(x, 1), lambda x: d.distill_step(x, wl.lr),
+             lambda x: d.pipeline_step(x, wl.lr), lambda x: d.distill_arch_step(x, 0.01)]
+    for call in calls:
+        with pytest.raises(pbd.PbdError, match="float32"):
+            call(good.to(torch.bfloat16))
+        with pytest.raises(pbd.PbdError, match="float32"):
+            call(good.double())
+        with pytest.raises(pbd.PbdError, match="shape"):
+            call(good[:4])
+        with pytest.raises(pbd.PbdError, match="shape"):
+            call(good.reshape(wl.batch, -1))
+        with pytest.raises(pbd.PbdError, match="contiguous"):
+            call(torch.zeros(wl.batch, wl.in_shape[0], wl.in_shape[1], 2 * wl.in_shape[2])[..., ::2])
+        with pytest.raises(pbd.PbdError, match="must live on"):
+            call(good)                                # a host tensor
+        with pytest.raises(pbd.PbdError, match="torch tensor"):
+            call(np.zeros((wl.batch, *wl.in_shape), dtype=np.float32))
+    d._ws = None

@@ -91,3 +91,24 @@ def test_capture_order_tuning_keeps_the_fastest_permutation():
     assert d.tried[0] == [0, 1, 2, 3, 4]                       # the default is among the candidates
     assert all(sorted(o) == [0, 1, 2, 3, 4] for o in d.tried)
     assert len({tuple(o) for o in d.tried[:-1]}) == len(d.tried) - 1 == wl.B + 3
+
+
+def test_family_fractions_split_convolutions_at_the_ridge():
+    """The metric's second half: convolutions against the MFMA peak (all launches, and those above / below
+    the ridge), bandwidth-bound families against the HBM peak; time-weighted, per step."""
+    ridge = bench.PEAK_BF16_TFLOPS * 1e12 / (bench.PEAK_HBM_GBS * 1e9)
+    hi = _entry("igemm_fwd_128x128_store", 0.200, 100e6, 100e6 * ridge * 4)
+    lo = _entry("wgrad_128x128", 0.100, 400e6, 400e6 * ridge / 4)
+    bn = _entry("bn_apply", 0.050, 300e6)
+    dw = _entry("dw_fwd_tile_k5", 0.150, 500e6, 1e9)
+    other = _entry("unknown_kernel", 1.0, 1e6)
+    conv, ew = bench.family_fractions([hi, lo, bn, dw, other] * 2, 2)
+    assert conv["launches_per_step"] == 2 and conv["ms_per_step"] == pytest.approx(0.300)
+    assert conv["TFLOPs"] == pytest.approx((hi["flops"] + lo["flops"]) / 300e-6 / 1e12, rel=1e-3)
+    assert conv["frac_of_mfma_peak"] == pytest.approx(conv["TFLOPs"] / bench.PEAK_BF16_TFLOPS, abs=1e-4)
+    assert conv["above_ridge"]["launches_per_step"] == 1
+    assert conv["above_ridge"]["TFLOPs"] == pytest.approx(hi["flops"] / 200e-6 / 1e12, rel=1e-3)
+    assert conv["below_ridge"]["GBs"] == pytest.approx(400e6 / 100e-6 / 1e9, rel=1e-3)
+    assert ew["launches_per_step"] == 2 and ew["ms_per_step"] == pytest.approx(0.200)
+    assert ew["GBs"] == pytest.approx(800e6 / 200e-6 / 1e9, rel=1e-3)
+    assert ew["frac_of_hbm_peak"] == pytest.approx(ew["GBs"] / bench.PEAK_HBM_GBS, abs=1e-4)

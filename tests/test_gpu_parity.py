@@ -67,8 +67,9 @@ def test_f32_path_matches_fp64_oracle(wl):
 
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
 def test_long_columns_take_the_chunked_bn_kernels(precision):
-    """Batch 96 gives the first blocks M = 24576 rows: above the whole-column limit (16384), so the
-    chunked statistics / finalize / apply kernels run, while the later blocks stay below it."""
+    """Batch 96 gives the first two blocks M = 98304 and 24576 rows: above the whole-column limit (4096 rows
+    per channel), so the chunked statistics / finalize / apply kernels run, while the last block (1536 rows)
+    stays below it."""
     wl = W.tiny_cnn()
     if precision == "f32":
         errs = parity.compare_step(wl, batch=96, precision="f32", steps=2, kink_floor=KINK_FLOOR)
