@@ -151,6 +151,20 @@ int pbd_teacher_prefix(pbd_ctx* ctx, const float* x_dev, int32_t upto, pbd_tenso
 int pbd_student_step(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i,
                      float lr, float* loss_dev);
 
+/* pbd_student_step for callers that cannot allocate device memory and do not want a workspace region to be
+ * written as scratch: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results bit for bit.  The block's reduction scratch (partial sums of the loss, of the
+ * batch-norm statistics and of the weight gradients, split-K partial tiles) is a 16 MiB static device array
+ * inside the library instead of the workspace's scratch region; a block that needs more returns
+ * PBD_ENOMEM_WS and launches nothing (pbd_student_step has no such limit).  The call allocates nothing on the
+ * device or through HIP (no hipMalloc / hipFree, no events, no graph): it only launches kernels on the bound
+ * stream; profiling must be off (PBD_ESTATE otherwise).  Each GPU holds one copy of the array until the
+ * process ends and every call on that GPU shares it: calls that may overlap on one GPU (two contexts, two
+ * streams) race, so order them.  Nothing in it has to start at zero (every partial result is written before
+ * it is read), so the contents a previous call left behind are harmless. */
+int pbd_student_step_static(pbd_ctx* ctx, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i,
+                            float lr, float* loss_dev);
+
 /* The whole step: relay, then every student block; no teacher block runs twice.
  * losses_dev: device float32[B].  Same results as the two calls above.  When the bound
  * stream is a real (non-null) stream and profiling is off, the body of the step is

@@ -25,7 +25,32 @@
 
 using namespace pbd;
 
+// Reduction scratch of pbd_student_step_static: partial sums of the loss, of the batch-norm statistics and of
+// the weight gradients, and split-K partial tiles.  One copy per GPU, held until the process ends; every
+// call on a GPU shares it.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// Device address of `scratch` on each GPU (the array's name is only a host-side handle: each device holds
+// its own copy at its own address).  Looked up once per device, with that device current.
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+hipError_t static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 enum { OP_CBA = 1, OP_POOL = 2, OP_ADD = 3, OP_MIX = 4 };
 constexpr int32_t kMagic = 0x50424431;
@@ -489,6 +514,7 @@ template <class T> struct Exec {
   hipStream_t st;
   int net = 0, blk = 0, opi = 0;
   size_t red_off;
+  float* red_static = nullptr;   // reduction scratch outside the workspace (pbd_student_step_static)
   int tset, sset;      // copy of the relay store the teacher writes / the students read
   explicit Exec(pbd_ctx* ctx) : c(ctx), st(ctx->stream), red_off(ctx->r_tred), tset(ctx->front), sset(ctx->front) {}
 
@@ -497,7 +523,7 @@ template <class T> struct Exec {
   T* relay_in(int i, int set) const { return ws((set ? c->r_relay2 : c->r_relay) + c->act_off[i]); }
   T* trelay(int i) const { return relay_in(i, tset); }
   T* srelay(int i) const { return relay_in(i, sset); }
-  float* red() const { return wsf(red_off); }
+  float* red() const { return red_static ? red_static : wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
 
@@ -1581,6 +1607,10 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
   if (reinterpret_cast<uintptr_t>(dev_ws) % kAlign) return fail(c, PBD_ENOMEM_WS, "workspace must be %zu-byte aligned", kAlign);
   c->ws = static_cast<char*>(dev_ws);
   c->stream = static_cast<hipStream_t>(hip_stream);
+  {
+    float* sp = nullptr;      // this device's copy of the static reduction scratch (pbd_student_step_static)
+    HIP_TRY(c, static_scratch(&sp));
+  }
   // parameters, optimiser state and statistics start at zero; the relay store too,
   // so that padded channels never hold stale bits
   HIP_TRY(c, hipMemsetAsync(c->ws, 0, c->r_tscr, c->stream));
@@ -1734,6 +1764,25 @@ int pbd_student_step(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_
   if ((rc = check_view(c, A_prev, i - 1, "A_prev"))) return rc;
   if ((rc = check_view(c, A_i, i, "A_i"))) return rc;
   return dispatch(c, [&](auto& e) { e.set_lr(lr); e.student_block(i - 1, loss_dev); });
+}
+
+int pbd_student_step_static(pbd_ctx* c, int32_t i, const pbd_tensor* A_prev, const pbd_tensor* A_i, float lr, float* loss_dev) {
+  int rc = check_idle(c);
+  if (rc) return rc;
+  if (i < 1 || i > c->B) return fail(c, PBD_EINVAL, "block index %d outside 1..%d", i, c->B);
+  if (!std::isfinite(lr)) return fail(c, PBD_EINVAL, "learning rate is not finite");
+  if (!loss_dev) return fail(c, PBD_EINVAL, "loss_dev is null");
+  if (c->prof_on) return fail(c, PBD_ESTATE, "profiling creates events: switch it off for the call that allocates nothing");
+  if (c->relayed_upto < i) return fail(c, PBD_ESTATE, "the teacher has not produced A_%d yet", i);
+  if ((rc = check_view(c, A_prev, i - 1, "A_prev"))) return rc;
+  if ((rc = check_view(c, A_i, i, "A_i"))) return rc;
+  const size_t need = c->net[1][i - 1].red_bytes;
+  if (need > kStaticScratchBytes)
+    return fail(c, PBD_ENOMEM_WS, "block %d needs %zu bytes of reduction scratch, the static buffer holds %zu: use pbd_student_step",
+                i, need, kStaticScratchBytes);
+  float* sp = nullptr;
+  HIP_TRY(c, static_scratch(&sp));
+  return dispatch(c, [&](auto& e) { e.red_static = sp; e.set_lr(lr); e.student_block(i - 1, loss_dev); });
 }
 
 int pbd_distill_step(pbd_ctx* c, const float* x_dev, float lr, float* losses_dev) {

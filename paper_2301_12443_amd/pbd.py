@@ -22,7 +22,7 @@ STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
 
 SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
            "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
-           "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_distill_step", "pbd_pipeline_step", "pbd_pipeline_flush", "pbd_set_pipeline_order", "pbd_uses_graph", "pbd_sync",
+           "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_student_step_static", "pbd_distill_step", "pbd_pipeline_step", "pbd_pipeline_flush", "pbd_set_pipeline_order", "pbd_uses_graph", "pbd_sync",
            "pbd_arch_step", "pbd_distill_arch_step", "pbd_load_alpha", "pbd_read_alpha",
            "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
 
@@ -79,6 +79,7 @@ def lib():
                                        C.c_float, C.c_void_p]
         L.pbd_distill_step.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p]
         L.pbd_arch_step.argtypes = L.pbd_student_step.argtypes
+        L.pbd_student_step_static.argtypes = L.pbd_student_step.argtypes
         L.pbd_distill_arch_step.argtypes = L.pbd_distill_step.argtypes
         L.pbd_pipeline_step.argtypes = L.pbd_distill_step.argtypes
         L.pbd_pipeline_flush.argtypes = [C.c_void_p, C.c_void_p]
@@ -216,6 +217,13 @@ class Distiller:
         a_i = self.views[i] if a_i is None else a_i
         self._check(lib().pbd_student_step(self.h, i, C.byref(a_prev), C.byref(a_i), lr,
                                            self.losses.data_ptr() + 4 * (i - 1)))
+
+    def student_step_static(self, i, lr, a_prev=None, a_i=None):
+        """student_step with the reduction scratch in the library's static device array (allocates nothing)."""
+        a_prev = self.views[i - 1] if a_prev is None else a_prev
+        a_i = self.views[i] if a_i is None else a_i
+        self._check(lib().pbd_student_step_static(self.h, i, C.byref(a_prev), C.byref(a_i), lr,
+                                                  self.losses.data_ptr() + 4 * (i - 1)))
 
     def distill_step(self, x_dev, lr):
         self._check(lib().pbd_distill_step(self.h, self._check_x(x_dev), lr, self.losses.data_ptr()))
