@@ -9,6 +9,7 @@ ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libpbd.so")
 SOURCES = [os.path.join(HERE, "csrc", "pbd.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "ew_kernels.h"), os.path.join(HERE, "csrc", "conv_kernels.h"),
+           os.path.join(HERE, "csrc", "conv_dma_kernels.h"),
            os.path.join(ROOT, "include", "pbd.h")]
 
 

@@ -1,0 +1,399 @@
+// Implicit-GEMM convolution (forward and backward-data) for the large layers: 256-row tiles, eight
+// wavefronts, operands moved from global memory straight into LDS.
+//
+// Same mathematics and argument block as igemm_kernel (conv_kernels.h):
+//   Out[m][j] = sum_kk Agather(m, kk) * Bw[j][kk],  m = (n, a, b),  kk = (r*S + s)*CA + c
+// What differs is how the tile loop is fed:
+//  * Tile 256 x BN x BK, 512 threads, BN one of 256 / 192 / 128 / 96 / 64 (the channel counts of the
+//    workloads are 64 2^k and 96 2^k), BK 64 or 32.  The eight wavefronts form a WAVES_M x WAVES_N grid and each owns
+//    TM x TN blocks of 32 x 32 (128 x 64 for BN 256 down to 32 x 64 for BN 64), so every fragment read from LDS feeds
+//    up to four v_mfma_f32_32x32x16_bf16: half the L2 -> LDS and LDS -> register bytes per multiply-add of a
+//    128 x 128 tile.
+//  * Global -> LDS without a register round trip: buffer_load_dwordx4 ... lds writes the 64 lanes' 16-byte
+//    chunks to 1 KiB of consecutive LDS (lane l at +16 l).  Rows are therefore unpadded (BK * 2 bytes); bank
+//    conflicts of the fragment reads are avoided by a swizzle instead: lane l of a load fetches the global
+//    chunk (l % CPR) ^ swz(row) of its row, so chunk kc of row r sits in slot kc ^ swz(r), with
+//    swz(r) = (r >> 1) & 7 for 128-byte rows and (r >> 2) & 3 for 64-byte rows: the 16 lanes that one
+//    ds_read_b128 cycle serves (16 consecutive rows, one chunk index) then hit 16 different 16-byte bank groups.
+//    An out-of-range lane (padding, ragged tile) gets the descriptor's zeros written.
+//  * A ring of NS stages with ONE barrier per reduction step: at step kt a wave waits for its own loads of
+//    stage kt (s_waitcnt vmcnt), passes the barrier (now every wave's part of stage kt is in LDS, and every
+//    wave has finished reading stage kt-1), issues the loads of stage kt+NS-1 into the buffer of stage kt-1,
+//    and multiplies stage kt.
+//  * Fragment reads are ds_read_b128 in inline assembly with their own s_waitcnt lgkmcnt: the compiler
+//    would otherwise order every LDS read behind ALL outstanding direct-to-LDS loads (it cannot tell the
+//    stages apart) and the prefetch would be lost.  Fragments of sub-step ks+1 are requested before the
+//    MFMAs of sub-step ks.
+//  * Tail tiles.  One workgroup per compute unit is resident (the ring takes most of the LDS), so a launch whose
+//    tile count is a little over a multiple of the number of compute units would end with a nearly empty round as
+//    long as a full one.  The host may therefore cut the last row tiles into 64-row tiles (blockIdx >= the number
+//    of big tiles): same code with BM = 64, a quarter of the time each, spread over four times as many units.
+// Needs CA % BK == 0 (a reduction step lies inside one filter tap: taps are uniform over the block).
+#pragma once
+#include "conv_kernels.h"
+
+namespace pbd {
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+
+__device__ __forceinline__ void dma_load16(__amdgpu_buffer_rsrc_t r, unsigned char* lds_wave_base, unsigned byte_off) {
+  // lane l's 16 bytes land at lds_wave_base + 16 l (the base must be uniform over the wavefront)
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void_ptr)lds_wave_base, 16, (int)byte_off, 0, 0, 0);
+}
+
+// Wait until at most N of this wave's vector-memory operations are outstanding.  The "memory" clobbers keep
+// the compiler from moving the direct-to-LDS loads (memory operations to it) across the wait or the barrier.
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+template <int N> __device__ __forceinline__ void wait_lgkmcnt() {
+  static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ bf16x8 lds_read16_async(unsigned addr) {
+  // the result arrives later: only use it behind wait_lgkmcnt + pin()
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+__device__ __forceinline__ void pin(bf16x8& v) { asm volatile("" : "+v"(v)); }
+
+constexpr int kDmaThreads = 512;
+constexpr int kDmaBM = 256;      // rows of a big tile
+constexpr int kDmaTailBM = 64;   // rows of a tail tile
+// waves along the rows of a big tile
+constexpr int dma_waves_m(int BN) { return BN == 256 ? 2 : (BN == 192 || BN == 128) ? 4 : 8; }
+// ring depth: what 160 KB of LDS hold
+constexpr int dma_stages(int BN, int BK) { return BK == 64 && BN >= 192 ? 2 : 3; }
+constexpr int dma_lds_bytes(int BN, int BK, bool accum) {
+  const int ring = dma_stages(BN, BK) * (kDmaBM + BN) * BK * 2;
+  const int out = 128 * (BN * (accum ? 4 : 2) + 16);   // 128 staged output rows
+  const int red = kDmaThreads * 16 * 4;                 // batch-norm sums on their way to the column threads
+  return ring > out ? (ring > red ? ring : red) : (out > red ? out : red);
+}
+
+// One tile of BM rows starting at row m0, columns n0 .. n0 + BN.  stat_row: which row of g.stats it fills.
+template <int MODE, int BM, int BN, int BK, int WAVES_M, int EPI>
+__device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const bf16_t* __restrict__ A,
+                                         const bf16_t* __restrict__ Bw, bf16_t* __restrict__ Out,
+                                         const float* __restrict__ ep_a, const float* __restrict__ ep_b, int act,
+                                         const IgemmArgs& g, int m0, int n0, int stat_row) {
+  // waves that multiply: WAVES_M x WAVES_N of the 8 (a 64-row tail tile of few columns leaves some idle; they still load)
+  constexpr int TM = BM / (WAVES_M * 32);
+  constexpr int WAVES_N_MAX = 8 / WAVES_M;
+  constexpr int TN = BN / 32 >= WAVES_N_MAX ? BN / (WAVES_N_MAX * 32) : 1;
+  constexpr int WAVES_N = BN / (TN * 32);
+  static_assert(TM >= 1 && TM * WAVES_M * 32 == BM && TN * WAVES_N * 32 == BN && WAVES_N <= WAVES_N_MAX, "wave grid");
+  constexpr int CPR = BK / 8;                    // 16-byte chunks per tile row
+  constexpr int ROWB = BK * 2;                   // bytes per tile row in LDS (no padding)
+  constexpr int NS = dma_stages(BN, BK);
+  constexpr int A_BYTES = kDmaBM * ROWB, STAGE = (kDmaBM + BN) * ROWB;   // (a tail tile uses the top of the A region)
+  constexpr int A_CHUNKS = BM * CPR, B_CHUNKS = BN * CPR;
+  constexpr int A_INSTR = (A_CHUNKS + kDmaThreads - 1) / kDmaThreads, B_INSTR = (B_CHUNKS + kDmaThreads - 1) / kDmaThreads;
+  constexpr int KS = BK / 16;                    // MFMA sub-steps per stage
+  constexpr int RPI = 64 / CPR;                  // rows one wave instruction covers
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N_MAX, wn = wave % WAVES_N_MAX;
+  const bool active = wn < WAVES_N;
+  const int sh = g.stride == 2 ? 1 : 0, smask = g.stride - 1;
+
+  if (EPI == EPI_AFFINE_ACT && tid < BN / 4) {
+    const int col = min(n0 + tid * 4, g.NC - 4);
+    *reinterpret_cast<float4*>(ep_s + tid * 4) = *reinterpret_cast<const float4*>(ep_a + col);
+    *reinterpret_cast<float4*>(ep_s + BN + tid * 4) = *reinterpret_cast<const float4*>(ep_b + col);
+  }
+
+  // ---- what this thread loads: chunk (i*8 + wave)*64 + lane of the A tile and of the B tile, where it exists ----
+  // slot = lane % CPR is where the chunk lands in its row; the global chunk it fetches is slot ^ swz(row)
+  const int lrow = lane / CPR, slot = lane % CPR;
+  auto swz = [](int row) { return BK == 64 ? (row >> 1) & 7 : (row >> 2) & 3; };
+  unsigned abase[A_INSTR];
+  int rh[A_INSTR], rw[A_INSTR];
+  int a_cnt = 0, b_cnt = 0;                      // loads this WAVE issues per stage (uniform)
+#pragma unroll
+  for (int i = 0; i < A_INSTR; ++i) {
+    if ((i * 8 + wave) * 64 < A_CHUNKS) ++a_cnt;
+    const int row = (i * 8 + wave) * RPI + lrow;
+    const int m = m0 + row;
+    const bool valid = row < BM && m < g.M;
+    const int mm = valid ? m : 0;
+    const int b_ = mm % g.WO;
+    const int t = mm / g.WO;
+    const int a_ = t % g.HO;
+    const int nbase = (t / g.HO) * g.HA * g.WA;
+    const int h0 = MODE == 0 ? a_ * g.stride - g.pad : a_ + g.pad;
+    const int w0 = MODE == 0 ? b_ * g.stride - g.pad : b_ + g.pad;
+    const int kc = slot ^ swz(row);
+    if (MODE == 0) abase[i] = (unsigned)(((nbase + h0 * g.WA + w0) * g.CA + kc * 8) * 2);
+    else abase[i] = (unsigned)((nbase * g.CA + ((h0 * g.WA + w0) * g.CA >> sh) + kc * 8) * 2);
+    rh[i] = valid ? h0 : -(1 << 24);             // rows past the end fail every range test
+    rw[i] = w0;
+  }
+  unsigned bbase[B_INSTR];
+#pragma unroll
+  for (int i = 0; i < B_INSTR; ++i) {
+    if ((i * 8 + wave) * 64 < B_CHUNKS) ++b_cnt;
+    const int row = (i * 8 + wave) * RPI + lrow;
+    const int kc = slot ^ swz(row);
+    bbase[i] = row < BN && n0 + row < g.NC ? (unsigned)((n0 + row) * g.Kred + kc * 8) * 2u : kOutOfRange;
+  }
+  const int lps = a_cnt + b_cnt;
+  constexpr int LPS_MAX = A_INSTR + B_INSTR;
+  const __amdgpu_buffer_rsrc_t a_rsrc = tensor_rsrc(A, g.a_bytes), b_rsrc = tensor_rsrc(Bw, g.b_bytes);
+
+  // reduction position of the next stage to be loaded: kk = (r*S + s)*CA + c, uniform over the block
+  int kk = 0, r = 0, s = 0, c = 0;
+  const int nk = g.Kred / BK;
+  auto issue_stage = [&](int stage) {
+    unsigned char* sa = smem + stage * STAGE + wave * 1024;
+    const int tap = MODE == 0 ? r * g.WA + s : -(r * g.WA + s);
+    const unsigned delta = (unsigned)(((tap * g.CA) >> (MODE == 1 ? sh : 0)) + c) * 2u;
+    const unsigned hlim = MODE == 0 ? (unsigned)g.HA : (unsigned)g.HA << sh;
+    const unsigned wlim = MODE == 0 ? (unsigned)g.WA : (unsigned)g.WA << sh;
+#pragma unroll
+    for (int i = 0; i < A_INSTR; ++i) {
+      if ((i * 8 + wave) * 64 >= A_CHUNKS) continue;        // (uniform over the wave)
+      const int h = MODE == 0 ? rh[i] + r : rh[i] - r, w = MODE == 0 ? rw[i] + s : rw[i] - s;
+      bool ok = (unsigned)h < hlim && (unsigned)w < wlim;
+      if (MODE == 1) ok = ok && ((h | w) & smask) == 0;
+      dma_load16(a_rsrc, sa + i * 8 * 1024, ok ? abase[i] + delta : kOutOfRange);
+    }
+#pragma unroll
+    for (int i = 0; i < B_INSTR; ++i) {
+      if ((i * 8 + wave) * 64 >= B_CHUNKS) continue;
+      dma_load16(b_rsrc, sa + A_BYTES + i * 8 * 1024, bbase[i] == kOutOfRange ? kOutOfRange : bbase[i] + (unsigned)kk * 2u);
+    }
+    kk += BK;
+    c += BK;
+    const bool wrap = c >= g.CA;
+    c = wrap ? 0 : c;
+    s += wrap ? 1 : 0;
+    const bool wrap2 = s == g.S;
+    s = wrap2 ? 0 : s;
+    r += wrap2 ? 1 : 0;
+  };
+  // wait until this wave's loads of the oldest `behind`-stages-old stage have landed
+  auto wait_stage = [&](bool more_in_flight) {
+    if (NS == 3 && more_in_flight) {
+      // one younger stage may stay outstanding: lps loads
+      if (lps == LPS_MAX) wait_vmcnt<LPS_MAX>();
+      else if (LPS_MAX >= 1 && lps == LPS_MAX - 1) wait_vmcnt<(LPS_MAX >= 1 ? LPS_MAX - 1 : 0)>();
+      else if (LPS_MAX >= 2 && lps == LPS_MAX - 2) wait_vmcnt<(LPS_MAX >= 2 ? LPS_MAX - 2 : 0)>();
+      else wait_vmcnt<0>();
+    } else {
+      wait_vmcnt<0>();
+    }
+  };
+
+  // ---- fragment addresses: row = lane % 32 (+ 32 i), chunk = 2 ks + lane / 32, slot = chunk ^ swz(row) ----
+  const int frow = lane & 31, fhi = lane >> 5;
+  unsigned fa[KS], fb[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const unsigned so = (unsigned)(((ks * 2 + fhi) ^ swz(frow)) * 16);   // (blocks start at multiples of 32 rows: same swizzle)
+    fa[ks] = (unsigned)((wm * TM * 32 + frow) * ROWB) + so;
+    fb[ks] = (unsigned)(A_BYTES + (wn * TN * 32 + frow) * ROWB) + so;
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  struct Frag { bf16x8 a[TM], b[TN]; };
+  auto read_frag = [&](Frag& f, unsigned addr_a, unsigned addr_b) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) f.a[i] = lds_read16_async(addr_a + i * 32 * ROWB);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.b[j] = lds_read16_async(addr_b + j * 32 * ROWB);
+  };
+  auto pin_frag = [&](Frag& f) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) pin(f.a[i]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) pin(f.b[j]);
+  };
+
+  // ---- the ring ----
+#pragma unroll
+  for (int st = 0; st < NS - 1; ++st)
+    if (st < nk) issue_stage(st);
+  int stage = 0, next = NS - 1;                 // buffer of step kt, buffer the next loads go to
+  for (int kt = 0; kt < nk; ++kt) {
+    wait_stage(kt + 1 < nk);
+    block_barrier();
+    // every wave is past step kt-1: its buffer takes the loads of step kt+NS-1
+    if (kt + NS - 1 < nk) issue_stage(next);
+    if (active) {
+      const unsigned sbase = (unsigned)(stage * STAGE);
+      Frag f[2];
+      read_frag(f[0], fa[0] + sbase, fb[0] + sbase);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) read_frag(f[(ks + 1) & 1], fa[ks + 1] + sbase, fb[ks + 1] + sbase);
+        Frag& cur = f[ks & 1];
+        // LDS reads return in order: the older group is complete once at most the newer group's reads are pending
+        if (ks + 1 < KS) wait_lgkmcnt<TM + TN>(); else wait_lgkmcnt<0>();
+        pin_frag(cur);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j], cur.a[i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);      // keep the next group's reads behind these MFMAs' issue, not ahead of the wait
+      }
+    }
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    next = next + 1 == NS ? 0 : next + 1;
+  }
+  wait_vmcnt<0>();
+  __syncthreads();                              // the ring is dead: LDS now stages the output tile
+
+  // ---- epilogue: up to 128 staged rows at a time, then coalesced 16-byte stores ----------------------
+  // lane holds pixel (lane % 32) and channels 8 (v / 4) + 4 (lane / 32) + v % 4 of each 32 x 32 block
+  const bool full = m0 + BM <= g.M && n0 + BN <= g.NC;
+  constexpr int ESZ = EPI == EPI_ACCUM ? 4 : 2;
+  constexpr int OP = BN * ESZ + 16;              // bytes per staged row
+  constexpr int CPROW = BN / 8;                  // 8-channel chunks per row
+  constexpr int ST = (CPROW & (CPROW - 1)) == 0 ? kDmaThreads : 384;   // storing threads: a multiple of CPROW (12 and 24 divide 384)
+  constexpr int PR = BM < 128 ? BM : 128;        // rows per pass
+  constexpr int NCHUNK = PR * CPROW;
+  constexpr int CPT = NCHUNK / ST;               // chunks per storing thread and pass
+  static_assert(ST % CPROW == 0 && NCHUNK % ST == 0, "a storing thread keeps its chunk column over the rows it stores");
+  float s1[8], s2[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s1[e] = s2[e] = 0.f;
+#pragma unroll
+  for (int pass = 0; pass < BM / PR; ++pass) {
+    const int rbase = pass * PR;
+    // values the stores of this pass combine with (a fused residual, or what an accumulating launch adds to)
+    uint4 extra[CPT];
+    const bf16_t* esrc = EPI == EPI_ACCUM ? Out : static_cast<const bf16_t*>(g.res);
+    if (esrc && tid < ST) {
+#pragma unroll
+      for (int k = 0; k < CPT; ++k) {
+        const int cidx = tid + k * ST;
+        const int row = m0 + rbase + cidx / CPROW, col = n0 + (cidx % CPROW) * 8;
+        extra[k] = (full || (row < g.M && col < g.NC)) ? *reinterpret_cast<const uint4*>(esrc + (size_t)row * g.NC + col)
+                                                       : make_uint4(0, 0, 0, 0);
+      }
+    }
+    if (pass) __syncthreads();                   // the previous pass has been read out
+    if (active && (wm * TM * 32) / PR == pass) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int lr = (wm * TM * 32) % PR + i * 32 + (lane & 31);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int lcol = wn * TN * 32 + j * 32 + 8 * q + 4 * (lane >> 5);
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
+            if (EPI == EPI_ACCUM) {
+              *reinterpret_cast<float4*>(smem + lr * OP + lcol * 4) = make_float4(o[0], o[1], o[2], o[3]);
+            } else {
+              if (EPI == EPI_AFFINE_ACT) {
+                const float4 ea = *reinterpret_cast<const float4*>(ep_s + lcol);
+                const float4 eb = *reinterpret_cast<const float4*>(ep_s + BN + lcol);
+                o[0] = apply_act(fmaf(o[0], ea.x, eb.x), act); o[1] = apply_act(fmaf(o[1], ea.y, eb.y), act);
+                o[2] = apply_act(fmaf(o[2], ea.z, eb.z), act); o[3] = apply_act(fmaf(o[3], ea.w, eb.w), act);
+              }
+              uint2 pk;
+              pk.x = pack_bf2(o[0], o[1]);
+              pk.y = pack_bf2(o[2], o[3]);
+              *reinterpret_cast<uint2*>(smem + lr * OP + lcol * 2) = pk;
+            }
+          }
+      }
+    }
+    __syncthreads();
+    if (tid < ST) {
+#pragma unroll
+      for (int k = 0; k < CPT; ++k) {
+        const int cidx = tid + k * ST;
+        const int lr = cidx / CPROW, c16 = cidx % CPROW;
+        const int row = m0 + rbase + lr, col = n0 + c16 * 8;
+        if (full || (row < g.M && col < g.NC)) {   // NC % 8 == 0: a chunk is in or out as a whole
+          uint4 v;
+          if (EPI == EPI_ACCUM) {
+            const float4 lo = *reinterpret_cast<const float4*>(smem + lr * OP + c16 * 32);
+            const float4 hi = *reinterpret_cast<const float4*>(smem + lr * OP + c16 * 32 + 16);
+            v.x = pack_bf2(lo.x + bf_lo(extra[k].x), lo.y + bf_hi(extra[k].x));
+            v.y = pack_bf2(lo.z + bf_lo(extra[k].y), lo.w + bf_hi(extra[k].y));
+            v.z = pack_bf2(hi.x + bf_lo(extra[k].z), hi.y + bf_hi(extra[k].z));
+            v.w = pack_bf2(hi.z + bf_lo(extra[k].w), hi.w + bf_hi(extra[k].w));
+          } else {
+            v = *reinterpret_cast<const uint4*>(smem + lr * OP + c16 * 16);
+            if (EPI == EPI_STORE && g.stats) {
+              const float f[8] = {bf_lo(v.x), bf_hi(v.x), bf_lo(v.y), bf_hi(v.y), bf_lo(v.z), bf_hi(v.z), bf_lo(v.w), bf_hi(v.w)};
+#pragma unroll
+              for (int e = 0; e < 8; ++e) { s1[e] += f[e]; s2[e] = fmaf(f[e], f[e], s2[e]); }
+            }
+            if (g.res) {
+              const uint4 r_ = extra[k];
+              v.x = pack_bf2(apply_act(bf_lo(v.x) + bf_lo(r_.x), g.res_act), apply_act(bf_hi(v.x) + bf_hi(r_.x), g.res_act));
+              v.y = pack_bf2(apply_act(bf_lo(v.y) + bf_lo(r_.y), g.res_act), apply_act(bf_hi(v.y) + bf_hi(r_.y), g.res_act));
+              v.z = pack_bf2(apply_act(bf_lo(v.z) + bf_lo(r_.z), g.res_act), apply_act(bf_hi(v.z) + bf_hi(r_.z), g.res_act));
+              v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(r_.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(r_.w), g.res_act));
+            }
+          }
+          *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = v;
+        }
+      }
+    }
+  }
+  if (EPI == EPI_STORE && g.stats) {
+    // storing threads with equal tid % CPROW hold the same 8 channels: their sums meet in LDS and the column's
+    // first thread adds them in thread order (a fixed association)
+    __syncthreads();                             // the staged rows have been read by everyone
+    float* red = reinterpret_cast<float*>(smem); // [storing thread][16]
+    if (tid < ST) {
+      *reinterpret_cast<float4*>(red + tid * 16) = make_float4(s1[0], s1[1], s1[2], s1[3]);
+      *reinterpret_cast<float4*>(red + tid * 16 + 4) = make_float4(s1[4], s1[5], s1[6], s1[7]);
+      *reinterpret_cast<float4*>(red + tid * 16 + 8) = make_float4(s2[0], s2[1], s2[2], s2[3]);
+      *reinterpret_cast<float4*>(red + tid * 16 + 12) = make_float4(s2[4], s2[5], s2[6], s2[7]);
+    }
+    __syncthreads();
+    // thread t: column t / 16, value t % 16 (8 sums, 8 sums of squares)
+    const int cc = tid >> 4, e = tid & 15, col = n0 + cc * 8;
+    if (cc < CPROW && col < g.NC) {
+      float t = 0.f;
+      for (int w = 0; w < ST / CPROW; ++w) t += red[(w * CPROW + cc) * 16 + e];
+      g.stats[(size_t)stat_row * 2 * g.NC + (e >> 3) * g.NC + col + (e & 7)] = t;
+    }
+  }
+}
+
+// blockIdx.x < g.big_tiles: big tile number xcd_contiguous(blockIdx.x, big_tiles) (column tiles of a row tile
+// next to each other, each XCD a contiguous run).  Above that: 64-row tail tiles over the rows from
+// g.tail_m0 on, in order.
+template <int MODE, int BN, int BK, int EPI>
+__global__ __launch_bounds__(kDmaThreads) void igemm_dma_kernel(const bf16_t* __restrict__ A,
+                                                                const bf16_t* __restrict__ Bw,
+                                                                bf16_t* __restrict__ Out,
+                                                                const float* __restrict__ ep_a,
+                                                                const float* __restrict__ ep_b, int act,
+                                                                IgemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[dma_lds_bytes(BN, BK, EPI == EPI_ACCUM)];
+  __shared__ __attribute__((aligned(16))) float ep_s[EPI == EPI_AFFINE_ACT ? 2 * BN : 4];
+  if ((int)blockIdx.x < g.big_tiles) {
+    const int tile = xcd_contiguous(blockIdx.x, g.big_tiles);
+    const int tile_n = tile % g.tiles_n, tile_m = tile / g.tiles_n;
+    dma_tile<MODE, kDmaBM, BN, BK, dma_waves_m(BN), EPI>(smem, ep_s, A, Bw, Out, ep_a, ep_b, act, g, tile_m * kDmaBM, tile_n * BN, tile_m);
+  } else {
+    const int tile = blockIdx.x - g.big_tiles;
+    const int tile_n = tile % g.tiles_n, tile_m = tile / g.tiles_n;
+    dma_tile<MODE, kDmaTailBM, BN, BK, 1, EPI>(smem, ep_s, A, Bw, Out, ep_a, ep_b, act, g, g.tail_m0 + tile_m * kDmaTailBM,
+                                               tile_n * BN, g.big_tiles / g.tiles_n + tile_m);
+  }
+}
+
+}  // namespace pbd

@@ -145,6 +145,9 @@ struct IgemmArgs {
   // batch-norm statistics of the stored result from the same pass (EPI_STORE): per row tile and channel the
   // sums of y and y^2 over the tile's rows, stats[tile_m][2][NC] (fp32; summed further in double)
   float* stats;
+  // igemm_dma_kernel only: the first big_tiles workgroups take 256-row tiles (tiles_n per row tile), the others
+  // 64-row tiles over the rows from tail_m0 on
+  int big_tiles, tail_m0;
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel

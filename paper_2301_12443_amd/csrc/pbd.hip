@@ -21,6 +21,7 @@
 
 #include "../../include/pbd.h"
 #include "conv_kernels.h"
+#include "conv_dma_kernels.h"
 #include "ew_kernels.h"
 
 using namespace pbd;
@@ -116,6 +117,7 @@ struct pbd_ctx {
   std::vector<hipStream_t> side;        // one stream per student block (graph capture branches)
   std::vector<hipEvent_t> ev_fork, ev_join;
   char* ws = nullptr;
+  int num_cu = 256;                     // compute units of the bound device (tile-count heuristics)
   hipStream_t stream = nullptr;
   bool bound = false, fold_dirty = true;
   int relayed_upto = 0;                 // A_0..A_relayed_upto hold the current input's activations
@@ -317,6 +319,49 @@ IgemmCfg igemm_cfg(long M, int NC, int Kred, int CA) {
   return c;
 }
 int igemm_splits(long M, int NC, int Kred, int CA) { return igemm_cfg(M, NC, Kred, CA).splits; }
+
+// Launch shape of igemm_dma_kernel (256-row tiles, operands straight into LDS) for one dense layer, or use = false
+// when the layer keeps igemm_kernel: channel counts that are no multiple of 32, fewer tiles than most of the
+// compute units (there 128- and 64-row tiles and split-K fill the chip better), and 1 x 1 layers with a short
+// reduction (a handful of steps per tile: with one resident workgroup per unit the fill and the store of a tile are
+// not hidden behind another tile's work, and the 128-row kernel with two resident workgroups is as fast or faster;
+// measured on 256 x 56 x 56 x 256 -> 96 and 256 x 14 x 14 x 384 -> 1024).
+struct DmaCfg { bool use; int BN, BK, tiles_n, big_m, tail_m; };
+DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int taps, int num_cu) {
+  DmaCfg d{};
+  if (CA % 32 != 0 || NC % 8 != 0 || NC < 64 || M < 4096) return d;
+  if (taps == 1 ? Kred < 512 : Kred < 256) return d;
+  d.BK = CA % 64 == 0 ? 64 : 32;
+  const long tm = (M + kDmaBM - 1) / kDmaBM;
+  // One workgroup per compute unit is resident: time ~ rounds x columns of the tile (a little more per column for
+  // narrow tiles, whose fragments feed fewer MFMAs).  A last round that fills at most a quarter of the units is
+  // run as 64-row tail tiles instead, which costs two thirds of a round (a tail tile still loads the whole
+  // weight tile: measured 275.7 -> 252.6 us on 256 x 28 x 28 x 256 -> 256, 3 x 3, 784 tiles).
+  static const int kBN[5] = {256, 192, 128, 96, 64};
+  static const double kCost[5] = {1.0, 1.05, 1.15, 1.25, 1.4};
+  double best = 1e30;
+  for (int i = 0; i < 5; ++i) {
+    const int bn = kBN[i];
+    const long tn = (NC + bn - 1) / bn, T = tm * tn;
+    const long full = T / num_cu, r = T % num_cu;
+    double rounds = (double)full;
+    if (r) rounds += (full >= 1 && r <= num_cu / 4) ? 0.66 : 1.0;
+    const double t = rounds * bn * kCost[i];
+    if (t < best) { best = t; d.BN = bn; d.tiles_n = (int)tn; }
+  }
+  const long T = tm * d.tiles_n;
+  if (T < num_cu * 7 / 10) return d;       // (use stays false)
+  d.use = true;
+  d.big_m = (int)tm;
+  d.tail_m = 0;
+  const long r = T % num_cu;
+  if (T >= num_cu && r && r <= num_cu / 4) {
+    const int cut = (int)((r + d.tiles_n - 1) / d.tiles_n);     // row tiles that go to the tail
+    d.big_m = (int)tm - cut;
+    d.tail_m = (int)((M - (long)d.big_m * kDmaBM + kDmaTailBM - 1) / kDmaTailBM);
+  }
+  return d;
+}
 
 constexpr int kMseBlocks = 1024;
 
@@ -533,7 +578,13 @@ template <class T> struct Exec {
   bool fuses_residual(const OpPlan& op) const {
     if (!mfma() || op.dw) return false;
     const IgemmCfg cfg = igemm_cfg((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
-    return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);
+    return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);      // (the 256-row kernel, where it is used, fuses it too)
+  }
+  // the 256-row, direct-to-LDS kernel takes a launch when its tile count fills the chip and no split-K is wanted
+  DmaCfg dma_for(long M, int NC, int Kred, int CA) const {
+    DmaCfg d = dma_cfg(M, NC, Kred, CA, Kred / CA, c->num_cu);
+    if (d.use && igemm_cfg(M, NC, Kred, CA).splits != 1) d.use = false;
+    return d;
   }
   // Row tiles whose staged store also delivers the batch-norm sums of the convolution's output (0: the
   // layer takes its statistics in a pass of its own).  Same conditions as fuses_residual, whole channel
@@ -541,6 +592,8 @@ template <class T> struct Exec {
   int fused_stats_tiles(const OpPlan& op) const {
     const long M = (long)c->o.batch * op.out.h * op.out.w;
     if (!fuses_residual(op) || op.d.c_out % 8 != 0 || short_column(M)) return 0;
+    const DmaCfg d = dma_for(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
+    if (d.use) return d.big_m + d.tail_m;
     const IgemmCfg cfg = igemm_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
     return (int)((M + cfg.BM - 1) / cfg.BM);
   }
@@ -570,6 +623,30 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
+    const DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA);
+    if (dc.use && (epi == EPI_STORE || epi == EPI_AFFINE_ACT || epi == EPI_ACCUM)) {
+      g.tiles_n = dc.tiles_n;
+      g.tiles_m = dc.big_m + dc.tail_m;
+      g.splits = 1;
+      g.big_tiles = dc.big_m * dc.tiles_n;
+      g.tail_m0 = dc.big_m * kDmaBM;
+      const dim3 grid(g.big_tiles + dc.tail_m * dc.tiles_n);
+      static const char* const kEpiName[] = {"store", "affine", "accum"};
+      char name[32];
+      snprintf(name, sizeof name, "igemm_%s_256x%d_%s", MODE ? "dgrad" : "fwd", dc.BN, kEpiName[epi]);
+      ProfScope ps(c, name, bytes, flops, net, blk, opi);
+#define PBD_DMA(BN_, BK_, EPI_) launch(c, igemm_dma_kernel<MODE, BN_, BK_, EPI_>, grid, kDmaThreads, 0, st, A, Bw, out, a, b, act, g)
+#define PBD_DMA_BK(BN_, EPI_) do { if (dc.BK == 64) PBD_DMA(BN_, 64, EPI_); else PBD_DMA(BN_, 32, EPI_); } while (0)
+#define PBD_DMA_BN(EPI_) do { switch (dc.BN) { case 256: PBD_DMA_BK(256, EPI_); break; case 192: PBD_DMA_BK(192, EPI_); break; \
+        case 128: PBD_DMA_BK(128, EPI_); break; case 96: PBD_DMA_BK(96, EPI_); break; default: PBD_DMA_BK(64, EPI_); } } while (0)
+      // (forward launches never accumulate, backward-data launches have no folded batch norm)
+      if constexpr (MODE == 0) { if (epi == EPI_AFFINE_ACT) PBD_DMA_BN(EPI_AFFINE_ACT); else PBD_DMA_BN(EPI_STORE); }
+      else { if (epi == EPI_ACCUM) PBD_DMA_BN(EPI_ACCUM); else PBD_DMA_BN(EPI_STORE); }
+#undef PBD_DMA_BN
+#undef PBD_DMA_BK
+#undef PBD_DMA
+      return;
+    }
     IgemmCfg cfg = igemm_cfg(g.M, g.NC, g.Kred, g.CA);
     // an accumulating 256-row tile cannot stage its fp32 results in LDS: 128 rows store whole cache lines
     if (epi == EPI_ACCUM && cfg.BM == 256) cfg.BM = 128;
@@ -1610,6 +1687,10 @@ int pbd_bind(pbd_ctx* c, void* dev_ws, size_t bytes, void* hip_stream) {
   {
     float* sp = nullptr;      // this device's copy of the static reduction scratch (pbd_student_step_static)
     HIP_TRY(c, static_scratch(&sp));
+    int dev = 0, cus = 0;
+    HIP_TRY(c, hipGetDevice(&dev));
+    HIP_TRY(c, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus > 0) c->num_cu = cus;
   }
   // parameters, optimiser state and statistics start at zero; the relay store too,
   // so that padded channels never hold stale bits
