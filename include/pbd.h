@@ -127,6 +127,19 @@ int pbd_read_act(pbd_ctx* ctx, int32_t i, float* host, size_t n);
  * read the add's output instead.  Testing aid; waits. */
 int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
 
+/* More of what the last pbd_student_step of student block b (from 0) left behind, for checking one layer at a
+ * time (testing aids like pbd_read_value; float32 NCHW; same validity rules; all wait):
+ *  - pbd_read_conv_out: the output of the convolution of conv+BN op `op`, before normalisation.
+ *  - pbd_read_batch_stats: that op's batch mean and 1 / sqrt(biased batch variance + eps), n = its channels.
+ *  - pbd_read_grad_value: the stored gradient that belongs to value v (v >= 1).  For the output of a conv+BN op
+ *    this is the gradient of loss_i (Sec. II-A) with respect to the CONVOLUTION output, i.e. already taken back
+ *    through the activation and the normalisation (the tensor the op's weight gradient and backward-data are
+ *    formed from); for the output of a pool, add or weighted-sum op it is the gradient with respect to the value
+ *    itself.  Unspecified for values no gradient reached (e.g. after pbd_arch_step). */
+int pbd_read_conv_out(pbd_ctx* ctx, int32_t b, int32_t op, float* host, size_t n);
+int pbd_read_batch_stats(pbd_ctx* ctx, int32_t b, int32_t op, float* mean_host, float* invstd_host, size_t n);
+int pbd_read_grad_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
+
 /* Teacher relay (Algorithm 1, load + T.forward; Sec. IV-A, Sec. VII-A).  x_dev:
  * device float32 NCHW [batch][C0][H0][W0].  Runs T_1..T_B once each in inference
  * mode and keeps every activation.  A (host array of B+1 views, may be null) gets

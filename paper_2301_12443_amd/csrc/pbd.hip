@@ -1814,6 +1814,46 @@ int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
   return download_act(c, dev, s, host);
 }
 
+int pbd_read_conv_out(pbd_ctx* c, int32_t b, int32_t opi, float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  const OpPlan* op = find_cba(c, PBD_STUDENT, b, opi);
+  if (!op) return fail(c, PBD_EINVAL, "no conv+BN operation at student block %d op %d", b, opi);
+  BlockPlan& bp = c->net[1][b];
+  if (!bp.stepped) return fail(c, PBD_ESTATE, "block %d holds no saved values (not stepped, or scratch reused)", b);
+  const size_t want = (size_t)c->o.batch * op->out.c * op->out.h * op->out.w;
+  if (n != want) return fail(c, PBD_ESHAPE, "the convolution output has %zu elements, %zu asked", want, n);
+  return download_act(c, c->ws + bp.scr_off + op->y, op->out, host);
+}
+
+int pbd_read_batch_stats(pbd_ctx* c, int32_t b, int32_t opi, float* mean_host, float* invstd_host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!mean_host || !invstd_host) return fail(c, PBD_EINVAL, "host pointer is null");
+  const OpPlan* op = find_cba(c, PBD_STUDENT, b, opi);
+  if (!op) return fail(c, PBD_EINVAL, "no conv+BN operation at student block %d op %d", b, opi);
+  if (!c->net[1][b].stepped) return fail(c, PBD_ESTATE, "block %d has not been stepped", b);
+  if (n != (size_t)op->d.c_out) return fail(c, PBD_ESHAPE, "the layer has %d channels, %zu asked", op->d.c_out, n);
+  HIP_TRY(c, hipMemcpyAsync(mean_host, c->ws + op->s_mean, n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipMemcpyAsync(invstd_host, c->ws + op->s_invstd, n * 4, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PBD_OK;
+}
+
+int pbd_read_grad_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
+  int rc = check_ready(c);
+  if (rc) return rc;
+  if (!host) return fail(c, PBD_EINVAL, "host pointer is null");
+  if (b < 0 || b >= c->B) return fail(c, PBD_EINVAL, "block %d outside 0..%d", b, c->B - 1);
+  BlockPlan& bp = c->net[1][b];
+  if (v < 1 || v >= (int)bp.shapes.size()) return fail(c, PBD_EINVAL, "value %d outside 1..%zu", v, bp.shapes.size() - 1);
+  if (!bp.stepped) return fail(c, PBD_ESTATE, "block %d holds no saved values (not stepped, or scratch reused)", b);
+  const Shape s = bp.shapes[v];
+  if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
+  return download_act(c, c->ws + bp.scr_off + bp.dval[v], s, host);
+}
+
 int pbd_teacher_relay(pbd_ctx* c, const float* x_dev, pbd_tensor* A) {
   int rc = check_idle(c);
   if (rc) return rc;

@@ -22,6 +22,7 @@ STATUS = {0: "PBD_OK", -1: "PBD_EINVAL", -2: "PBD_ESHAPE", -3: "PBD_ENOMEM_WS",
 
 SYMBOLS = ["pbd_create", "pbd_destroy", "pbd_last_error", "pbd_num_blocks", "pbd_workspace_bytes",
            "pbd_bind", "pbd_load_param", "pbd_read_tensor", "pbd_read_act", "pbd_read_value",
+           "pbd_read_conv_out", "pbd_read_batch_stats", "pbd_read_grad_value",
            "pbd_teacher_relay", "pbd_teacher_prefix", "pbd_student_step", "pbd_student_step_static", "pbd_distill_step", "pbd_pipeline_step", "pbd_pipeline_flush", "pbd_set_pipeline_order", "pbd_uses_graph", "pbd_sync",
            "pbd_arch_step", "pbd_distill_arch_step", "pbd_load_alpha", "pbd_read_alpha",
            "pbd_set_profile", "pbd_reset_profile", "pbd_get_profile"]
@@ -73,6 +74,9 @@ def lib():
         L.pbd_read_tensor.argtypes = [C.c_void_p] + [C.c_int32] * 5 + [fp, C.c_size_t]
         L.pbd_read_act.argtypes = [C.c_void_p, C.c_int32, fp, C.c_size_t]
         L.pbd_read_value.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
+        L.pbd_read_conv_out.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
+        L.pbd_read_batch_stats.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, fp, C.c_size_t]
+        L.pbd_read_grad_value.argtypes = [C.c_void_p, C.c_int32, C.c_int32, fp, C.c_size_t]
         L.pbd_teacher_relay.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(pbd_tensor)]
         L.pbd_teacher_prefix.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(pbd_tensor)]
         L.pbd_student_step.argtypes = [C.c_void_p, C.c_int32, C.POINTER(pbd_tensor), C.POINTER(pbd_tensor),
@@ -173,6 +177,27 @@ class Distiller:
         shape = (self.batch, *W.block_shapes(self.wl.student[b], self.act_shapes[b])[v])
         out = np.empty(int(np.prod(shape)), dtype=np.float32)
         self._check(lib().pbd_read_value(self.h, b, v, _fp(out), out.size))
+        return out.reshape(shape)
+
+    def read_conv_out(self, b, j):
+        """Output of the convolution of student op j of block b (before normalisation), float32 NCHW."""
+        shape = (self.batch, *W.block_shapes(self.wl.student[b], self.act_shapes[b])[j + 1])
+        out = np.empty(int(np.prod(shape)), dtype=np.float32)
+        self._check(lib().pbd_read_conv_out(self.h, b, j, _fp(out), out.size))
+        return out.reshape(shape)
+
+    def read_batch_stats(self, b, j):
+        """(batch mean, 1 / sqrt(biased batch variance + eps)) of student op j of block b."""
+        n = W.block_shapes(self.wl.student[b], self.act_shapes[b])[j + 1][0]
+        mean, invstd = np.empty(n, dtype=np.float32), np.empty(n, dtype=np.float32)
+        self._check(lib().pbd_read_batch_stats(self.h, b, j, _fp(mean), _fp(invstd), n))
+        return mean, invstd
+
+    def read_grad_value(self, b, v):
+        """The stored gradient that belongs to value v of block b (see pbd_read_grad_value)."""
+        shape = (self.batch, *W.block_shapes(self.wl.student[b], self.act_shapes[b])[v])
+        out = np.empty(int(np.prod(shape)), dtype=np.float32)
+        self._check(lib().pbd_read_grad_value(self.h, b, v, _fp(out), out.size))
         return out.reshape(shape)
 
     def _check_x(self, x_dev):

@@ -1,0 +1,259 @@
+"""Layer-by-layer parity of one bf16 student step against the PLAIN fp64 oracle primitives.
+
+A gradient of a rectified network is discontinuous in its mask bits, pool winners and, in bf16, in the stored
+codes themselves, so two correct evaluations of a deep block that round differently drift apart by far more
+than a rounding error (the end-to-end comparisons measure that).  Here the oracle is therefore applied to
+one operation at a time, on the very tensors the library's kernels read: every input of an operation is read
+back from the device (bf16 values are exact in float64), the operation's plain definition is evaluated in
+fp64 - orc.conv_fwd / conv_dgrad / conv_wgrad / bn_train_fwd / bn_train_bwd / act / maxpool / mse, no
+storage mode - and compared with what the library stored for it.  Each comparison then sees float32-vs-fp64
+arithmetic and ONE bf16 rounding of the result, whatever the depth of the graph; decisions (masks, winners)
+are taken from identical inputs on both sides.  Elements whose pre-activation lies within `floor` of a kink
+(where float32 and fp64 may legitimately decide differently) are left out of the elementwise comparison and
+their largest possible influence on the per-channel sums is added to those sums' tolerance.
+
+The executor's wiring (which tensor feeds which, accumulation over several readers, the update) is covered
+by the same walk: the reference gradient of a value is assembled from ALL its readers' stored gradients.
+"""
+import numpy as np
+
+from oracle import pbd_oracle as orc
+from paper_2301_12443_amd import pbd, workloads as W
+
+EPS, RHO = 1e-5, 0.1
+
+
+def _max_rel(got, ref, keep=None):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    den = float(np.max(np.abs(ref))) if ref.size else 0.0
+    diff = np.abs(got - ref)
+    if keep is not None:
+        diff = diff[keep]
+    if diff.size == 0:
+        return 0.0
+    return float(np.max(diff) / den) if den else float(np.max(diff))
+
+
+def student_params(wl, b, overrides=None):
+    """{(op, slot): float64 array} of block b before any step (seeded; `overrides` {slot: value} fills a slot)."""
+    out = {}
+    for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+        arr = W.make_param(wl, W.NET_STUDENT, b, j, slot, shape).astype(np.float64)
+        if overrides and slot in overrides:
+            arr = np.full(shape, overrides[slot], dtype=np.float64)
+        out[(j, slot)] = arr
+    return out
+
+
+def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, log=None):
+    """d: a Distiller whose block b has just been stepped ONCE from the parameters `par` (momentum 0, running
+    statistics (0, 1)) on the relayed activations it still holds.  Returns ({name: max-norm relative error},
+    {name: error of a quantity that must agree to float32 rounding}).  fwd_ops / bwd_values restrict the walk
+    (full-size runs check a few heavy layers only); None = everything."""
+    blk = wl.student[b]
+    ops = blk.ops
+    nval = len(ops) + 1
+    N = d.batch
+    R = orc.round_bf16
+    E, T = {}, {}
+    say = log or (lambda s: None)
+    want_fwd = (lambda j: True) if fwd_ops is None else (lambda j: j in fwd_ops)
+    want_bwd = (lambda v: True) if bwd_values is None else (lambda v: v in bwd_values)
+
+    vals = {0: d.read_act(b).astype(np.float64)}
+    conv_y, pre, stats, pool_idx, wq = {}, {}, {}, {}, {}
+
+    def value(v):
+        """Value v as the library's kernels read it: read back, or (never written: the add that reads it is
+        fused into the producer's normalisation pass) the bf16 code of its plain definition."""
+        if v not in vals:
+            try:
+                vals[v] = d.read_value(b, v).astype(np.float64)
+            except pbd.PbdError as e:
+                if e.code != -4:
+                    raise
+                j = v - 1
+                vals[v] = R(orc.act_fwd(pre_of(j), ops[j].act)).reshape(pre_of(j).shape)
+        return vals[v]
+
+    def y_of(j):
+        if j not in conv_y:
+            conv_y[j] = d.read_conv_out(b, j).astype(np.float64)
+        return conv_y[j]
+
+    def pre_of(j):
+        """Tensor before the activation of op j (conv+BN: the normalised GPU conv output, batch statistics in
+        fp64; add: the sum of the inputs), with the statistics it used."""
+        if j not in pre:
+            op = ops[j]
+            if op.type == W.OP_CBA:
+                p, mean, var = orc.bn_train_fwd(y_of(j), par[(j, W.P_GAMMA)], par[(j, W.P_BETA)], EPS)
+                pre[j], stats[j] = p, (mean, var)
+            else:
+                pre[j] = value(op.inputs[0]) + value(op.inputs[1])
+        return pre[j]
+
+    def weights(j):
+        if j not in wq:
+            wq[j] = R(par[(j, W.P_WEIGHT)]).reshape(par[(j, W.P_WEIGHT)].shape)     # the bf16 compute copy
+        return wq[j]
+
+    # ---- forward --------------------------------------------------------------------------------------
+    for j, op in enumerate(ops):
+        v = j + 1
+        if not want_fwd(j):
+            continue
+        if op.type == W.OP_CBA:
+            xin = value(op.inputs[0])
+            E[f"op{j}.conv"] = _max_rel(y_of(j), orc.conv_fwd(xin, weights(j), op.stride, op.pad, op.groups))
+            p = pre_of(j)
+            mean, var = stats[j]
+            mg, ig = d.read_batch_stats(b, j)
+            T[f"op{j}.mean"] = float(np.max(np.abs(mg - mean) / np.sqrt(var + EPS)))
+            T[f"op{j}.invstd"] = float(np.max(np.abs(ig * np.sqrt(var + EPS) - 1.0)))
+            m = N * p.shape[2] * p.shape[3]
+            shape = (op.c_out,)
+            T[f"op{j}.rmean"] = float(np.max(np.abs(d.read_tensor(pbd.PBD_PARAM, 1, b, j, W.P_RMEAN, shape) - RHO * mean)
+                                             / np.sqrt(var + EPS)))
+            T[f"op{j}.rvar"] = _max_rel(d.read_tensor(pbd.PBD_PARAM, 1, b, j, W.P_RVAR, shape),
+                                        (1 - RHO) + RHO * var * m / (m - 1))
+            try:
+                zg = d.read_value(b, v).astype(np.float64)
+                vals[v] = zg
+                E[f"op{j}.out"] = _max_rel(zg, orc.act_fwd(p, op.act))
+            except pbd.PbdError as e:
+                if e.code != -4:
+                    raise
+        elif op.type == W.OP_POOL:
+            z, idx = orc.maxpool_fwd(value(op.inputs[0]), op.k, op.stride, op.pad)
+            pool_idx[j] = idx
+            E[f"op{j}.pool"] = _max_rel(value(v), z)           # picks stored codes: exact
+        elif op.type == W.OP_ADD:
+            E[f"op{j}.add"] = _max_rel(value(v), orc.act_fwd(pre_of(j), op.act))
+        else:
+            z = sum(pk * value(i) for pk, i in zip(op.p, op.inputs))
+            E[f"op{j}.mix"] = _max_rel(value(v), z)
+        say(f"  fwd op{j}")
+
+    # ---- loss -----------------------------------------------------------------------------------------
+    a_next = d.read_act(b + 1).astype(np.float64)
+    loss_ref, dS = orc.mse(value(nval - 1), a_next)
+    E["loss"] = abs(float(d.losses[b].item()) - loss_ref) / loss_ref
+
+    # ---- backward -------------------------------------------------------------------------------------
+    readers = {v: [] for v in range(nval)}
+    for k, op in enumerate(ops):
+        for slot_i, i in enumerate(op.inputs):
+            readers[i].append((k, slot_i))
+    grads = {}
+
+    def G(v):
+        if v not in grads:
+            grads[v] = d.read_grad_value(b, v).astype(np.float64)
+        return grads[v]
+
+    for v in range(nval - 1, 0, -1):
+        if not want_bwd(v):
+            continue
+        j = v - 1
+        op = ops[j]
+        xshape = value(v).shape
+        dz = dS.reshape(xshape).copy() if v == nval - 1 else np.zeros(xshape)
+        for k, slot_i in readers[v]:
+            rk = ops[k]
+            gk = G(k + 1)
+            if rk.type == W.OP_CBA:
+                dz += orc.conv_dgrad(gk, weights(k), xshape, rk.stride, rk.pad, rk.groups)
+            elif rk.type == W.OP_POOL:
+                if k not in pool_idx:
+                    pool_idx[k] = orc.maxpool_fwd(value(v), rk.k, rk.stride, rk.pad)[1]
+                dz += orc.maxpool_bwd(gk, pool_idx[k], xshape)
+            elif rk.type == W.OP_ADD:
+                dz += orc.act_bwd(gk, pre_of(k), rk.act)
+            else:
+                dz += rk.p[slot_i] * gk
+        if op.type != W.OP_CBA:
+            E[f"v{v}.dvalue"] = _max_rel(G(v), dz)
+            say(f"  bwd value {v}")
+            continue
+        # conv + BN + activation: back through the activation and the normalisation, then the weight gradient
+        p = pre_of(j)
+        mean, var = stats[j]
+        gamma = par[(j, W.P_GAMMA)]
+        near = np.zeros(p.shape, dtype=bool)
+        if op.act != W.ACT_NONE:
+            near |= np.abs(p) < floor
+        if op.act == W.ACT_RELU6:
+            near |= np.abs(p - 6.0) < floor
+        # a channel whose convolution output is one constant (a dead input channel: all zeros) normalises to
+        # exactly beta in any arithmetic: its mask bits are decided
+        near &= (var > 0.0)[None, :, None, None]
+        dpre = orc.act_bwd(dz, p, op.act)
+        dconv, dgam, dbet = orc.bn_train_bwd(dpre, y_of(j), gamma, mean, var, EPS)
+        # largest influence of the undecided elements on the channel sums (and through them on every element)
+        xhat_max = float(np.max(np.abs((y_of(j) - mean[None, :, None, None]) / np.sqrt(var + EPS)[None, :, None, None])))
+        slack = np.sum(np.abs(dz) * near, axis=(0, 2, 3))
+        m = N * p.shape[2] * p.shape[3]
+        gd = G(v)
+        scale = float(np.max(np.abs(dconv)))
+        per_ch = np.max(np.abs(gd - dconv) * ~near, axis=(0, 2, 3))
+        bump = np.abs(gamma) / np.sqrt(var + EPS) * slack * (1.0 + xhat_max ** 2) / m
+        E[f"op{j}.dconv"] = float(np.max(np.maximum(per_ch - bump, 0.0)) / scale) if scale else 0.0
+        den = max(float(np.max(np.abs(dgam))), float(np.max(np.abs(dbet))))
+        gg = d.read_tensor(pbd.PBD_GRAD, 1, b, j, W.P_GAMMA, gamma.shape)
+        gb = d.read_tensor(pbd.PBD_GRAD, 1, b, j, W.P_BETA, gamma.shape)
+        E[f"op{j}.dgamma"] = float(np.max(np.maximum(np.abs(gg - dgam) - slack * xhat_max, 0.0)) / den) if den else 0.0
+        E[f"op{j}.dbeta"] = float(np.max(np.maximum(np.abs(gb - dbet) - slack, 0.0)) / den) if den else 0.0
+        T[f"op{j}.undecided"] = float(np.mean(near))
+        # the weight gradient from the gradient the library itself stored
+        wshape = par[(j, W.P_WEIGHT)].shape
+        gw = d.read_tensor(pbd.PBD_GRAD, 1, b, j, W.P_WEIGHT, wshape)
+        E[f"op{j}.dW"] = _max_rel(gw, orc.conv_wgrad(gd, value(op.inputs[0]), op.k, op.stride, op.pad, op.groups))
+        # first step: momentum = gradient, parameter = start - lr * gradient (float32 arithmetic on both sides)
+        for slot, g32 in ((W.P_WEIGHT, gw), (W.P_GAMMA, gg), (W.P_BETA, gb)):
+            shp = par[(j, slot)].shape
+            T[f"op{j}.mom{slot}"] = _max_rel(d.read_tensor(pbd.PBD_MOMENTUM, 1, b, j, slot, shp), g32)
+            new = d.read_tensor(pbd.PBD_PARAM, 1, b, j, slot, shp)
+            ref = par[(j, slot)].astype(np.float32).astype(np.float64) - lr * g32.astype(np.float64)
+            T[f"op{j}.upd{slot}"] = float(np.max(np.abs(new - ref)) / max(float(np.max(np.abs(ref))), 1e-30))
+        say(f"  bwd value {v} (op{j})")
+    return E, T
+
+
+TOL_BF16 = 2e-2      # losses, values, gradients (max-norm relative error per tensor)
+TOL_F32 = 1e-4       # quantities computed in float32 from the same inputs: statistics, momentum, update
+
+
+def run_and_check(wl, batch, selection=None):
+    """Relay once, then step and walk each block (all of them, or {block: (fwd_ops, bwd_values)}); asserts the
+    bounds and returns the worst error per kind of tensor."""
+    import time
+
+    import torch
+
+    import parity
+    d = parity.make_distiller(wl, batch, "bf16")
+    d.teacher_relay(torch.from_numpy(W.make_input(wl, batch=batch)).cuda())
+    worst = {}
+    for b in (sorted(selection) if selection is not None else range(wl.B)):
+        t0 = time.time()
+        d.student_step(b + 1, wl.lr)
+        d.sync()
+        fwd_ops, bwd_values = selection[b] if selection is not None else (None, None)
+        E, T = check_block(d, wl, b, student_params(wl, b), wl.lr, fwd_ops=fwd_ops, bwd_values=bwd_values)
+        und = {k: v for k, v in T.items() if k.endswith(".undecided")}
+        T = {k: v for k, v in T.items() if not k.endswith(".undecided")}
+        kinds = sorted({k.split(".")[-1] for k in E})
+        summary = ", ".join(f"{kind} {max(v for k, v in E.items() if k.split('.')[-1] == kind):.1e}" for kind in kinds)
+        print(f"[{wl.name} N={batch}] block {b + 1}: {len(E)} tensors in {time.time() - t0:.1f} s; worst per kind: {summary}; "
+              f"float32 quantities {max(T.values()) if T else 0:.1e}; undecided mask bits {max(und.values()) if und else 0:.1e}",
+              flush=True)
+        bad = {k: v for k, v in E.items() if not v < TOL_BF16}
+        assert not bad, (b, dict(sorted(bad.items(), key=lambda kv: -kv[1])[:8]))
+        bad = {k: v for k, v in T.items() if not v < TOL_F32}
+        assert not bad, (b, dict(sorted(bad.items(), key=lambda kv: -kv[1])[:8]))
+        assert all(v < 1e-3 for v in und.values()), und
+        for k, v in E.items():
+            kind = k.split(".")[-1]
+            worst[kind] = max(worst.get(kind, 0.0), v)
+    return worst
