@@ -45,7 +45,15 @@ def student_params(wl, b, overrides=None):
     return out
 
 
-def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, log=None):
+def stored(a, precision):
+    """A tensor as the path stores it: bfloat16 codes (nearest even) or float32."""
+    a = np.asarray(a, dtype=np.float64)
+    if precision == "bf16":
+        return orc.round_bf16(a).reshape(a.shape)
+    return a.astype(np.float32).astype(np.float64)
+
+
+def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, log=None, precision="bf16"):
     """d: a Distiller whose block b has just been stepped ONCE from the parameters `par` (momentum 0, running
     statistics (0, 1)) on the relayed activations it still holds.  Returns ({name: max-norm relative error},
     {name: error of a quantity that must agree to float32 rounding}).  fwd_ops / bwd_values restrict the walk
@@ -54,7 +62,7 @@ def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, lo
     ops = blk.ops
     nval = len(ops) + 1
     N = d.batch
-    R = orc.round_bf16
+    R = lambda a: stored(a, precision)
     E, T = {}, {}
     say = log or (lambda s: None)
     want_fwd = (lambda j: True) if fwd_ops is None else (lambda j: j in fwd_ops)
@@ -73,7 +81,7 @@ def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, lo
                 if e.code != -4:
                     raise
                 j = v - 1
-                vals[v] = R(orc.act_fwd(pre_of(j), ops[j].act)).reshape(pre_of(j).shape)
+                vals[v] = R(orc.act_fwd(pre_of(j), ops[j].act))
         return vals[v]
 
     def y_of(j):
@@ -95,7 +103,7 @@ def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, lo
 
     def weights(j):
         if j not in wq:
-            wq[j] = R(par[(j, W.P_WEIGHT)]).reshape(par[(j, W.P_WEIGHT)].shape)     # the bf16 compute copy
+            wq[j] = R(par[(j, W.P_WEIGHT)])     # the compute copy of the master weights
         return wq[j]
 
     # ---- forward --------------------------------------------------------------------------------------
@@ -224,7 +232,27 @@ TOL_BF16 = 2e-2      # losses, values, gradients (max-norm relative error per te
 TOL_F32 = 1e-4       # quantities computed in float32 from the same inputs: statistics, momentum, update
 
 
-def run_and_check(wl, batch, selection=None):
+def teacher_block_error(d, wl, b, images=None):
+    """A_{b+1} as the library relayed it against the plain fp64 oracle's T_{b+1} applied to the library's own
+    A_b (the frozen teacher normalises with its running statistics, so every image stands alone and a few
+    sampled images can be checked at any batch size).  Max-norm relative error over the sampled images."""
+    shapes = W.activation_shapes(wl)
+    tb = wl.teacher[b]
+    probe = W.Workload("probe", 1, shapes[b], [tb], [tb], wl.precision, lr=wl.lr)
+    words, pool = W.pack(probe)
+    imgs = list(range(d.batch)) if images is None else list(images)
+    o = orc.Oracle(words, pool, len(imgs))
+    for (j, slot), shape in W.param_shapes(wl, W.NET_TEACHER, b).items():
+        arr = W.make_param(wl, W.NET_TEACHER, b, j, slot, shape)
+        # the teacher's weights are stored in the path's tensor type; its folded BN terms are float32
+        o.set_param(W.NET_TEACHER, 0, j, slot, stored(arr, "bf16" if d.precision == pbd.PBD_BF16 else "f32")
+                    if slot == W.P_WEIGHT else arr)
+    a_prev, a_next = d.read_act(b)[imgs], d.read_act(b + 1)[imgs]
+    ref = o.teacher_relay(a_prev)[1]
+    return _max_rel(a_next.ravel(), ref)
+
+
+def run_and_check(wl, batch, selection=None, precision="bf16", force_direct=False):
     """Relay once, then step and walk each block (all of them, or {block: (fwd_ops, bwd_values)}); asserts the
     bounds and returns the worst error per kind of tensor."""
     import time
@@ -232,15 +260,22 @@ def run_and_check(wl, batch, selection=None):
     import torch
 
     import parity
-    d = parity.make_distiller(wl, batch, "bf16")
+    tol = TOL_BF16 if precision == "bf16" else TOL_F32
+    d = parity.make_distiller(wl, batch, precision, force_direct)
     d.teacher_relay(torch.from_numpy(W.make_input(wl, batch=batch)).cuda())
     worst = {}
+    if selection is None:
+        for b in range(wl.B):
+            err = teacher_block_error(d, wl, b)
+            worst["teacher"] = max(worst.get("teacher", 0.0), err)
+            assert err < tol, (b, err)
     for b in (sorted(selection) if selection is not None else range(wl.B)):
         t0 = time.time()
         d.student_step(b + 1, wl.lr)
         d.sync()
         fwd_ops, bwd_values = selection[b] if selection is not None else (None, None)
-        E, T = check_block(d, wl, b, student_params(wl, b), wl.lr, fwd_ops=fwd_ops, bwd_values=bwd_values)
+        E, T = check_block(d, wl, b, student_params(wl, b), wl.lr, fwd_ops=fwd_ops, bwd_values=bwd_values,
+                           precision=precision)
         und = {k: v for k, v in T.items() if k.endswith(".undecided")}
         T = {k: v for k, v in T.items() if not k.endswith(".undecided")}
         kinds = sorted({k.split(".")[-1] for k in E})
@@ -248,7 +283,7 @@ def run_and_check(wl, batch, selection=None):
         print(f"[{wl.name} N={batch}] block {b + 1}: {len(E)} tensors in {time.time() - t0:.1f} s; worst per kind: {summary}; "
               f"float32 quantities {max(T.values()) if T else 0:.1e}; undecided mask bits {max(und.values()) if und else 0:.1e}",
               flush=True)
-        bad = {k: v for k, v in E.items() if not v < TOL_BF16}
+        bad = {k: v for k, v in E.items() if not v < tol}
         assert not bad, (b, dict(sorted(bad.items(), key=lambda kv: -kv[1])[:8]))
         bad = {k: v for k, v in T.items() if not v < TOL_F32}
         assert not bad, (b, dict(sorted(bad.items(), key=lambda kv: -kv[1])[:8]))
