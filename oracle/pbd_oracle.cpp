@@ -313,6 +313,20 @@ void sgd(R* w, R* v, const R* g, size_t n, R lr, R mu) {
   }
 }
 
+// Gradient of the loss with respect to the architecture parameters of one weighted sum
+// z = sum_k p_k y_k, p = softmax(alpha) (Sec. VI-A, the architecture round), given dL/dz:
+//   g_k = <dL/dz, y_k>,   dL/dalpha_j = p_j (g_j - sum_k p_k g_k)      (dp_k/dalpha_j = p_k ([k == j] - p_j))
+template <class R>
+void mix_alpha_grad(const R* dz, const R* const* y, const R* p, int n, size_t numel, R* dalpha) {
+  std::vector<R> g(n, R(0));
+  R mean = 0;
+  for (int k = 0; k < n; ++k) {
+    for (size_t i = 0; i < numel; ++i) g[k] += dz[i] * y[k][i];
+    mean += p[k] * g[k];
+  }
+  for (int k = 0; k < n; ++k) dalpha[k] = p[k] * (g[k] - mean);
+}
+
 // nearest-even rounding to bfloat16 (8 significand bits), the storage type of the bf16 path
 inline double round_bf16(double v) {
   float f = (float)v;
@@ -797,15 +811,9 @@ struct Net final : NetBase {
       } else {
         const std::vector<R> p = probs(b, j);
         if (arch) {
-          // z = sum_k p_k y_k, p = softmax(alpha):  dp_k/dalpha_j = p_k ([k == j] - p_j)
-          std::vector<R> g(o.nin, R(0));
-          R mean = 0;
-          for (int k = 0; k < o.nin; ++k) {
-            const std::vector<R>& y = v[o.in[k]];
-            for (size_t i = 0; i < dy.size(); ++i) g[k] += dy[i] * y[i];
-            mean += p[k] * g[k];
-          }
-          for (int k = 0; k < o.nin; ++k) alpha_g[b][j][k] = p[k] * (g[k] - mean);
+          std::vector<const R*> ys(o.nin);
+          for (int k = 0; k < o.nin; ++k) ys[k] = v[o.in[k]].data();
+          mix_alpha_grad(dy.data(), ys.data(), p.data(), o.nin, dy.size(), alpha_g[b][j].data());
         }
         for (int k = 0; k < o.nin; ++k) {
           std::vector<R> g(dy.size());
@@ -993,6 +1001,11 @@ void orc_maxpool_fwd(const double* x, double* y, int32_t* idx, int N, int C, int
 void orc_maxpool_bwd(const double* dy, const int32_t* idx, double* dx, int N, int C, int H, int W,
                      int P, int Q) {
   maxpool_bwd(dy, idx, dx, N, C, H, W, P, Q);
+}
+void orc_mix_alpha_grad(const double* dz, const double* ys, const double* p, int n, long numel, double* dalpha) {
+  std::vector<const double*> y(n);
+  for (int k = 0; k < n; ++k) y[k] = ys + (size_t)k * (size_t)numel;
+  mix_alpha_grad(dz, y.data(), p, n, (size_t)numel, dalpha);
 }
 double orc_mse(const double* s, const double* t, double* ds, long M) { return mse(s, t, ds, (size_t)M); }
 void orc_sgd(double* w, double* v, const double* g, long n, double lr, double mu) {

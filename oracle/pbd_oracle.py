@@ -81,6 +81,7 @@ def lib():
         L.orc_act_bwd.argtypes = [_dp, _dp, _dp, C.c_long, C.c_int]
         L.orc_maxpool_fwd.argtypes = [_dp, _dp, _ip] + [C.c_int] * 7
         L.orc_maxpool_bwd.argtypes = [_dp, _ip, _dp] + [C.c_int] * 6
+        L.orc_mix_alpha_grad.argtypes = [_dp, _dp, _dp, C.c_int, C.c_long, _dp]
         L.orc_mse.restype = C.c_double
         L.orc_mse.argtypes = [_dp, _dp, _dp, C.c_long]
         L.orc_sgd.argtypes = [_dp, _dp, _dp, C.c_long, C.c_double, C.c_double]
@@ -205,6 +206,16 @@ def maxpool_bwd(dy, idx, x_shape):
     lib().orc_maxpool_bwd(_d(dy), idx.ctypes.data_as(_ip), _d(dx), N, Cc, H, W,
                           dy.shape[2], dy.shape[3])
     return dx
+
+
+def mix_alpha_grad(dz, ys, p):
+    """dL/dalpha of one weighted sum z = sum_k softmax(alpha)_k y_k, from dL/dz, the candidates y_k and p."""
+    dz = _f64(dz).ravel()
+    ys = np.ascontiguousarray(np.stack([_f64(y).ravel() for y in ys]))
+    p = _f64(p).ravel()
+    out = np.empty(p.size)
+    lib().orc_mix_alpha_grad(_d(dz), _d(ys), _d(p), p.size, dz.size, _d(out))
+    return out
 
 
 def mse(s, t):

@@ -155,3 +155,23 @@ def test_relay_arch_step_is_the_per_block_round():
     assert np.array_equal(la, np.array(lb))
     for j, n in mix_ops(wl):
         assert np.array_equal(a.get_alpha(0, j, n), b.get_alpha(0, j, n))
+
+
+def test_mix_alpha_grad_primitive_against_autograd():
+    """The exported primitive on its own: dL/dalpha of z = sum_k softmax(alpha)_k y_k for a linear loss <c, z>
+    against PyTorch autograd with alpha as a leaf, and its two invariants (components sum to zero; identical
+    candidates give zero)."""
+    import torch
+    g = np.random.default_rng(3)
+    n, numel = 5, 257
+    ys = g.standard_normal((n, numel))
+    c = g.standard_normal(numel)
+    alpha = torch.tensor(g.standard_normal(n), dtype=torch.float64, requires_grad=True)
+    p = torch.softmax(alpha, 0)
+    loss = torch.dot(torch.from_numpy(c), (p[:, None] * torch.from_numpy(ys)).sum(0))
+    (ref,) = torch.autograd.grad(loss, alpha)
+    got = orc.mix_alpha_grad(c, list(ys), p.detach().numpy())
+    np.testing.assert_allclose(got, ref.numpy(), rtol=1e-12, atol=1e-14)
+    assert abs(got.sum()) < 1e-12 * np.abs(got).max()
+    same = orc.mix_alpha_grad(c, [ys[0]] * n, p.detach().numpy())
+    assert np.abs(same).max() < 1e-12 * abs(np.dot(c, ys[0]))
