@@ -114,6 +114,11 @@ def layer_workloads():
     t.cba(0, 16, 3)
     v = s.cba(0, 40, 1); s.cba(v, 16, 3)
     wl("l_long_column", (24, 64, 64), t, s, 36)
+    # a long column that is no multiple of any tile height: 18000 rows (70 tiles of 256 rows and a ragged 80-row one)
+    t, s = W.Block(), W.Block()
+    t.cba(0, 64, 3)
+    v = s.cba(0, 40, 1); s.cba(v, 64, 3)
+    wl("l_ragged_long", (24, 60, 60), t, s, 5)
     return out
 
 

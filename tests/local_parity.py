@@ -252,7 +252,7 @@ def teacher_block_error(d, wl, b, images=None):
     return _max_rel(a_next.ravel(), ref)
 
 
-def run_and_check(wl, batch, selection=None, precision="bf16", force_direct=False):
+def run_and_check(wl, batch, selection=None, precision="bf16", force_direct=False, overrides=None):
     """Relay once, then step and walk each block (all of them, or {block: (fwd_ops, bwd_values)}); asserts the
     bounds and returns the worst error per kind of tensor."""
     import time
@@ -262,6 +262,11 @@ def run_and_check(wl, batch, selection=None, precision="bf16", force_direct=Fals
     import parity
     tol = TOL_BF16 if precision == "bf16" else TOL_F32
     d = parity.make_distiller(wl, batch, precision, force_direct)
+    if overrides:      # e.g. {W.P_BETA: 10.0}: every student tensor of that slot, on both sides
+        for b in range(wl.B):
+            for (j, slot), shape in W.param_shapes(wl, W.NET_STUDENT, b).items():
+                if slot in overrides:
+                    d.load_param(W.NET_STUDENT, b, j, slot, np.full(shape, overrides[slot], dtype=np.float32))
     d.teacher_relay(torch.from_numpy(W.make_input(wl, batch=batch)).cuda())
     worst = {}
     if selection is None:
@@ -274,7 +279,7 @@ def run_and_check(wl, batch, selection=None, precision="bf16", force_direct=Fals
         d.student_step(b + 1, wl.lr)
         d.sync()
         fwd_ops, bwd_values = selection[b] if selection is not None else (None, None)
-        E, T = check_block(d, wl, b, student_params(wl, b), wl.lr, fwd_ops=fwd_ops, bwd_values=bwd_values,
+        E, T = check_block(d, wl, b, student_params(wl, b, overrides), wl.lr, fwd_ops=fwd_ops, bwd_values=bwd_values,
                            precision=precision)
         und = {k: v for k, v in T.items() if k.endswith(".undecided")}
         T = {k: v for k, v in T.items() if not k.endswith(".undecided")}
