@@ -148,6 +148,10 @@ struct IgemmArgs {
   // igemm_dma_kernel only: the first big_tiles workgroups take 256-row tiles (tiles_n per row tile), the others
   // 64-row tiles over the rows from tail_m0 on
   int big_tiles, tail_m0;
+  // igemm_dma_kernel, backward-data with stride 2 only: the rows are taken parity class by parity class of the
+  // input pixel (class id = 2 (h % 2) + w % 2; only the taps of matching parity reach such a pixel), par_classes
+  // of them in the order par_order lists (2 bits per class id); 0: rows in pixel order, every tap tested
+  int par_classes, par_order;
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel

@@ -277,9 +277,33 @@ inline DwWgradCfg dw_wgrad_cfg(bool bf16, int N, int h_out, int w_out, int Cp, i
   return w;
 }
 
-struct WgradCfg { int TM, TN, BKP, tiles_k, tiles_j, splits, pix_per_split; };
-WgradCfg wgrad_cfg(long M, int K, int J) {
+struct WgradCfg { int TM, TN, BKP, tiles_k, tiles_j, splits, pix_per_split; bool dma; };
+// taps = R * S of the layer (J = taps * C).  Layers with a filter (taps > 1), whole 64- or 96-channel groups and a
+// long pixel range take wgrad_dma_kernel: TM x 256 tiles, one workgroup per compute unit, the pixel range cut
+// so that about 256 workgroups result.  Everything else (1 x 1 layers, which are bound by memory, stems) keeps
+// wgrad_tr_kernel.
+WgradCfg wgrad_cfg(long M, int K, int J, int taps) {
   WgradCfg w;
+  w.dma = false;
+  // (measured on the 3 x 3 layers of ResNet-50 x1.5 at batch 256: 192 channels 274 -> 184 us, 768 channels 265 -> 166 us,
+  // 384 channels 204 -> 190 us; tiles of 128, 96 or 64 channels are no faster than wgrad_tr_kernel and stay with it)
+  if (taps > 1 && M >= 8192 && J >= 512 && (K % 256 == 0 || K % 192 == 0) && (J / taps) % 8 == 0) {
+    w.dma = true;
+    w.TM = K % 256 == 0 ? 256 : 192;
+    w.TN = kWgradTN;
+    w.BKP = 32;
+    w.tiles_k = K / w.TM;
+    w.tiles_j = (J + w.TN - 1) / w.TN;
+    const long tiles = (long)w.tiles_k * w.tiles_j;
+    long splits = std::max(1L, 256 / tiles);
+    splits = std::min(splits, std::max(1L, (long)(256u << 20) / ((long)K * J * 4)));
+    splits = std::min(splits, (M + w.BKP - 1) / w.BKP);
+    long pps = (M + splits - 1) / splits;
+    pps = (pps + w.BKP - 1) / w.BKP * w.BKP;
+    w.pix_per_split = (int)pps;
+    w.splits = (int)((M + pps - 1) / pps);
+    return w;
+  }
   w.TM = K > 64 ? 128 : 64;       // a 128-wide tile that is 3/4 full still beats two 64-wide ones
   w.TN = J > 64 ? 128 : 64;
   w.BKP = 32;
@@ -322,16 +346,16 @@ int igemm_splits(long M, int NC, int Kred, int CA) { return igemm_cfg(M, NC, Kre
 
 // Launch shape of igemm_dma_kernel (256-row tiles, operands straight into LDS) for one dense layer, or use = false
 // when the layer keeps igemm_kernel: channel counts that are no multiple of 32, fewer tiles than most of the
-// compute units (there 128- and 64-row tiles and split-K fill the chip better), and 1 x 1 layers with a short
-// reduction (a handful of steps per tile: with one resident workgroup per unit the fill and the store of a tile are
-// not hidden behind another tile's work, and the 128-row kernel with two resident workgroups is as fast or faster;
-// measured on 256 x 56 x 56 x 256 -> 96 and 256 x 14 x 14 x 384 -> 1024).
+// compute units (there 128- and 64-row tiles and split-K fill the chip better), and reductions shorter than 256
+// (one or two steps per tile: nothing to pipeline).
 struct DmaCfg { bool use; int BN, BK, tiles_n, big_m, tail_m; };
-DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int taps, int num_cu) {
+DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu) {
   DmaCfg d{};
   if (CA % 32 != 0 || NC % 8 != 0 || NC < 64 || M < 4096) return d;
-  if (taps == 1 ? Kred < 512 : Kred < 256) return d;
-  d.BK = CA % 64 == 0 ? 64 : 32;
+#ifndef PBD_DMA_MIN_K_1X1
+#define PBD_DMA_MIN_K_1X1 256
+#endif
+  if (Kred < (Kred == CA ? PBD_DMA_MIN_K_1X1 : 256)) return d;
   const long tm = (M + kDmaBM - 1) / kDmaBM;
   // One workgroup per compute unit is resident: time ~ rounds x columns of the tile (a little more per column for
   // narrow tiles, whose fragments feed fewer MFMAs).  A last round that fills at most a quarter of the units is
@@ -343,19 +367,25 @@ DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int taps, int num_cu) {
   for (int i = 0; i < 5; ++i) {
     const int bn = kBN[i];
     const long tn = (NC + bn - 1) / bn, T = tm * tn;
-    const long full = T / num_cu, r = T % num_cu;
+    const long slots = (bn <= 128 ? 2 : 1) * (long)num_cu;       // (narrow tiles: two resident workgroups per unit)
+    const long full = T / slots, r = T % slots;
     double rounds = (double)full;
-    if (r) rounds += (full >= 1 && r <= num_cu / 4) ? 0.66 : 1.0;
-    const double t = rounds * bn * kCost[i];
+    if (r) rounds += (full >= 1 && r <= slots / 4) ? 0.66 : 1.0;
+    const double t = rounds * slots * bn * kCost[i];
     if (t < best) { best = t; d.BN = bn; d.tiles_n = (int)tn; }
   }
+  // K step 64 (128-byte rows) for the wide tiles; the narrow ones take 32, whose three stages fit twice in a
+  // compute unit's LDS, so that two workgroups hide each other's fill, barriers and store
+  // (256 x 56 x 56 x 64 -> 64, 3 x 3: 129 -> 113 us; 256 -> 96, 1 x 1: 152 -> 124 us)
+  d.BK = CA % 64 == 0 && d.BN >= 192 ? 64 : 32;
   const long T = tm * d.tiles_n;
   if (T < num_cu * 7 / 10) return d;       // (use stays false)
   d.use = true;
   d.big_m = (int)tm;
   d.tail_m = 0;
-  const long r = T % num_cu;
-  if (T >= num_cu && r && r <= num_cu / 4) {
+  const long slots = (d.BN <= 128 ? 2 : 1) * (long)num_cu;
+  const long r = T % slots;
+  if (T >= slots && r && r <= slots / 4) {
     const int cut = (int)((r + d.tiles_n - 1) / d.tiles_n);     // row tiles that go to the tail
     d.big_m = (int)tm - cut;
     d.tail_m = (int)((M - (long)d.big_m * kDmaBM + kDmaTailBM - 1) / kDmaTailBM);
@@ -459,7 +489,7 @@ int plan(pbd_ctx* c) {
                                              op.d.stride, op.d.pad);
           need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
-          const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p);
+          const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.d.k * op.d.k);
           need_red((size_t)w.splits * op.wn * 4);
           // per-row-tile batch-norm sums from the convolution's store (64-row tiles at most), and their regrouping
           need_red(((size_t)(M + 63) / 64 + kStatGroupsMax + 1) * 2 * op.cout_p * 4);
@@ -582,7 +612,7 @@ template <class T> struct Exec {
   }
   // the 256-row, direct-to-LDS kernel takes a launch when its tile count fills the chip and no split-K is wanted
   DmaCfg dma_for(long M, int NC, int Kred, int CA) const {
-    DmaCfg d = dma_cfg(M, NC, Kred, CA, Kred / CA, c->num_cu);
+    DmaCfg d = dma_cfg(M, NC, Kred, CA, c->num_cu);
     if (d.use && igemm_cfg(M, NC, Kred, CA).splits != 1) d.use = false;
     return d;
   }
@@ -623,7 +653,23 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
-    const DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA);
+    DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA);
+    if (MODE == 1 && g.par_classes) {
+      // parity classes: par_classes x ceil(rows of a class / 256) row tiles, no tail tiles
+      const long mc = (long)g.N * (g.HO / 2) * (g.WO / 2);
+      const int tm = (int)((mc + kDmaBM - 1) / kDmaBM);
+      // a class reduces over few taps: short tiles, for which two resident workgroups (narrow tile, K step 32)
+      // beat the wide tile (256 x 28 x 28 x 384, 3 x 3: 176 us at 128 columns, 222 us at 192; 56 x 56 x 192: 266 us
+      // at 96, 324 us at 192; 14 x 14 x 768: 187 us at 128, 189 us at 192)
+      int bn = 0;
+      for (int b : {128, 96, 64})
+        if (g.NC % b == 0) { bn = b; break; }
+      if (dc.use && bn && (long)tm * g.par_classes * (g.NC / bn) >= c->num_cu * 7 / 10) {
+        dc.BN = bn; dc.BK = 32; dc.tiles_n = g.NC / bn;
+        dc.big_m = tm * g.par_classes; dc.tail_m = 0;
+      }
+      else g.par_classes = 0;               // (the other kernels take the rows in pixel order)
+    }
     if (dc.use && (epi == EPI_STORE || epi == EPI_AFFINE_ACT || epi == EPI_ACCUM)) {
       g.tiles_n = dc.tiles_n;
       g.tiles_m = dc.big_m + dc.tail_m;
@@ -698,6 +744,21 @@ template <class T> struct Exec {
         IgemmArgs g{N, op.out.h, op.out.w, op.d.c_out, op.in.h, op.in.w, op.cin_p, op.d.k, op.d.k,
                     op.d.stride, op.d.pad, N * op.in.h * op.in.w, op.d.k * op.d.k * op.d.c_out, 0,
                     (unsigned)((size_t)N * op.out.h * op.out.w * op.d.c_out * 2), (unsigned)(op.wn * 2)};
+        // stride 2: an input pixel is reached only by the taps of its own parity (1, 2, 2 and 4 of the 9 taps
+        // of a 3 x 3 kernel for the four pixel classes; one class only for a 1 x 1 kernel), so the rows are
+        // taken class by class, heaviest class first.  Classes no tap reaches hold zeros: an accumulating
+        // launch leaves them out.
+        if (op.d.stride == 2 && op.in.h % 2 == 0 && op.in.w % 2 == 0) {
+          int taps[4], order[4] = {0, 1, 2, 3}, n = 0;
+          for (int cl = 0; cl < 4; ++cl) {
+            const int r0 = ((cl >> 1) + op.d.pad) & 1, s0 = ((cl & 1) + op.d.pad) & 1;
+            taps[cl] = ((op.d.k - r0 + 1) / 2) * ((op.d.k - s0 + 1) / 2);
+          }
+          std::stable_sort(order, order + 4, [&](int a, int b) { return taps[a] > taps[b]; });
+          for (int i = 0; i < 4; ++i)
+            if (taps[order[i]] > 0 || !accumulate) { g.par_order |= order[i] << (2 * n); ++n; }
+          g.par_classes = n;
+        }
         launch_igemm<1>(g, (const bf16_t*)dy, (const bf16_t*)wt, (bf16_t*)dx, nullptr, nullptr, 0,
                         accumulate ? EPI_ACCUM : EPI_STORE, bytes, flops);
       }
@@ -717,7 +778,7 @@ template <class T> struct Exec {
     const double bytes = bytes_of(op.in) + bytes_of(op.out) + (double)op.wn * 4;
     if (mfma()) {
       if constexpr (sizeof(T) == 2) {
-        const WgradCfg w = wgrad_cfg(M, op.d.c_out, J);
+        const WgradCfg w = wgrad_cfg(M, op.d.c_out, J, op.d.k * op.d.k);
         const int pq = op.out.h * op.out.w;
         WgradTrArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                       op.d.stride, op.d.pad, (int)M, J, w.pix_per_split,
@@ -730,10 +791,16 @@ template <class T> struct Exec {
           char name[32];
           snprintf(name, sizeof name, "wgrad_%dx%d", w.TM, w.TN);
           ProfScope ps(c, name, bytes, flops, net, blk, opi);
+          if (w.dma) {
+#define PBD_WGD(TM_) launch(c, wgrad_dma_kernel<TM_>, grid, kDmaThreads, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g)
+            if (w.TM == 256) PBD_WGD(256); else PBD_WGD(192);
+#undef PBD_WGD
+          } else {
 #define PBD_WG(TM_, TN_) launch(c, wgrad_tr_kernel<TM_, TN_>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g)
-          if (w.TM == 128) { if (w.TN == 128) PBD_WG(128, 128); else PBD_WG(128, 64); }
-          else { if (w.TN == 128) PBD_WG(64, 128); else PBD_WG(64, 64); }
+            if (w.TM == 128) { if (w.TN == 128) PBD_WG(128, 128); else PBD_WG(128, 64); }
+            else { if (w.TN == 128) PBD_WG(64, 128); else PBD_WG(64, 64); }
 #undef PBD_WG
+          }
         }
         if (w.splits > 1) {
           ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);

@@ -119,6 +119,21 @@ def layer_workloads():
     t.cba(0, 64, 3)
     v = s.cba(0, 40, 1); s.cba(v, 64, 3)
     wl("l_ragged_long", (24, 60, 60), t, s, 5)
+    # stride-2 3 x 3 and stride-2 1 x 1 that both read an interior value (a bottleneck with projection shortcut
+    # in the middle of a block): their backward-data launches take the input pixels parity class by parity class,
+    # one storing (for the 1 x 1: three classes of zeros), one adding onto it; 25392 rows a class (99 tiles and a
+    # ragged one), in both orders
+    for name, shortcut_first in (("l_s2_classes", False), ("l_s2_classes_swapped", True)):
+        t, s = W.Block(), W.Block()
+        t.cba(0, 256, 3, 2)
+        v1 = s.cba(0, 192, 1)
+        if shortcut_first:
+            sc = s.cba(v1, 256, 1, 2, act=W.ACT_NONE)
+        v = s.cba(v1, 64, 3, 2); v = s.cba(v, 256, 1, act=W.ACT_NONE)
+        if not shortcut_first:
+            sc = s.cba(v1, 256, 1, 2, act=W.ACT_NONE)
+        s.add(v, sc, W.ACT_RELU)
+        wl(name, (24, 46, 46), t, s, 48)
     return out
 
 

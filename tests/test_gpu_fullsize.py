@@ -1,7 +1,8 @@
 """The layer-by-layer walk of local_parity.py at the FULL batch and image size of configurations 3-5, in the
 launch configuration the benchmark times, on the heaviest layers: elementwise against the plain fp64 oracle
 primitives at 2e-2.  Covered launch shapes: the 256-row direct-to-LDS implicit GEMM (forward and backward-data)
-with batch-norm sums taken from its store and more row tiles than one finalize walks, the weight gradient split
+with batch-norm sums taken from its store and more row tiles than one finalize walks, the stride-2 backward-data
+by parity classes, the weight gradient split
 768 ways over 802816 pixels, the residual add fused into a normalisation pass and its backward, a backward-data
 launch that accumulates onto another reader's gradient, the 256 x 128 tile of a 1.6 M-row pointwise layer, the
 5 x 5 and 7 x 7 depthwise tile kernels at 112 x 112, wide 1 x 1 layers over 12544 rows."""
@@ -21,12 +22,15 @@ def test_resnet50_stage1_and_stage4_layers_at_full_batch():
     wl = W.CONFIGS["resnet50_x1.5"]()
     ops = wl.student[0].ops
     assert (ops[3].k, ops[3].c_out, ops[9].k, ops[9].act, ops[10].type) == (3, 96, 1, W.ACT_NONE, W.OP_ADD)
+    assert (wl.student[3].ops[1].k, wl.student[3].ops[1].stride) == (3, 2)
     sel = {
         # stage 1 (56 x 56, 802816 rows): 3 x 3 96 -> 96; 1 x 1 96 -> 256 whose output only the fused add reads;
         # value 11 = that add's output, read by a 1 x 1 (backward-data) and by the next add (two gradients meet)
         0: ({3, 9, 10}, {4, 10, 11}),
-        # stage 4 (7 x 7, 12544 rows): 3 x 3 768 -> 768, 1 x 1 768 -> 2048 + fused add
-        3: ({6, 7, 8}, {7, 8}),
+        # stage 4: the stride-2 3 x 3 768 -> 768 from 14 x 14 (its backward-data takes the input pixels parity class
+        # by parity class and writes the gradient of value 1); at 7 x 7 (12544 rows) 3 x 3 768 -> 768 and
+        # 1 x 1 768 -> 2048 + fused add
+        3: ({1, 6, 7, 8}, {1, 7, 8}),
     }
     worst = local_parity.run_and_check(wl, wl.batch, sel)
     print("worst per kind:", {k: f"{v:.1e}" for k, v in sorted(worst.items())}, flush=True)
