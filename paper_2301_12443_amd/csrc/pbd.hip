@@ -310,13 +310,22 @@ WgradCfg wgrad_cfg(long M, int K, int J, int taps) {
   w.tiles_k = (K + w.TM - 1) / w.TM;
   w.tiles_j = (J + w.TN - 1) / w.TN;
   const long tiles = (long)w.tiles_k * w.tiles_j;
-  // long reductions: three workgroups per compute unit hide the load latency; short ones: one per
-  // compute unit, or the partial sums cost more than the overlap gains
-  const long target = M >= 32768 ? 768 : 256;
-  long splits = std::max(1L, (target + tiles - 1) / tiles);
+  // How many ways to cut the pixel range: q = ceil(tiles * splits / 256) workgroups share a compute unit; one alone
+  // leaves the matrix cores waiting for its loads, two run 1.55 x, three or more 2 x as fast together (768 ->
+  // 2048, 1 x 1, 12544 pixels, 96 tiles: 2 / 3 / 5 / 8 splits take 114 / 92 / 63 / 56 us); every split writes and
+  // re-reads K x J partial sums.  Time model: q * pixels per split * 18.2 ns (a 128 x 128 tile) / speed-up + partials
+  // at 3 TB/s; the smallest estimate wins, the fewest splits among equals.
   const long max_by_mem = std::max(1L, (long)(256u << 20) / ((long)K * J * 4));
-  splits = std::min(splits, max_by_mem);
-  splits = std::min(splits, (M + w.BKP - 1) / w.BKP);
+  const long smax = std::max(1L, std::min(std::min(max_by_mem, (M + w.BKP - 1) / w.BKP), (2048 + tiles - 1) / tiles));
+  const double c_pix = 18.2e-9 * (double)(w.TM * w.TN) / (128.0 * 128.0);
+  double best = 1e30;
+  long splits = 1;
+  for (long sp = 1; sp <= smax; ++sp) {
+    const long q = (tiles * sp + 255) / 256;
+    const double eff = q >= 3 ? 2.0 : q == 2 ? 1.55 : 1.0;
+    const double t = (double)q * ((double)M / sp) * c_pix / eff + (double)sp * K * J * 4.0 / 3e12;
+    if (t < best * 0.999) { best = t; splits = sp; }
+  }
   long pps = (M + splits - 1) / splits;
   pps = (pps + w.BKP - 1) / w.BKP * w.BKP;
   w.pix_per_split = (int)pps;
@@ -349,13 +358,15 @@ int igemm_splits(long M, int NC, int Kred, int CA) { return igemm_cfg(M, NC, Kre
 // compute units (there 128- and 64-row tiles and split-K fill the chip better), and reductions shorter than 256
 // (one or two steps per tile: nothing to pipeline).
 struct DmaCfg { bool use; int BN, BK, tiles_n, big_m, tail_m; };
-DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu) {
+// affine: the store applies a folded batch norm and activation (the frozen teacher's layers)
+DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu, bool affine) {
   DmaCfg d{};
   if (CA % 32 != 0 || NC % 8 != 0 || NC < 64 || M < 4096) return d;
-#ifndef PBD_DMA_MIN_K_1X1
-#define PBD_DMA_MIN_K_1X1 256
-#endif
-  if (Kred < (Kred == CA ? PBD_DMA_MIN_K_1X1 : 256)) return d;
+  // Short reductions are bound by the store, not by the loop.  Measured per layer inside the ResNet-50 x1.5 step:
+  // the student's 1 x 1 layers from 64 channels on gain (96 -> 256 at 56 x 56: 178 -> 162 us, 192 -> 512 at
+  // 28 x 28: 126 -> 96 us), the teacher's affine stores below 256 channels lose to the 128-row kernel, of which
+  // four workgroups share a compute unit (64 -> 256 with the residual: 244 -> 292 us).
+  if (Kred < (Kred == CA && !affine ? 64 : 256)) return d;
   const long tm = (M + kDmaBM - 1) / kDmaBM;
   // One workgroup per compute unit is resident: time ~ rounds x columns of the tile (a little more per column for
   // narrow tiles, whose fragments feed fewer MFMAs).  A last round that fills at most a quarter of the units is
@@ -611,8 +622,8 @@ template <class T> struct Exec {
     return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);      // (the 256-row kernel, where it is used, fuses it too)
   }
   // the 256-row, direct-to-LDS kernel takes a launch when its tile count fills the chip and no split-K is wanted
-  DmaCfg dma_for(long M, int NC, int Kred, int CA) const {
-    DmaCfg d = dma_cfg(M, NC, Kred, CA, c->num_cu);
+  DmaCfg dma_for(long M, int NC, int Kred, int CA, bool affine = false) const {
+    DmaCfg d = dma_cfg(M, NC, Kred, CA, c->num_cu, affine);
     if (d.use && igemm_cfg(M, NC, Kred, CA).splits != 1) d.use = false;
     return d;
   }
@@ -653,7 +664,7 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
-    DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA);
+    DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA, epi == EPI_AFFINE_ACT);
     if (MODE == 1 && g.par_classes) {
       // parity classes: par_classes x ceil(rows of a class / 256) row tiles, no tail tiles
       const long mc = (long)g.N * (g.HO / 2) * (g.WO / 2);

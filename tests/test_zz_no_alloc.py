@@ -64,7 +64,8 @@ def test_static_scratch_step_equals_the_workspace_step(precision, batch):
 def test_static_scratch_step_rejects_what_does_not_fit_and_bad_arguments():
     import torch
     L = pbd.lib()
-    wl, batch = [c for c in layer_workloads() if c[0].name == "l_deepK3x3"][0]
+    wl = [c for c in layer_workloads() if c[0].name == "l_deepK3x3"][0][0]
+    batch = 256       # 12544 pixels: the weight gradient of the 3 x 3 layer is cut into several pixel ranges
     d = parity.make_distiller(wl, batch=batch, precision="bf16")
     x = torch.from_numpy(W.make_input(wl, batch=batch)).cuda()
     loss = torch.zeros(1, device="cuda")
@@ -72,7 +73,8 @@ def test_static_scratch_step_rejects_what_does_not_fit_and_bad_arguments():
     assert L.pbd_student_step_static(d.h, 1, C.byref(v), C.byref(v), 0.1, loss.data_ptr()) == -4     # no relay yet
     views = d.teacher_relay(x)
     before = d.read_tensor(pbd.PBD_PARAM, 1, 0, 1, W.P_WEIGHT, (384, 384, 3, 3)).copy()
-    # 4 partial weight gradients of 384 x 3456 floats (21 MB): more than the 16 MiB array holds
+    # partial weight gradients of 384 x 3456 floats (5.3 MB) for each of four or more pixel ranges: more than the
+    # 16 MiB array holds
     rc = L.pbd_student_step_static(d.h, 1, C.byref(views[0]), C.byref(views[1]), 0.1, loss.data_ptr())
     assert rc == -3 and b"static" in L.pbd_last_error(d.h)
     d.sync()
