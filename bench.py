@@ -26,9 +26,11 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # under profiles/ (the record says so under roofline.traffic_source), and apply only to the workload
 # and the kernel build they were measured on.
 HBM_TRAFFIC_PER_LAUNCH = {
-    "vgg16_dsconv": ("profiles/vgg16_dsconv_step_hbm_traffic.md", {
-        "bn_bwd_reduce": 30546058, "bn_bwd_apply": 45063308, "bn_apply": 30114369, "bn_stats": 12422596,
-        "dw_wgrad_tile_k3": 27355086, "sum_partials": 7972637, "bn_small_bwd": 7983131, "bn_small_fwd": 5250496,
+    "resnet50_x1.5": ("profiles/resnet50_x1.5_step_hbm_traffic.md", {
+        "bn_bwd_apply": 369925203, "bn_bwd_reduce": 248252287, "join_bwd": 706521934, "mse_loss_grad": 578063144,
+        "wgrad_128x128": 308842427, "wgrad_192x256": 237297813, "wgrad_256x256": 218341142,
+        "igemm_fwd_256x192x64_store": 234746699, "igemm_dgrad_256x192x64_store": 167211701,
+        "igemm_fwd_256x256x64_affine": 181709559, "igemm_fwd_256x256x64_store": 221472085,
     }),
 }
 
@@ -229,6 +231,9 @@ def main():
                          "a few orders before the warm-up and keeping the fastest (any order computes the same bits)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch the step's kernels one by one (for rocprofv3 --pmc runs)")
+    ap.add_argument("--counter-run", action="store_true",
+                    help="for rocprofv3 --pmc runs, where every dispatch is serialised: no one-step-at-a-time timing, "
+                         "one event-timed step instead of 20, and a progress line on stderr after every phase")
     ap.add_argument("--classes", action="store_true", help="also print the per-kernel-class table to stderr")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure what this box reaches on a plain 1 GiB device copy and on a library "
@@ -265,6 +270,11 @@ def main():
                 d.teacher_prefix(x, i)
                 d.student_step(i, wl.lr)
 
+    def progress(what):
+        if args.counter_run:
+            print(f"[bench] {what}", file=sys.stderr, flush=True)
+
+    progress("set up")
     order = None
     if args.mode == "pipelined" and not args.no_tune and not args.no_graph:
         order = tune_pipeline_order(d, x, wl, torch)
@@ -272,9 +282,13 @@ def main():
         step()
     d.pipeline_flush()                  # (nothing to do outside the pipelined mode)
     torch.cuda.synchronize()
+    progress("warm-up done")
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for k in range(args.steps):
         step()
+        if args.counter_run:
+            torch.cuda.synchronize()
+            progress(f"step {k + 1} of {args.steps}")
     d.pipeline_flush()                  # the students' pass on the last batch belongs to the K steps
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -284,7 +298,7 @@ def main():
     # One step at a time: median over pbd_distill_step calls, each bracketed by two HIP events recorded on the
     # library's own stream (the stream its kernels run on), beside the mean of the pipelined steps above.
     one_step = None
-    if args.mode in ("pipelined", "relay"):
+    if args.mode in ("pipelined", "relay") and not args.counter_run:
         nev = max(20, min(args.steps, 50))
         for _ in range(3):
             d.distill_step(x, wl.lr)
@@ -300,7 +314,7 @@ def main():
                         samples_per_s=round(wl.batch / (med * 1e-3), 1), timer="HIP events on the library's stream")
 
     # per-kernel timings with HIP events on the library's stream (separate, profiled steps)
-    psteps = 20
+    psteps = 1 if args.counter_run else 20
     d.set_profile(True); d.reset_profile()
     for _ in range(psteps):
         if args.mode in ("arch", "two_round"):
@@ -309,6 +323,7 @@ def main():
             d.distill_step(x, wl.lr)
     prof = d.get_profile()
     d.set_profile(False)
+    progress("event-timed step done")
     roof, classes, totals = roofline_from_profile(prof, psteps)
     conv, elementwise = family_fractions(prof, psteps)
     src, table = HBM_TRAFFIC_PER_LAUNCH.get(args.config, (None, {}))

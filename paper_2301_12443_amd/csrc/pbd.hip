@@ -689,8 +689,8 @@ template <class T> struct Exec {
       g.tail_m0 = dc.big_m * kDmaBM;
       const dim3 grid(g.big_tiles + dc.tail_m * dc.tiles_n);
       static const char* const kEpiName[] = {"store", "affine", "accum"};
-      char name[32];
-      snprintf(name, sizeof name, "igemm_%s_256x%d_%s", MODE ? "dgrad" : "fwd", dc.BN, kEpiName[epi]);
+      char name[40];
+      snprintf(name, sizeof name, "igemm_%s_256x%dx%d_%s", MODE ? "dgrad" : "fwd", dc.BN, dc.BK, kEpiName[epi]);
       ProfScope ps(c, name, bytes, flops, net, blk, opi);
 #define PBD_DMA(BN_, BK_, EPI_) launch(c, igemm_dma_kernel<MODE, BN_, BK_, EPI_>, grid, kDmaThreads, 0, st, A, Bw, out, a, b, act, g)
 #define PBD_DMA_BK(BN_, EPI_) do { if (dc.BK == 64) PBD_DMA(BN_, 64, EPI_); else PBD_DMA(BN_, 32, EPI_); } while (0)
