@@ -32,12 +32,6 @@
 #pragma once
 #include "conv_kernels.h"
 
-#ifndef PBD_DMA_PROBE
-#define PBD_DMA_PROBE 0
-#endif
-#ifndef PBD_DMA_SETPRIO
-#define PBD_DMA_SETPRIO 0
-#endif
 
 namespace pbd {
 
@@ -96,10 +90,7 @@ constexpr int kDmaTailBM = 64;   // rows of a tail tile
 // waves along the rows of a big tile
 constexpr int dma_waves_m(int BN) { return BN == 256 ? 2 : (BN == 192 || BN == 128) ? 4 : 8; }
 // ring depth: what 160 KB of LDS hold
-#ifndef PBD_DMA_STAGES32
-#define PBD_DMA_STAGES32 3
-#endif
-constexpr int dma_stages(int BN, int BK) { return BK == 64 ? (BN >= 192 ? 2 : 3) : PBD_DMA_STAGES32; }
+constexpr int dma_stages(int BN, int BK) { return BK == 64 && BN >= 192 ? 2 : 3; }
 constexpr int dma_lds_bytes(int BN, int BK, bool accum) {
   const int ring = dma_stages(BN, BK) * (kDmaBM + BN) * BK * 2;
   const int out = 128 * (BN * (accum ? 4 : 2) + 16);   // 128 staged output rows
@@ -203,18 +194,12 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
       const int h = MODE == 0 ? rh[i] + r : rh[i] - r, w = MODE == 0 ? rw[i] + s : rw[i] - s;
       bool ok = (unsigned)h < hlim && (unsigned)w < wlim;
       if (MODE == 1) ok = ok && ((h | w) & smask) == 0;
-#if PBD_DMA_PROBE == 1 || PBD_DMA_PROBE == 3      // (microbenchmark builds only: leave the A loads out to see what they cost)
-      (void)ok;
-#else
       dma_load16(a_rsrc, sa + i * 8 * 1024, ok ? abase[i] + delta : kOutOfRange);
-#endif
     }
 #pragma unroll
     for (int i = 0; i < B_INSTR; ++i) {
       if ((i * 8 + wave) * 64 >= B_CHUNKS) continue;
-#if PBD_DMA_PROBE != 2 && PBD_DMA_PROBE != 3
       dma_load16(b_rsrc, sa + A_BYTES + i * 8 * 1024, bbase[i] == kOutOfRange ? kOutOfRange : bbase[i] + kk * 2u);
-#endif
     }
     c += BK;
     const bool wrap = c >= g.CA;
@@ -280,17 +265,11 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
         // LDS reads return in order: the older group is complete once at most the newer group's reads are pending
         if (ks + 1 < KS) wait_lgkmcnt<TM + TN>(); else wait_lgkmcnt<0>();
         pin_frag(cur);
-#if PBD_DMA_SETPRIO
-        __builtin_amdgcn_s_setprio(PBD_DMA_SETPRIO);
-#endif
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int j = 0; j < TN; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur.b[j], cur.a[i], acc[i][j], 0, 0, 0);
-#if PBD_DMA_SETPRIO
-        __builtin_amdgcn_s_setprio(0);
-#endif
         __builtin_amdgcn_sched_barrier(0);      // keep the next group's reads behind these MFMAs' issue, not ahead of the wait
       }
     }

@@ -358,9 +358,10 @@ int igemm_splits(long M, int NC, int Kred, int CA) { return igemm_cfg(M, NC, Kre
 // compute units (there 128- and 64-row tiles and split-K fill the chip better), and reductions shorter than 256
 // (one or two steps per tile: nothing to pipeline).
 struct DmaCfg { bool use; int BN, BK, tiles_n, big_m, tail_m; };
-// affine: the store applies a folded batch norm and activation (the frozen teacher's layers)
-DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu, bool affine) {
+// epi: what the store does (EPI_AFFINE_ACT: a folded batch norm and activation, the frozen teacher's layers)
+DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu, int epi) {
   DmaCfg d{};
+  const bool affine = epi == EPI_AFFINE_ACT;
   if (CA % 32 != 0 || NC % 8 != 0 || NC < 64 || M < 4096) return d;
   // Short reductions are bound by the store, not by the loop.  Measured per layer inside the ResNet-50 x1.5 step:
   // the student's 1 x 1 layers from 64 channels on gain (96 -> 256 at 56 x 56: 178 -> 162 us, 192 -> 512 at
@@ -372,11 +373,18 @@ DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu, bool affine) {
   // narrow tiles, whose fragments feed fewer MFMAs).  A last round that fills at most a quarter of the units is
   // run as 64-row tail tiles instead, which costs two thirds of a round (a tail tile still loads the whole
   // weight tile: measured 275.7 -> 252.6 us on 256 x 28 x 28 x 256 -> 256, 3 x 3, 784 tiles).
+  // Short reductions behind a store without batch-norm sums (the teacher's, the accumulating backward-data ones)
+  // run faster as two narrow workgroups per compute unit than as one wide one: one fills while the other stores
+  // (1024 -> 256 at 14 x 14, affine: 91 -> 66 us; 256 -> 96 accumulating at 56 x 56: 198 -> 176 us); with the sums
+  // in the store the wide tile stays ahead (192 -> 512 at 28 x 28: 97 against 103 us).  Measured per layer inside
+  // the ResNet-50 x1.5 step.
+  const bool narrow = (epi == EPI_AFFINE_ACT || epi == EPI_ACCUM) && (Kred <= 512 || (affine && Kred <= 1024 && NC >= 512));
   static const int kBN[5] = {256, 192, 128, 96, 64};
   static const double kCost[5] = {1.0, 1.05, 1.15, 1.25, 1.4};
   double best = 1e30;
   for (int i = 0; i < 5; ++i) {
     const int bn = kBN[i];
+    if (narrow && bn > 128) continue;
     const long tn = (NC + bn - 1) / bn, T = tm * tn;
     const long slots = (bn <= 128 ? 2 : 1) * (long)num_cu;       // (narrow tiles: two resident workgroups per unit)
     const long full = T / slots, r = T % slots;
@@ -622,8 +630,8 @@ template <class T> struct Exec {
     return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);      // (the 256-row kernel, where it is used, fuses it too)
   }
   // the 256-row, direct-to-LDS kernel takes a launch when its tile count fills the chip and no split-K is wanted
-  DmaCfg dma_for(long M, int NC, int Kred, int CA, bool affine = false) const {
-    DmaCfg d = dma_cfg(M, NC, Kred, CA, c->num_cu, affine);
+  DmaCfg dma_for(long M, int NC, int Kred, int CA, int epi = EPI_STORE) const {
+    DmaCfg d = dma_cfg(M, NC, Kred, CA, c->num_cu, epi);
     if (d.use && igemm_cfg(M, NC, Kred, CA).splits != 1) d.use = false;
     return d;
   }
@@ -664,7 +672,7 @@ template <class T> struct Exec {
   template <int MODE>
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
-    DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA, epi == EPI_AFFINE_ACT);
+    DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA, epi);
     if (MODE == 1 && g.par_classes) {
       // parity classes: par_classes x ceil(rows of a class / 256) row tiles, no tail tiles
       const long mc = (long)g.N * (g.HO / 2) * (g.WO / 2);
