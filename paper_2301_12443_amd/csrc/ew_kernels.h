@@ -42,7 +42,17 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, unsigne
 constexpr unsigned kOutOfRange = 0x80000000u;   // byte offset beyond any tensor (they are < 2^31 elements)
 
 template <class T> struct IO;
+// ld_raw() only starts the 16- or 32-byte load, unpack() converts later: a loop that calls ld_raw() for all its rows,
+// then __builtin_amdgcn_sched_barrier(0), then unpack() has every load in flight before the first wait (left to
+// itself the scheduler pairs each load with its conversion and the loads go out one at a time).
 template <> struct IO<float> {
+  struct Raw { float4 a, b; };
+  static __device__ __forceinline__ Raw ld_raw(const float* p) {
+    Raw q; q.a = reinterpret_cast<const float4*>(p)[0]; q.b = reinterpret_cast<const float4*>(p)[1]; return q;
+  }
+  static __device__ __forceinline__ void unpack(const Raw& q, float v[8]) {
+    v[0] = q.a.x; v[1] = q.a.y; v[2] = q.a.z; v[3] = q.a.w; v[4] = q.b.x; v[5] = q.b.y; v[6] = q.b.z; v[7] = q.b.w;
+  }
   static __device__ __forceinline__ void ld(const float* p, float v[8]) {
     const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -53,6 +63,12 @@ template <> struct IO<float> {
   }
 };
 template <> struct IO<bf16_t> {
+  typedef uint4 Raw;
+  static __device__ __forceinline__ Raw ld_raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  static __device__ __forceinline__ void unpack(const Raw& u, float v[8]) {
+    v[0] = bf_lo(u.x); v[1] = bf_hi(u.x); v[2] = bf_lo(u.y); v[3] = bf_hi(u.y);
+    v[4] = bf_lo(u.z); v[5] = bf_hi(u.z); v[6] = bf_lo(u.w); v[7] = bf_hi(u.w);
+  }
   static __device__ __forceinline__ void ld(const bf16_t* p, float v[8]) {
     const uint4 u = *reinterpret_cast<const uint4*>(p);
     v[0] = bf_lo(u.x); v[1] = bf_hi(u.x); v[2] = bf_lo(u.y); v[3] = bf_hi(u.y);
@@ -95,18 +111,24 @@ template <> struct BufIO<float> {
   }
 };
 
+// Written as selects on two values derived from `act` (a clamp bound that no value reaches unless the layer is a
+// ReLU6, and "no rectifier at all"), not as a branch per case: `act` is a launch argument, the kernels call this
+// per element inside their loops, and the compiler keeps a branch chain per element otherwise.  Same value as the
+// case-by-case definition for every input, NaN and infinities included:
+//   ReLU: v > 0 ? v : 0;  ReLU6: v > 0 ? min(v, 6) : 0;  none: v
 __device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == ACT_RELU) return v > 0.f ? v : 0.f;
-  if (act == ACT_RELU6) return v > 0.f ? (v < 6.f ? v : 6.f) : 0.f;
-  return v;
+  const bool all = act != ACT_RELU && act != ACT_RELU6;
+  const float hi = act == ACT_RELU6 ? 6.f : __builtin_nanf("");     // (v >= NaN never holds)
+  const float t = v >= hi ? hi : v;
+  return (all || v > 0.f) ? t : 0.f;
 }
-// slope of the activation at pre-activation v (1 where it passes the gradient)
+// slope of the activation at pre-activation v (1 where it passes the gradient):
+//   ReLU: v > 0;  ReLU6: 0 < v < 6;  none: always
 __device__ __forceinline__ bool act_pass(float v, int act) {
-  if (act == ACT_RELU) return v > 0.f;
-  if (act == ACT_RELU6) return v > 0.f && v < 6.f;
-  return true;
+  const bool all = act != ACT_RELU && act != ACT_RELU6;
+  const float hi = act == ACT_RELU6 ? 6.f : __builtin_nanf("");
+  return all || (v > 0.f && !(v >= hi));
 }
-
 // ---------------------------------------------------------------------------
 // layout / cast:  x float32 NCHW  ->  A_0  T NHWC with Cp channels (pads = 0)
 // ---------------------------------------------------------------------------
@@ -236,21 +258,28 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
     mu[k] = mean[c]; a[k] = gamma[c] * invstd[c]; b[k] = beta[c];
   }
   long r = r0 + row_lane;
-  for (; r + 3 * rl < r1; r += 4 * rl) {
-    float v[4][8];
+  for (; r + 3 * rl < r1; r += 4 * rl) {             // four rows (with a residual: eight loads) in flight
+    typename IO<T>::Raw yr[4], sr[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+    for (int u = 0; u < 4; ++u) yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+    if (res) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) sr[u] = IO<T>::ld_raw(res + ((r + u * rl) * ncv + cv) * 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
+      float v[8];
+      IO<T>::unpack(yr[u], v);
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v[u][k] = apply_act(fmaf(v[u][k] - mu[k], a[k], b[k]), act);
+      for (int k = 0; k < 8; ++k) v[k] = apply_act(fmaf(v[k] - mu[k], a[k], b[k]), act);
       if (res) {
         float s[8];
-        IO<T>::ld(res + ((r + u * rl) * ncv + cv) * 8, s);
+        IO<T>::unpack(sr[u], s);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[u][k] = apply_act(as_stored<T>(v[u][k]) + s[k], res_act);
+        for (int k = 0; k < 8; ++k) v[k] = apply_act(as_stored<T>(v[k]) + s[k], res_act);
       }
-      IO<T>::st(z + ((r + u * rl) * ncv + cv) * 8, v[u]);
+      IO<T>::st(z + ((r + u * rl) * ncv + cv) * 8, v);
     }
   }
   for (; r < r1; r += rl) {
@@ -288,9 +317,13 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, 
     IO<T>::ld(y + (long)cv * 8, piv);
     long r = r0 + row_lane;
     for (; r + 3 * rl < r1; r += 4 * rl) {           // four rows in flight
+      typename IO<T>::Raw yr[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+      __builtin_amdgcn_sched_barrier(0);
       float v[4][8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+      for (int u = 0; u < 4; ++u) IO<T>::unpack(yr[u], v[u]);
 #pragma unroll
       for (int u = 0; u < 4; ++u)
 #pragma unroll
@@ -410,22 +443,27 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 #pragma unroll
     for (int k = 0; k < 8; ++k) sc[k] = av[k] * iv[k];
     long r = r0 + row_lane;
-    for (; r + rl < r1; r += 2 * rl) {               // two rows (four loads) in flight
-      float d[2][8], v[2][8];
+    for (; r + 3 * rl < r1; r += 4 * rl) {           // four rows (eight loads) in flight
+      typename IO<T>::Raw dr[4], yr[4];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        IO<T>::ld(dz + ((r + u * rl) * ncv + cv) * 8, d[u]);
-        IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+      for (int u = 0; u < 4; ++u) {
+        dr[u] = IO<T>::ld_raw(dz + ((r + u * rl) * ncv + cv) * 8);
+        yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+      for (int u = 0; u < 4; ++u) {
+        float d[8], v[8];
+        IO<T>::unpack(dr[u], d);
+        IO<T>::unpack(yr[u], v);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          const float yc = v[u][k] - mv[k];
-          const float dp = act_pass(fmaf(yc, sc[k], bv[k]), act) ? d[u][k] : 0.f;
+          const float yc = v[k] - mv[k];
+          const float dp = act_pass(fmaf(yc, sc[k], bv[k]), act) ? d[k] : 0.f;
           acc[k] += dp;
           acc[8 + k] = fmaf(dp, yc * iv[k], acc[8 + k]);
         }
+      }
     }
     for (; r < r1; r += rl) {
       float d[8], v[8];
@@ -484,22 +522,26 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     c2[k] = k2[c]; c3[k] = k3[c];
   }
   long r = r0 + row_lane;
-  for (; r + rl < r1; r += 2 * rl) {
-    float d[2][8], v[2][8];
+  for (; r + 3 * rl < r1; r += 4 * rl) {             // four rows (eight loads) in flight
+    typename IO<T>::Raw dr[4], yr[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      IO<T>::ld(dz + ((r + u * rl) * ncv + cv) * 8, d[u]);
-      IO<T>::ld(y + ((r + u * rl) * ncv + cv) * 8, v[u]);
+    for (int u = 0; u < 4; ++u) {
+      dr[u] = IO<T>::ld_raw(dz + ((r + u * rl) * ncv + cv) * 8);
+      yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 4; ++u) {
+      float d[8], v[8];
+      IO<T>::unpack(dr[u], d);
+      IO<T>::unpack(yr[u], v);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const float yc = v[u][k] - mu[k];
-        const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[u][k] : 0.f;
-        d[u][k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
+        const float yc = v[k] - mu[k];
+        const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
+        d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
       }
-      IO<T>::st(dz + ((r + u * rl) * ncv + cv) * 8, d[u]);
+      IO<T>::st(dz + ((r + u * rl) * ncv + cv) * 8, d);
     }
   }
   for (; r < r1; r += rl) {
