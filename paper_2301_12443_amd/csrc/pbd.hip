@@ -363,11 +363,11 @@ DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu, int epi) {
   DmaCfg d{};
   const bool affine = epi == EPI_AFFINE_ACT;
   if (CA % 32 != 0 || NC % 8 != 0 || NC < 64 || M < 4096) return d;
-  // Short reductions are bound by the store, not by the loop.  Measured per layer inside the ResNet-50 x1.5 step:
-  // the student's 1 x 1 layers from 64 channels on gain (96 -> 256 at 56 x 56: 178 -> 162 us, 192 -> 512 at
-  // 28 x 28: 126 -> 96 us), the teacher's affine stores below 256 channels lose to the 128-row kernel, of which
-  // four workgroups share a compute unit (64 -> 256 with the residual: 244 -> 292 us).
-  if (Kred < (Kred == CA && !affine ? 64 : 256)) return d;
+  // 1 x 1 layers from 64 channels on (measured per layer inside the ResNet-50 x1.5 step against the 128-row kernel:
+  // student 96 -> 256 at 56 x 56 178 -> 162 us, 192 -> 512 at 28 x 28 126 -> 96 us; teacher 64 -> 256 with the fused
+  // residual 233 -> 183 us, 128 -> 512 140 -> 105 us on the narrow tiles chosen below); filters from 256 reduction
+  // elements on.
+  if (Kred < (Kred == CA ? 64 : 256)) return d;
   const long tm = (M + kDmaBM - 1) / kDmaBM;
   // One workgroup per compute unit is resident: time ~ rounds x columns of the tile (a little more per column for
   // narrow tiles, whose fragments feed fewer MFMAs).  A last round that fills at most a quarter of the units is
