@@ -152,6 +152,61 @@ __global__ void cast_input_kernel(const float* __restrict__ x, T* __restrict__ o
 }
 
 // ---------------------------------------------------------------------------
+// Space-to-depth form of a 3-channel input for a 7 x 7 stride-2 stem (pad 3):
+//   x float32 NCHW  ->  x2 T [N][H/2][W/2][16],  x2[n][i][j][(dy*2 + dx)*3 + c] = x[n][c][2i + dy][2j + dx], lanes 12..15 = 0.
+// With the filter repacked the same way (pack_stem_weights_kernel) the stem is a 4 x 4 stride-1 convolution
+// over 16 channels with two rows / columns of padding in front:
+//   out[a][b] = sum_{r,s,c} W[r][s][c] x[2a-3+r][2b-3+s][c],  row 2a-3+r = 2 (a-2+br) + dy  <=>  r = 2 br + dy - 1,
+// a reduction of 4*4*16 = 256 elements (147 of them real) instead of 7*7*8 = 392 with the channels padded to 8.
+// ---------------------------------------------------------------------------
+template <class T>
+__global__ void s2d_input_kernel(const float* __restrict__ x, T* __restrict__ out, int N, int C, int H, int W) {
+  const int H2 = H / 2, W2 = W / 2;
+  const long npix = (long)N * H2 * W2;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < npix; i += (long)gridDim.x * blockDim.x) {
+    const int j = (int)(i % W2);
+    const long t = i / W2;
+    const int ii = (int)(t % H2), n = (int)(t / H2);
+    float v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = 0.f;
+#pragma unroll
+    for (int dy = 0; dy < 2; ++dy)
+      for (int c = 0; c < C; ++c) {                  // (C <= 4)
+        const float2 p = *reinterpret_cast<const float2*>(x + (((long)n * C + c) * H + 2 * ii + dy) * W + 2 * j);
+        v[(dy * 2 + 0) * C + c] = p.x;
+        v[(dy * 2 + 1) * C + c] = p.y;
+      }
+    IO<T>::st(out + i * 16, v);
+    IO<T>::st(out + i * 16 + 8, v + 8);
+  }
+}
+// w [K][7][7][8] (channel lanes >= C are zero) -> w2 [K][4][4][16] as above; one thread per element of w2
+template <class T>
+__global__ void pack_stem_weights_kernel(const T* __restrict__ w, T* __restrict__ w2, int K, int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= K * 256) return;
+  const int lane = i & 15, bs = (i >> 4) & 3, br = (i >> 6) & 3, k = i >> 8;
+  const int q = lane / C, c = lane % C;              // q = dy*2 + dx
+  const int r = 2 * br + (q >> 1) - 1, s_ = 2 * bs + (q & 1) - 1;
+  T v = T(0);
+  if (lane < 4 * C && r >= 0 && s_ >= 0) v = w[((k * 7 + r) * 7 + s_) * 8 + c];
+  w2[i] = v;
+}
+// the inverse on the weight gradient: dw2 float32 [K][4][4][16] -> dw float32 [K][7][7][8] (lanes >= C zero)
+__global__ void unpack_stem_grad_kernel(const float* __restrict__ dw2, float* __restrict__ dw, int K, int C) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= K * 392) return;
+  const int c = i & 7, t = i >> 3, s_ = t % 7, r = (t / 7) % 7, k = t / 49;
+  float v = 0.f;
+  if (c < C) {
+    const int br = (r + 1) >> 1, dy = (r + 1) & 1, bs = (s_ + 1) >> 1, dx = (s_ + 1) & 1;
+    v = dw2[((k * 4 + br) * 4 + bs) * 16 + (dy * 2 + dx) * C + c];
+  }
+  dw[i] = v;
+}
+
+// ---------------------------------------------------------------------------
 // inference-mode BN folded to  y = a*x + b  (teacher; Sec. II-A: the teacher is
 // pretrained and only evaluated)
 // ---------------------------------------------------------------------------

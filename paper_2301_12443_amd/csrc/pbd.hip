@@ -80,6 +80,10 @@ struct OpPlan {
   // scratch byte offsets
   size_t y = 0, idx = 0;
   int mix_slot = -1;        // student mix op: which 32-float state record of the block it owns
+  // 7 x 7 stride-2 stem on the 3-channel input, run as a 4 x 4 stride-1 convolution over the space-to-depth copy
+  // of the input (s2d_input_kernel): byte offset (parameter region) of the repacked filter [K][4][4][16]
+  bool s2d = false;
+  size_t w2 = 0;
 };
 
 struct BlockPlan {
@@ -110,6 +114,7 @@ struct pbd_ctx {
   std::vector<BlockPlan> net[2];
   std::vector<Shape> act;               // A_0..A_B
   std::vector<size_t> act_off;          // byte offsets (relay region)
+  size_t s2d_off = (size_t)-1;          // ... of the space-to-depth copy of A_0 (none: -1)
   size_t esz = 4;                       // bytes per tensor element
   // regions (byte offsets from the workspace base)
   size_t r_param = 0, r_relay = 0, r_relay2 = 0, r_tscr = 0, r_tred = 0, total = 0;
@@ -414,6 +419,15 @@ DmaCfg dma_cfg(long M, int NC, int Kred, int CA, int num_cu, int epi) {
 
 constexpr int kMseBlocks = 1024;
 
+// the stem that is run on the space-to-depth copy of the input: first block, reads A_0, 7 x 7, stride 2, pad 3,
+// at most 4 input channels, even image size, bf16 MFMA path
+bool stem_s2d(const pbd_ctx* c, int block, const OpPlan& op) {
+  return c->o.precision == PBD_BF16 && !c->o.force_direct && block == 0 && op.d.type == OP_CBA && !op.dw &&
+         op.d.in[0] == 0 && op.d.k == 7 && op.d.stride == 2 && op.d.pad == 3 && op.in.c <= 4 && op.cin_p == 8 &&
+         op.in.h % 2 == 0 && op.in.w % 2 == 0 && op.out.h == op.in.h / 2 && op.out.w == op.in.w / 2;
+}
+constexpr int kS2dK = 256;     // reduction length of such a stem: 4 x 4 taps x 16 lanes
+
 int plan(pbd_ctx* c) {
   const size_t es = c->esz;
   const bool bf = c->o.precision == PBD_BF16;
@@ -431,6 +445,12 @@ int plan(pbd_ctx* c) {
         need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p) * M * op.d.c_out * 4);
       }
       op.t_w = take(op.wn * es);
+      op.s2d = stem_s2d(c, (int)(&bp - &c->net[0][0]), op);
+      if (op.s2d) {
+        op.w2 = take((size_t)op.d.c_out * kS2dK * es);
+        const long M = (long)c->o.batch * op.out.h * op.out.w;
+        need_red((size_t)igemm_splits(M, op.d.c_out, kS2dK, 16) * M * op.d.c_out * 4);
+      }
       op.t_gamma = take(op.cout_p * 4); op.t_beta = take(op.cout_p * 4);
       op.t_rmean = take(op.cout_p * 4); op.t_rvar = take(op.cout_p * 4);
       op.t_a = take(op.cout_p * 4); op.t_b = take(op.cout_p * 4);
@@ -447,6 +467,8 @@ int plan(pbd_ctx* c) {
       op.e_beta = e; e += op.cout_p;
       for (size_t* s : {&op.s_rmean, &op.s_rvar, &op.s_mean, &op.s_invstd, &op.s_k2, &op.s_k3})
         *s = take(op.cout_p * 4);
+      op.s2d = stem_s2d(c, (int)(&bp - &c->net[1][0]), op);
+      if (op.s2d) op.w2 = take((size_t)op.d.c_out * kS2dK * es);
       // transposed copy for backward-data of dense convolutions that need it
       if (!op.dw && op.d.in[0] != 0 && bf) {
         op.e_wt = (long)et;
@@ -473,6 +495,13 @@ int plan(pbd_ctx* c) {
   c->act_off.clear();
   size_t r = 0;
   for (Shape s : c->act) { c->act_off.push_back(r); r += tensor_bytes(c, s); }
+  c->s2d_off = (size_t)-1;
+  for (int t = 0; t < 2; ++t)
+    for (const OpPlan& op : c->net[t][0].ops)
+      if (op.s2d && c->s2d_off == (size_t)-1) {
+        c->s2d_off = r;
+        r += align_up((size_t)c->o.batch * (op.in.h / 2) * (op.in.w / 2) * 16 * es);
+      }
   cur += r;
   c->r_relay2 = cur;      // second copy: the teacher fills one while the students still read the other
   cur += r;
@@ -508,12 +537,14 @@ int plan(pbd_ctx* c) {
                                              op.d.stride, op.d.pad);
           need_red((size_t)gw.chunks * op.d.k * op.d.k * op.cout_p * 4);
         } else if (bf && !c->o.force_direct) {
-          const WgradCfg w = wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.d.k * op.d.k);
-          need_red((size_t)w.splits * op.wn * 4);
+          const WgradCfg w = op.s2d ? wgrad_cfg(M, op.d.c_out, kS2dK, 16) : wgrad_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.d.k * op.d.k);
+          // (the stem on the space-to-depth input: partial sums and their sum in the repacked layout, then unpacked)
+          need_red(op.s2d ? ((size_t)w.splits + 1) * op.d.c_out * kS2dK * 4 : (size_t)w.splits * op.wn * 4);
           // per-row-tile batch-norm sums from the convolution's store (64-row tiles at most), and their regrouping
           need_red(((size_t)(M + 63) / 64 + kStatGroupsMax + 1) * 2 * op.cout_p * 4);
           const long Min = (long)c->o.batch * op.in.h * op.in.w;
           need_red((size_t)igemm_splits(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p) * M * op.d.c_out * 4);
+          if (op.s2d) need_red((size_t)igemm_splits(M, op.d.c_out, kS2dK, 16) * M * op.d.c_out * 4);
           need_red((size_t)igemm_splits(Min, op.cin_p, op.d.k * op.d.k * op.d.c_out, op.d.c_out) * Min * op.cin_p * 4);
         }
       } else if (op.d.type == OP_POOL) {
@@ -617,6 +648,11 @@ template <class T> struct Exec {
   T* relay_in(int i, int set) const { return ws((set ? c->r_relay2 : c->r_relay) + c->act_off[i]); }
   T* trelay(int i) const { return relay_in(i, tset); }
   T* srelay(int i) const { return relay_in(i, sset); }
+  // the space-to-depth copy of A_0 that the net at hand reads
+  T* s2d_input() const { return ws(((net == PBD_TEACHER ? tset : sset) ? c->r_relay2 : c->r_relay) + c->s2d_off); }
+  // reduction length and gathered channels of a dense convolution as it is run
+  static int kred_of(const OpPlan& op) { return op.s2d ? kS2dK : op.d.k * op.d.k * op.cin_p; }
+  static int ca_of(const OpPlan& op) { return op.s2d ? 16 : op.cin_p; }
   float* red() const { return red_static ? red_static : wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
@@ -626,7 +662,7 @@ template <class T> struct Exec {
   // MFMA kernel's LDS-staged store does it: no split-K, and not the 64 x 32 tile (whose idle waves skip it).
   bool fuses_residual(const OpPlan& op) const {
     if (!mfma() || op.dw) return false;
-    const IgemmCfg cfg = igemm_cfg((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
+    const IgemmCfg cfg = igemm_cfg((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, kred_of(op), ca_of(op));
     return cfg.splits == 1 && !(cfg.BM == 64 && cfg.BN == 32);      // (the 256-row kernel, where it is used, fuses it too)
   }
   // the 256-row, direct-to-LDS kernel takes a launch when its tile count fills the chip and no split-K is wanted
@@ -641,9 +677,9 @@ template <class T> struct Exec {
   int fused_stats_tiles(const OpPlan& op) const {
     const long M = (long)c->o.batch * op.out.h * op.out.w;
     if (!fuses_residual(op) || op.d.c_out % 8 != 0 || short_column(M)) return 0;
-    const DmaCfg d = dma_for(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
+    const DmaCfg d = dma_for(M, op.d.c_out, kred_of(op), ca_of(op));
     if (d.use) return d.big_m + d.tail_m;
-    const IgemmCfg cfg = igemm_cfg(M, op.d.c_out, op.d.k * op.d.k * op.cin_p, op.cin_p);
+    const IgemmCfg cfg = igemm_cfg(M, op.d.c_out, kred_of(op), ca_of(op));
     return (int)((M + cfg.BM - 1) / cfg.BM);
   }
   // res (optional): a residual join fused into the store, y = res_act(conv result + res); only where
@@ -658,9 +694,18 @@ template <class T> struct Exec {
         IgemmArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                     op.d.stride, op.d.pad, N * op.out.h * op.out.w, op.d.k * op.d.k * op.cin_p, 0,
                     (unsigned)((size_t)N * op.in.h * op.in.w * op.cin_p * 2), (unsigned)(op.wn * 2)};
+        double bytes_run = bytes;
+        if (op.s2d) {
+          // 4 x 4, stride 1, two rows / columns of padding in front, over the space-to-depth copy of the input
+          g.HA = op.in.h / 2; g.WA = op.in.w / 2; g.CA = 16; g.R = g.S = 4; g.stride = 1; g.pad = 2; g.Kred = kS2dK;
+          g.a_bytes = (unsigned)((size_t)N * g.HA * g.WA * 16 * 2); g.b_bytes = (unsigned)(op.d.c_out * kS2dK * 2);
+          x = s2d_input();
+          w = reinterpret_cast<const T*>(c->ws + op.w2);
+          bytes_run = (double)g.a_bytes + bytes_of(op.out) * (res ? 2 : 1) + (double)g.b_bytes;
+        }
         g.res = res; g.res_act = res_act; g.stats = stats;
         launch_igemm<0>(g, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, a ? EPI_AFFINE_ACT : EPI_STORE,
-                        bytes, flops);
+                        bytes_run, flops);
       }
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
@@ -797,7 +842,7 @@ template <class T> struct Exec {
     const double bytes = bytes_of(op.in) + bytes_of(op.out) + (double)op.wn * 4;
     if (mfma()) {
       if constexpr (sizeof(T) == 2) {
-        const WgradCfg w = wgrad_cfg(M, op.d.c_out, J, op.d.k * op.d.k);
+        const WgradCfg w = op.s2d ? wgrad_cfg(M, op.d.c_out, kS2dK, 16) : wgrad_cfg(M, op.d.c_out, J, op.d.k * op.d.k);
         const int pq = op.out.h * op.out.w;
         WgradTrArgs g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k,
                       op.d.stride, op.d.pad, (int)M, J, w.pix_per_split,
@@ -806,10 +851,24 @@ template <class T> struct Exec {
                       w.tiles_k, w.tiles_j, w.splits};
         const dim3 grid(w.tiles_k * w.tiles_j * w.splits);
         float* part = w.splits == 1 ? dw : red();
+        long wn_run = (long)op.wn;
+        float* dw_run = dw;                        // where the summed gradient goes
+        double bytes_run = bytes;
+        if (op.s2d) {
+          // the stem on the space-to-depth copy of the input: gradient of the repacked filter first (partial sums,
+          // then their sum behind them in the scratch), unpacked into the 7 x 7 layout at the end
+          g.H = op.in.h / 2; g.W = op.in.w / 2; g.C = 16; g.R = g.S = 4; g.stride = 1; g.pad = 2; g.J = kS2dK;
+          g.x_bytes = (unsigned)((size_t)N * g.H * g.W * 16 * 2);
+          x = s2d_input();
+          wn_run = (long)op.d.c_out * kS2dK;
+          dw_run = red() + (size_t)w.splits * wn_run;
+          part = w.splits == 1 ? dw_run : red();
+          bytes_run = (double)g.x_bytes + bytes_of(op.out) + (double)wn_run * 4;
+        }
         {
           char name[32];
           snprintf(name, sizeof name, "wgrad_%dx%d", w.TM, w.TN);
-          ProfScope ps(c, name, bytes, flops, net, blk, opi);
+          ProfScope ps(c, name, bytes_run, flops, net, blk, opi);
           if (w.dma) {
 #define PBD_WGD(TM_) launch(c, wgrad_dma_kernel<TM_>, grid, kDmaThreads, 0, st, (const bf16_t*)dy, (const bf16_t*)x, part, g)
             if (w.TM == 256) PBD_WGD(256); else PBD_WGD(192);
@@ -822,9 +881,11 @@ template <class T> struct Exec {
           }
         }
         if (w.splits > 1) {
-          ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * op.wn * 4, 0, net, blk, opi);
-          sum_partials(part, dw, (long)op.wn, w.splits);
+          ProfScope ps(c, "sum_partials", (double)(w.splits + 1) * wn_run * 4, 0, net, blk, opi);
+          sum_partials(part, dw_run, wn_run, w.splits);
         }
+        if (op.s2d)
+          launch(c, unpack_stem_grad_kernel, (op.d.c_out * 392 + 255) / 256, 256, 0, st, dw_run, dw, op.d.c_out, op.in.c);
       }
     } else {
       ConvGeom g{N, op.in.h, op.in.w, op.cin_p, op.out.h, op.out.w, op.d.c_out, op.d.k, op.d.k, op.d.stride, op.d.pad};
@@ -1019,6 +1080,11 @@ template <class T> struct Exec {
           launch(c, bn_fold_kernel, (op.cout_p + 255) / 256, 256, 0, st, wsf(op.t_gamma), wsf(op.t_beta), wsf(op.t_rmean),
                                                                   wsf(op.t_rvar), wsf(op.t_a), wsf(op.t_b), op.cout_p,
                                                                   c->o.bn_eps);
+    // the stems that run on the space-to-depth input: their filters in that layout
+    for (OpPlan& op : c->net[0][0].ops)
+      if (op.s2d)
+        launch(c, pack_stem_weights_kernel<T>, (op.d.c_out * kS2dK + 255) / 256, 256, 0, st,
+               reinterpret_cast<const T*>(c->ws + op.t_w), reinterpret_cast<T*>(c->ws + op.w2), op.d.c_out, op.in.c);
     c->fold_dirty = false;
   }
 
@@ -1040,6 +1106,13 @@ template <class T> struct Exec {
       net = PBD_TEACHER; blk = -1; opi = -1;
       ProfScope ps(c, "cast_input", (double)c->o.batch * s.c * s.h * s.w * 4 + bytes_of(s), 0, net, blk, opi);
       launch(c, cast_input_kernel<T>, grid_for(nvec), 256, 0, st, x_dev, trelay(0), c->o.batch, s.c, s.h * s.w, round8(s.c));
+    }
+    if (c->s2d_off != (size_t)-1) {
+      const Shape s = c->act[0];
+      const long npix = (long)c->o.batch * (s.h / 2) * (s.w / 2);
+      ProfScope ps(c, "cast_input_s2d", (double)c->o.batch * s.c * s.h * s.w * 4 + (double)npix * 16 * sizeof(T), 0, net, blk, opi);
+      launch(c, s2d_input_kernel<T>, grid_for(npix), 256, 0, st, x_dev, ws((tset ? c->r_relay2 : c->r_relay) + c->s2d_off),
+             c->o.batch, s.c, s.h, s.w);
     }
   }
   void relay_all(const float* x_dev) { relay_prefix(x_dev, c->B); }
@@ -1119,6 +1192,10 @@ template <class T> struct Exec {
     bp.dirty = false;
   }
   void transpose_weights(BlockPlan& bp) {
+    for (OpPlan& op : bp.ops)
+      if (op.s2d)
+        launch(c, pack_stem_weights_kernel<T>, (op.d.c_out * kS2dK + 255) / 256, 256, 0, st, ws(bp.wc) + op.e_w,
+               reinterpret_cast<T*>(c->ws + op.w2), op.d.c_out, op.in.c);
     if (bp.ttable.empty()) return;
     ProfScope ps(c, "transpose_weights", 2.0 * bp.wt_elems * sizeof(T), 0, net, blk, -1);
     dim3 grid(64, (unsigned)bp.ttable.size());

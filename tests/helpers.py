@@ -85,11 +85,17 @@ def layer_workloads():
     v = s.cba(0, 64, 3, groups=64); v = s.cba(v, 128, 1)
     v = s.cba(v, 128, 3, groups=128); v = s.cba(v, 128, 1); s.pool(v, 2, 2)
     wl("l_dsconv", (64, 16, 16), t, s, 64)
-    # 3-channel input: 7x7 stride-2 stem, 3x3 s2 p1 pool, 1x1 (ResNet stem)
+    # 3-channel input: 7x7 stride-2 stem, 3x3 s2 p1 pool, 1x1 (ResNet stem; even image size: the library runs it as a
+    # 4 x 4 stride-1 convolution over a space-to-depth copy of the input)
     t, s = W.Block(), W.Block()
     v = t.cba(0, 64, 7, 2); t.pool(v, 3, 2, 1)
     v = s.cba(0, 64, 7, 2); v = s.pool(v, 3, 2, 1); s.cba(v, 64, 1)
     wl("l_stem7x7", (3, 64, 64), t, s, 8)
+    # the same stem on an odd image size: no space-to-depth copy of the input, the 7 x 7 filter is run as it is
+    t, s = W.Block(), W.Block()
+    v = t.cba(0, 64, 7, 2); t.pool(v, 3, 2, 1)
+    v = s.cba(0, 64, 7, 2); v = s.pool(v, 3, 2, 1); s.cba(v, 64, 1)
+    wl("l_stem7x7_odd", (3, 45, 45), t, s, 8)
     # MBConv k5 stride 2 (MobileNet student) and k7 stride 1 with residual (supernet candidate)
     t, s = W.Block(), W.Block()
     W._mbconv(t, 0, 24, 32, 3, 6, 2)

@@ -181,7 +181,7 @@ KNOWN_DRIFT = {
                          "s0.b5.op2.g": 2.66e-2, "s0.b5.op2.w": 3.13e-2, "s0.b5.op3.w": 2.16e-2, "s0.b5.op7.g": 3.63e-2,
                          "s0.b5.op7.w": 2.26e-2, "s0.b5.op8.w": 2.19e-2},
     "resnet50_x1.5": {"s0.b0.op0.w": 8.45e-2, "s0.b3.op9.w": 2.37e-2, "s0.b3.op9.g": 2.21e-2, "s0.b3.op5.g": 2.12e-2,
-                      "s0.b3.op5.w": 2.01e-2},
+                      "s0.b3.op5.w": 2.01e-2, "s0.b2.op9.g": 2.09e-2},
 }
 
 
