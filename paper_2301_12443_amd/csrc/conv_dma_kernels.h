@@ -146,7 +146,11 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
   const int lrow = lane / CPR, slot = lane % CPR;
   auto swz = [](int row) { return BK == 64 ? (row >> 1) & 7 : (row >> 2) & 3; };
   unsigned abase[A_INSTR];
-  int rh[A_INSTR], rw[A_INSTR];
+  int rh[A_INSTR], rw[A_INSTR], kc8[A_INSTR];
+  // elements between neighbouring pixels of A: the channel count, except for a tap that spans several pixels
+  // (g.pix_shift > 0: CA = a run of CA >> pix_shift-wide pixels, each range-tested on its own)
+  const int pitch = MODE == 0 && g.pix_shift ? g.CA >> g.pix_shift : g.CA;
+  const int pshift = MODE == 0 && g.pix_shift ? 31 - __builtin_clz(pitch) : 31;     // (x >> 31 = 0: one pixel per tap)
   int a_cnt = 0, b_cnt = 0;                      // loads this WAVE issues per stage (uniform)
 #pragma unroll
   for (int i = 0; i < A_INSTR; ++i) {
@@ -162,7 +166,8 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
     const int h0 = MODE == 0 ? a_ * g.stride - g.pad : (par ? 2 * a_ + ph : a_) + g.pad;
     const int w0 = MODE == 0 ? b_ * g.stride - g.pad : (par ? 2 * b_ + pw : b_) + g.pad;
     const int kc = slot ^ swz(row);
-    if (MODE == 0) abase[i] = (unsigned)(((nbase + h0 * g.WA + w0) * g.CA + kc * 8) * 2);
+    kc8[i] = kc * 8;
+    if (MODE == 0) abase[i] = (unsigned)(((nbase + h0 * g.WA + w0) * pitch + kc * 8) * 2);
     else abase[i] = (unsigned)((nbase * g.CA + ((h0 * g.WA + w0) * g.CA >> sh) + kc * 8) * 2);
     rh[i] = valid ? h0 : -(1 << 24);             // rows past the end fail every range test
     rw[i] = w0;
@@ -184,7 +189,7 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
   auto issue_stage = [&](int stage) {
     unsigned char* sa = smem + stage * STAGE + wave * 1024;
     const int tap = MODE == 0 ? r * g.WA + s : -(r * g.WA + s);
-    const unsigned delta = (unsigned)(((tap * g.CA) >> (MODE == 1 ? sh : 0)) + c) * 2u;
+    const unsigned delta = (unsigned)(((tap * (MODE == 0 ? pitch : g.CA)) >> (MODE == 1 ? sh : 0)) + c) * 2u;
     const unsigned hlim = MODE == 0 ? (unsigned)g.HA : (unsigned)g.HA << sh;
     const unsigned wlim = MODE == 0 ? (unsigned)g.WA : (unsigned)g.WA << sh;
     const unsigned kk = (unsigned)((r * g.S + s) * g.CA + c);
@@ -192,7 +197,7 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
     for (int i = 0; i < A_INSTR; ++i) {
       if ((i * 8 + wave) * 64 >= A_CHUNKS) continue;        // (uniform over the wave)
       const int h = MODE == 0 ? rh[i] + r : rh[i] - r, w = MODE == 0 ? rw[i] + s : rw[i] - s;
-      bool ok = (unsigned)h < hlim && (unsigned)w < wlim;
+      bool ok = (unsigned)h < hlim && (unsigned)(w + ((c + kc8[i]) >> pshift)) < wlim;
       if (MODE == 1) ok = ok && ((h | w) & smask) == 0;
       dma_load16(a_rsrc, sa + i * 8 * 1024, ok ? abase[i] + delta : kOutOfRange);
     }

@@ -152,6 +152,9 @@ struct IgemmArgs {
   // input pixel (class id = 2 (h % 2) + w % 2; only the taps of matching parity reach such a pixel), par_classes
   // of them in the order par_order lists (2 bits per class id); 0: rows in pixel order, every tap tested
   int par_classes, par_order;
+  // igemm_dma_kernel, forward only: a tap gathers a run of 1 << pix_shift neighbouring pixels of CA >> pix_shift
+  // channels each (CA contiguous elements; S counts such runs).  0: a tap is one pixel of CA channels
+  int pix_shift;
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel

@@ -652,7 +652,11 @@ template <class T> struct Exec {
   T* s2d_input() const { return ws(((net == PBD_TEACHER ? tset : sset) ? c->r_relay2 : c->r_relay) + c->s2d_off); }
   // reduction length and gathered channels of a dense convolution as it is run
   static int kred_of(const OpPlan& op) { return op.s2d ? kS2dK : op.d.k * op.d.k * op.cin_p; }
-  static int ca_of(const OpPlan& op) { return op.s2d ? 16 : op.cin_p; }
+  // (a space-to-depth stem: 64 where the direct-to-LDS kernel takes it, which gathers a filter row at a time)
+  int ca_of(const OpPlan& op) const {
+    if (!op.s2d) return op.cin_p;
+    return dma_for((long)c->o.batch * op.out.h * op.out.w, op.d.c_out, kS2dK, 64).use ? 64 : 16;
+  }
   float* red() const { return red_static ? red_static : wsf(red_off); }
   double bytes_of(Shape s) const { return (double)c->o.batch * s.h * s.w * round8(s.c) * sizeof(T); }
   bool mfma() const { return sizeof(T) == 2 && !c->o.force_direct; }
@@ -698,6 +702,8 @@ template <class T> struct Exec {
         if (op.s2d) {
           // 4 x 4, stride 1, two rows / columns of padding in front, over the space-to-depth copy of the input
           g.HA = op.in.h / 2; g.WA = op.in.w / 2; g.CA = 16; g.R = g.S = 4; g.stride = 1; g.pad = 2; g.Kred = kS2dK;
+          // the four taps of a filter row are 64 contiguous elements: one tap of four pixels to the direct-to-LDS kernel
+          if (dma_for(g.M, g.NC, kS2dK, 64, a ? EPI_AFFINE_ACT : EPI_STORE).use) { g.CA = 64; g.S = 1; g.pix_shift = 2; }
           g.a_bytes = (unsigned)((size_t)N * g.HA * g.WA * 16 * 2); g.b_bytes = (unsigned)(op.d.c_out * kS2dK * 2);
           x = s2d_input();
           w = reinterpret_cast<const T*>(c->ws + op.w2);
