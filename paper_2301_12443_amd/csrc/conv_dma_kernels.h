@@ -28,6 +28,11 @@
 //    tile count is a little over a multiple of the number of compute units would end with a nearly empty round as
 //    long as a full one.  The host may therefore cut the last row tiles into 64-row tiles (blockIdx >= the number
 //    of big tiles): same code with BM = 64, a quarter of the time each, spread over four times as many units.
+//  * Backward-data of a stride-2 layer takes the input pixels parity class by parity class (see dma_tile): only the
+//    taps that reach a class are reduced over.
+//  * Forward only: a tap may span a run of neighbouring pixels (IgemmArgs::pix_shift), which is how the 7 x 7 stem is
+//    run on the space-to-depth copy of its 3-channel input: a filter row of four 16-channel pixels is one
+//    64-element tap, and each 16-byte chunk is range-tested against the pixel it belongs to.
 // Needs CA % BK == 0 (a reduction step lies inside one filter tap: taps are uniform over the block).
 #pragma once
 #include "conv_kernels.h"
