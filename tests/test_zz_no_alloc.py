@@ -25,6 +25,16 @@ def _state(d, wl, b):
     return out
 
 
+def _value(d, b, v):
+    """Saved value v of block b, or None where the library does not keep it (its reader applies the normalisation)."""
+    try:
+        return d.read_value(b, v)
+    except pbd.PbdError as e:
+        if e.code != -4:
+            raise
+        return None
+
+
 @pytest.mark.parametrize("precision,batch", [("f32", 8), ("bf16", 8), ("bf16", 96)])
 def test_static_scratch_step_equals_the_workspace_step(precision, batch):
     import torch
@@ -52,7 +62,10 @@ def test_static_scratch_step_equals_the_workspace_step(precision, batch):
         for k in a:
             np.testing.assert_array_equal(a[k], b[k], err_msg=f"call {step}, block {i}, tensor {k}")
         for v in range(1, len(wl.student[i - 1].ops) + 1):
-            np.testing.assert_array_equal(ref.read_value(i - 1, v), dut.read_value(i - 1, v))
+            want, got = _value(ref, i - 1, v), _value(dut, i - 1, v)
+            assert (want is None) == (got is None)
+            if want is not None:
+                np.testing.assert_array_equal(want, got)
     # a second step of block 1 on both sides: momentum in play, the array now holds block 2's leftovers
     ref.student_step(1, wl.lr); ref.sync()
     dut.student_step_static(1, wl.lr); dut.sync()
