@@ -474,11 +474,16 @@ __global__ void regroup_partials_kernel(const float* __restrict__ part, float* _
 
 // BN backward, stage 1: with xhat = (y - mean)*invstd, pre = gamma*xhat + beta and
 // dpre = [act passes at pre] * dz:  part[chunk][0][c] = sum dpre, part[chunk][1][c] = sum dpre*xhat
-template <class T>
+// RES: the layer's output went straight into a two-input add (fused into its normalisation pass on the way
+// forward).  dz is then the gradient of the add's output and zres that output: the gradient passes where the
+// add's activation res_act does (zres == nullptr: no activation), is stored to dstore (the gradient of both
+// inputs of the add: the backward pass of the add itself, done here) and enters the sums.
+template <class T, bool RES = false>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const T* __restrict__ dz, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
-    float* __restrict__ part, long M, int Cp, int act, ColGrid g) {
+    float* __restrict__ part, long M, int Cp, int act, ColGrid g, const T* __restrict__ zres = nullptr,
+    int res_act = 0, T* __restrict__ dstore = nullptr) {
   extern __shared__ float smem[];
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
@@ -498,12 +503,16 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 #pragma unroll
     for (int k = 0; k < 8; ++k) sc[k] = av[k] * iv[k];
     long r = r0 + row_lane;
-    for (; r + 3 * rl < r1; r += 4 * rl) {           // four rows (eight loads) in flight
-      typename IO<T>::Raw dr[4], yr[4];
+    for (; r + 3 * rl < r1; r += 4 * rl) {           // four rows (eight loads, twelve with an add's output) in flight
+      typename IO<T>::Raw dr[4], yr[4], zr[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         dr[u] = IO<T>::ld_raw(dz + ((r + u * rl) * ncv + cv) * 8);
         yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+      }
+      if (RES && zres) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) zr[u] = IO<T>::ld_raw(zres + ((r + u * rl) * ncv + cv) * 8);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -511,6 +520,15 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
         float d[8], v[8];
         IO<T>::unpack(dr[u], d);
         IO<T>::unpack(yr[u], v);
+        if (RES) {
+          if (zres) {
+            float z[8];
+            IO<T>::unpack(zr[u], z);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) d[k] = act_pass(z[k], res_act) ? d[k] : 0.f;
+          }
+          IO<T>::st(dstore + ((r + u * rl) * ncv + cv) * 8, d);
+        }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const float yc = v[k] - mv[k];
@@ -524,6 +542,15 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
       float d[8], v[8];
       IO<T>::ld(dz + (r * ncv + cv) * 8, d);
       IO<T>::ld(y + (r * ncv + cv) * 8, v);
+      if (RES) {
+        if (zres) {
+          float z[8];
+          IO<T>::ld(zres + (r * ncv + cv) * 8, z);
+#pragma unroll
+          for (int k = 0; k < 8; ++k) d[k] = act_pass(z[k], res_act) ? d[k] : 0.f;
+        }
+        IO<T>::st(dstore + (r * ncv + cv) * 8, d);
+      }
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
         const float yc = v[k] - mv[k];
@@ -557,10 +584,11 @@ __global__ void bn_bwd_finalize_kernel(const float* __restrict__ part, int chunk
   k3[c] = (float)(sg / m);
 }
 
-// stage 3: gradient w.r.t. the convolution output, written over dz in place (column-grid launch)
+// stage 3: gradient w.r.t. the convolution output, written to dy (dy == dz: in place; column-grid launch, each
+// thread reads its elements before it writes them)
 template <class T>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
-    T* __restrict__ dz, const T* __restrict__ y, const float* __restrict__ gamma,
+    const T* dz, T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
     const float* __restrict__ k2, const float* __restrict__ k3, long M, int Cp, int act, ColGrid g) {
   const int ncv = Cp / 8;
@@ -596,7 +624,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
         const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
         d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
       }
-      IO<T>::st(dz + ((r + u * rl) * ncv + cv) * 8, d);
+      IO<T>::st(dy + ((r + u * rl) * ncv + cv) * 8, d);
     }
   }
   for (; r < r1; r += rl) {
@@ -609,7 +637,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
       const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
       d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
     }
-    IO<T>::st(dz + (r * ncv + cv) * 8, d);
+    IO<T>::st(dy + (r * ncv + cv) * 8, d);
   }
 }
 

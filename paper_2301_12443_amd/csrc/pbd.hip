@@ -1329,16 +1329,34 @@ template <class T> struct Exec {
         for (int k = 0; k < (o.type == OP_ADD || o.type == OP_MIX ? o.nin : 1); ++k) w |= wanted[o.in[k]];
         wanted[j + 1] = w;
       }
+    // An add whose backward pass rides in the batch-norm backward of the layer right before it (the one whose
+    // normalisation pass carried the add on the way forward): that layer's reduction reads the add's output
+    // gradient, masks it and stores the result once, where the add's other input collects its gradient.
+    struct AddBwd { const T* dz; const T* z; int act; T* dstore; };
+    std::vector<AddBwd> add_bwd(bp.ops.size(), AddBwd{nullptr, nullptr, 0, nullptr});
     for (int j = (int)bp.ops.size() - 1; j >= 0; --j) {
       const OpPlan& op = bp.ops[j];
       opi = j;
       if (!have[j + 1]) continue;
       T* dz = dvalue(j + 1);
       const int iv = op.d.in[0];
+      if (op.d.type == OP_ADD && !arch && j >= 1 && residual_reader(bp, j - 1) == j &&
+          !short_column((long)N * op.out.h * op.out.w)) {
+        const int other = op.d.in[0] == j ? op.d.in[1] : op.d.in[0];
+        if (!wanted[other] || !have[other]) {      // (a gradient already there would have to be added to, not replaced)
+          add_bwd[j - 1] = AddBwd{dz, op.d.act != ACT_NONE ? value(j + 1) : nullptr, op.d.act,
+                                  wanted[other] ? dvalue(other) : dvalue(j)};
+          if (wanted[other]) have[other] = 1;
+          have[j] = 1;
+          continue;
+        }
+      }
       if (op.d.type == OP_CBA) {
         if (arch && !wanted[iv]) continue;   // frozen weights and nothing trainable above: nothing to do
         const T* y = ws(scr + op.y);
         const long M = (long)N * op.out.h * op.out.w;
+        const AddBwd ab = add_bwd[j];
+        const T* dz_in = ab.dz ? ab.dstore : dz;     // what the last stage reads (dz: in place)
         if (short_column(M)) {
           ProfScope ps(c, "bn_small_bwd", 5 * bytes_of(op.out), 0, net, blk, opi);
           launch(c, bn_small_bwd_kernel<T>, op.cout_p / 8, kSmallThreads, 0, st, dz, y, master + op.e_gamma,
@@ -1346,11 +1364,16 @@ template <class T> struct Exec {
                  op.cout_p, op.d.act, (unsigned)(M * op.cout_p * sizeof(T)));
         } else {
           const ColGrid g = bn_bwd_grid(M, op.cout_p);
-          {
+          if (ab.dz) {
+            ProfScope ps(c, "bn_bwd_reduce_add", (ab.z ? 4 : 3) * bytes_of(op.out), 0, net, blk, opi);
+            launch(c, bn_bwd_reduce_kernel<T, true>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
+                ab.dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
+                op.d.act, g, ab.z, ab.act, ab.dstore);
+          } else {
             ProfScope ps(c, "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
-            launch(c, bn_bwd_reduce_kernel<T>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st, 
-                dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
-                op.d.act, g);
+            launch(c, bn_bwd_reduce_kernel<T, false>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
+                (const T*)dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
+                op.d.act, g, (const T*)nullptr, 0, (T*)nullptr);
           }
           launch(c, bn_bwd_finalize_kernel, op.cout_p / kFinalizeChannels, 256, 0, st, red(), g.chunks, op.cout_p, (double)M,
                                                                            grad + op.e_gamma, grad + op.e_beta,
@@ -1358,8 +1381,8 @@ template <class T> struct Exec {
           {
             const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);
             ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
-            launch(c, bn_bwd_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st, 
-                dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
+            launch(c, bn_bwd_apply_kernel<T>, dim3(ga.slabs, ga.chunks), 256, 0, st,
+                dz_in, dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
                 wsf(op.s_k3), M, op.cout_p, op.d.act, ga);
           }
         }
