@@ -135,7 +135,9 @@ int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
  *    this is the gradient of loss_i (Sec. II-A) with respect to the CONVOLUTION output, i.e. already taken back
  *    through the activation and the normalisation (the tensor the op's weight gradient and backward-data are
  *    formed from); for the output of a pool, add or weighted-sum op it is the gradient with respect to the value
- *    itself.  Unspecified for values no gradient reached (e.g. after pbd_arch_step). */
+ *    itself.  Unspecified for values no gradient reached (e.g. after pbd_arch_step).  Not stored (PBD_ESTATE) for
+ *    the block's output when the block ends in a two-input add that is fused into the normalisation pass of the
+ *    layer before it: that layer's backward reduction forms 2 (S_i - A_i) / M_i itself. */
 int pbd_read_conv_out(pbd_ctx* ctx, int32_t b, int32_t op, float* host, size_t n);
 int pbd_read_batch_stats(pbd_ctx* ctx, int32_t b, int32_t op, float* mean_host, float* invstd_host, size_t n);
 int pbd_read_grad_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);

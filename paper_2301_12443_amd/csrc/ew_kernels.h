@@ -478,12 +478,18 @@ __global__ void regroup_partials_kernel(const float* __restrict__ part, float* _
 // forward).  dz is then the gradient of the add's output and zres that output: the gradient passes where the
 // add's activation res_act does (zres == nullptr: no activation), is stored to dstore (the gradient of both
 // inputs of the add: the backward pass of the add itself, done here) and enters the sums.
-template <class T, bool RES = false>
+// LOSS (with RES and zres): the add's output is the block's output S.  dz is then the teacher's activation A,
+// the gradient of the add's output is 2 (S - A) / M rounded as it would be stored (Sec. II-A, the loss of the
+// block's output), and loss_part[workgroup] = sum (S - A)^2 over the workgroup's elements.
+template <class T, bool RES = false, bool LOSS = false>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const T* __restrict__ dz, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
     float* __restrict__ part, long M, int Cp, int act, ColGrid g, const T* __restrict__ zres = nullptr,
-    int res_act = 0, T* __restrict__ dstore = nullptr) {
+    int res_act = 0, T* __restrict__ dstore = nullptr, float* __restrict__ loss_part = nullptr,
+    float two_over_m = 0.f) {
+  static_assert(RES || !LOSS, "the loss rides only where the add does");
+  float lacc = 0.f;
   extern __shared__ float smem[];
   const int ncv = Cp / 8;
   const int cv_lane = threadIdx.x % g.cvl, row_lane = threadIdx.x / g.cvl, rl = 256 / g.cvl;
@@ -524,6 +530,14 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
           if (zres) {
             float z[8];
             IO<T>::unpack(zr[u], z);
+            if (LOSS) {
+#pragma unroll
+              for (int k = 0; k < 8; ++k) {
+                const float e = z[k] - d[k];
+                lacc = fmaf(e, e, lacc);
+                d[k] = as_stored<T>(e * two_over_m);
+              }
+            }
 #pragma unroll
             for (int k = 0; k < 8; ++k) d[k] = act_pass(z[k], res_act) ? d[k] : 0.f;
           }
@@ -546,6 +560,14 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
         if (zres) {
           float z[8];
           IO<T>::ld(zres + (r * ncv + cv) * 8, z);
+          if (LOSS) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const float e = z[k] - d[k];
+              lacc = fmaf(e, e, lacc);
+              d[k] = as_stored<T>(e * two_over_m);
+            }
+          }
 #pragma unroll
           for (int k = 0; k < 8; ++k) d[k] = act_pass(z[k], res_act) ? d[k] : 0.f;
         }
@@ -567,6 +589,16 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     float* p = part + (long)blockIdx.y * 2 * Cp + cv * 8;
 #pragma unroll
     for (int k = 0; k < 8; ++k) { p[k] = out[k]; p[Cp + k] = out[8 + k]; }
+  }
+  if (LOSS) {                                        // the workgroup's share of sum (S - A)^2, added in a fixed order
+    __syncthreads();
+    smem[threadIdx.x] = lacc;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+      if ((int)threadIdx.x < h) smem[threadIdx.x] += smem[threadIdx.x + h];
+      __syncthreads();
+    }
+    if (threadIdx.x == 0) loss_part[blockIdx.y * gridDim.x + blockIdx.x] = smem[0];
   }
 }
 

@@ -531,7 +531,7 @@ int plan(pbd_ctx* c) {
       if (op.d.type == OP_CBA) {
         op.y = s; s += tensor_bytes(c, op.out);
         const ColGrid g = bn_bwd_grid(M, op.cout_p);   // the larger of the two reductions' grids
-        need_red((size_t)g.chunks * 2 * op.cout_p * 4);
+        need_red(((size_t)g.chunks * 2 * op.cout_p + (size_t)g.slabs * g.chunks) * 4);   // (+ one loss partial a workgroup)
         if (op.dw) {
           const DwWgradCfg gw = dw_wgrad_cfg(bf && !c->o.force_direct, c->o.batch, op.out.h, op.out.w, op.cout_p, op.d.k,
                                              op.d.stride, op.d.pad);
@@ -1304,13 +1304,18 @@ template <class T> struct Exec {
     }
 
     // ---- loss and its gradient (fused) -----------------------------------
-    {
-      const Shape s = bp.shapes.back();
-      const long numel = (long)N * s.h * s.w * s.c;   // outputs have no padded channels
-      const long nvec = (long)N * s.h * s.w * round8(s.c) / 8;
+    // A block that ends in an add whose backward pass rides in a batch-norm reduction (below): that reduction also
+    // forms the loss and its gradient from the block's output and the teacher's activation.
+    const Shape s_out = bp.shapes.back();
+    const long numel = (long)N * s_out.h * s_out.w * s_out.c;   // outputs have no padded channels
+    const int last = (int)bp.ops.size() - 1;
+    const bool loss_rides = !arch && last >= 1 && bp.ops[last].d.type == OP_ADD && residual_reader(bp, last - 1) == last &&
+                            !short_column((long)N * s_out.h * s_out.w);
+    if (!loss_rides) {
+      const long nvec = (long)N * s_out.h * s_out.w * round8(s_out.c) / 8;
       const int nb = (int)std::min<long>(kMseBlocks, (nvec + 255) / 256);
       opi = -1;
-      ProfScope ps(c, "mse_loss_grad", 3 * bytes_of(s), 0, net, blk, opi);
+      ProfScope ps(c, "mse_loss_grad", 3 * bytes_of(s_out), 0, net, blk, opi);
       launch(c, mse_kernel<T>, nb, 256, 0, st, value(nval - 1), srelay(b + 1), dvalue(nval - 1), red(), nvec, (float)(2.0 / (double)numel));
       launch(c, mse_final_kernel, 1, 256, 0, st, red(), nb, 1.0 / (double)numel, loss_dev);
     }
@@ -1332,8 +1337,8 @@ template <class T> struct Exec {
     // An add whose backward pass rides in the batch-norm backward of the layer right before it (the one whose
     // normalisation pass carried the add on the way forward): that layer's reduction reads the add's output
     // gradient, masks it and stores the result once, where the add's other input collects its gradient.
-    struct AddBwd { const T* dz; const T* z; int act; T* dstore; };
-    std::vector<AddBwd> add_bwd(bp.ops.size(), AddBwd{nullptr, nullptr, 0, nullptr});
+    struct AddBwd { const T* dz; const T* z; int act; T* dstore; bool loss; };
+    std::vector<AddBwd> add_bwd(bp.ops.size(), AddBwd{nullptr, nullptr, 0, nullptr, false});
     for (int j = (int)bp.ops.size() - 1; j >= 0; --j) {
       const OpPlan& op = bp.ops[j];
       opi = j;
@@ -1344,8 +1349,9 @@ template <class T> struct Exec {
           !short_column((long)N * op.out.h * op.out.w)) {
         const int other = op.d.in[0] == j ? op.d.in[1] : op.d.in[0];
         if (!wanted[other] || !have[other]) {      // (a gradient already there would have to be added to, not replaced)
-          add_bwd[j - 1] = AddBwd{dz, op.d.act != ACT_NONE ? value(j + 1) : nullptr, op.d.act,
-                                  wanted[other] ? dvalue(other) : dvalue(j)};
+          const bool loss = loss_rides && j == last;   // (dz: the teacher's activation instead of a gradient)
+          add_bwd[j - 1] = AddBwd{loss ? srelay(b + 1) : dz, op.d.act != ACT_NONE || loss ? value(j + 1) : nullptr, op.d.act,
+                                  wanted[other] ? dvalue(other) : dvalue(j), loss};
           if (wanted[other]) have[other] = 1;
           have[j] = 1;
           continue;
@@ -1364,16 +1370,25 @@ template <class T> struct Exec {
                  op.cout_p, op.d.act, (unsigned)(M * op.cout_p * sizeof(T)));
         } else {
           const ColGrid g = bn_bwd_grid(M, op.cout_p);
-          if (ab.dz) {
+          if (ab.loss) {
+            float* loss_part = red() + (size_t)g.chunks * 2 * op.cout_p;
+            {
+              ProfScope ps(c, "bn_bwd_reduce_add_mse", 4 * bytes_of(op.out), 0, net, blk, opi);
+              launch(c, bn_bwd_reduce_kernel<T, true, true>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
+                  ab.dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
+                  op.d.act, g, ab.z, ab.act, ab.dstore, loss_part, (float)(2.0 / (double)numel));
+            }
+            launch(c, mse_final_kernel, 1, 256, 0, st, loss_part, g.slabs * g.chunks, 1.0 / (double)numel, loss_dev);
+          } else if (ab.dz) {
             ProfScope ps(c, "bn_bwd_reduce_add", (ab.z ? 4 : 3) * bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_bwd_reduce_kernel<T, true>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
                 ab.dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
-                op.d.act, g, ab.z, ab.act, ab.dstore);
+                op.d.act, g, ab.z, ab.act, ab.dstore, (float*)nullptr, 0.f);
           } else {
             ProfScope ps(c, "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
             launch(c, bn_bwd_reduce_kernel<T, false>, dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
                 (const T*)dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
-                op.d.act, g, (const T*)nullptr, 0, (T*)nullptr);
+                op.d.act, g, (const T*)nullptr, 0, (T*)nullptr, (float*)nullptr, 0.f);
           }
           launch(c, bn_bwd_finalize_kernel, op.cout_p / kFinalizeChannels, 256, 0, st, red(), g.chunks, op.cout_p, (double)M,
                                                                            grad + op.e_gamma, grad + op.e_beta,
@@ -2043,6 +2058,11 @@ int pbd_read_grad_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n)
   if (!bp.stepped) return fail(c, PBD_ESTATE, "block %d holds no saved values (not stepped, or scratch reused)", b);
   const Shape s = bp.shapes[v];
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
+  const int last = (int)bp.ops.size() - 1;
+  if (v == last + 1 && last >= 1 && bp.ops[last].d.type == OP_ADD && residual_reader(bp, last - 1) == last &&
+      !short_column((long)c->o.batch * s.h * s.w))
+    return fail(c, PBD_ESTATE, "the gradient of the output of block %d is not stored: the batch-norm reduction that does the last add's "
+                "backward pass forms it from the block's output and the teacher's activation", b);
   return download_act(c, c->ws + bp.scr_off + bp.dval[v], s, host);
 }
 

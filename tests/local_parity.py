@@ -156,8 +156,15 @@ def check_block(d, wl, b, par, lr, floor=2e-5, fwd_ops=None, bwd_values=None, lo
     grads = {}
 
     def G(v):
+        """The stored gradient of value v; for a block output whose gradient the library never stores (it is
+        formed inside the reduction that does the last add's backward pass): the stored form of its definition."""
         if v not in grads:
-            grads[v] = d.read_grad_value(b, v).astype(np.float64)
+            try:
+                grads[v] = d.read_grad_value(b, v).astype(np.float64)
+            except pbd.PbdError as e:
+                if e.code != -4 or v != nval - 1:
+                    raise
+                grads[v] = R(dS.reshape(value(v).shape))
         return grads[v]
 
     for v in range(nval - 1, 0, -1):
