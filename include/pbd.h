@@ -124,7 +124,8 @@ int pbd_read_act(pbd_ctx* ctx, int32_t i, float* host, size_t n);
  * side in the workspace they share one region and the values are valid only until another
  * block is stepped (PBD_ESTATE afterwards).  The output of a layer without activation whose only reader is
  * a two-input add is never written (the add is fused into the layer's normalisation pass; PBD_ESTATE);
- * read the add's output instead.  Testing aid; waits. */
+ * read the add's output instead.  Likewise the output of a layer whose only reader is a max-pool (the pool
+ * normalises the convolution output as it reads it).  Testing aid; waits. */
 int pbd_read_value(pbd_ctx* ctx, int32_t b, int32_t v, float* host, size_t n);
 
 /* More of what the last pbd_student_step of student block b (from 0) left behind, for checking one layer at a

@@ -874,9 +874,15 @@ __global__ __launch_bounds__(kSmallThreads) void bn_small_bwd_kernel(
 // ---------------------------------------------------------------------------
 // max-pool; idx keeps the window position r*k+t of the first maximum
 // ---------------------------------------------------------------------------
+// The producing layer's normalisation and activation applied to every element a pool reads (mean == nullptr: x is
+// read as it is): x is then that layer's convolution output, each element becomes what bn_apply_kernel would have
+// stored (same arithmetic, same rounding), and the normalised tensor, which only the pool reads, is never written.
+struct NormFold { const float* mean; const float* invstd; const float* gamma; const float* beta; int act; };
+
 template <class T>
 __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ z, uint8_t* __restrict__ idx,
-                                   int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad) {
+                                   int N, int H, int W, int P, int Q, int ncv, int k, int stride, int pad,
+                                   NormFold fold) {
   const long nvec = (long)N * P * Q * ncv;
   for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
     const int cv = (int)(i % ncv);
@@ -888,6 +894,14 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ z, u
     int bi[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) { best[e] = 0.f; bi[e] = -1; }
+    float mu[8], fa[8], fb[8];
+    if (fold.mean) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int ch = cv * 8 + e;
+        mu[e] = fold.mean[ch]; fa[e] = fold.gamma[ch] * fold.invstd[ch]; fb[e] = fold.beta[ch];
+      }
+    }
     for (int r = 0; r < k; ++r) {
       const int h = p * stride + r - pad;
       if (h < 0 || h >= H) continue;
@@ -896,6 +910,10 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ z, u
         if (w < 0 || w >= W) continue;
         float v[8];
         IO<T>::ld(x + ((((long)n * H + h) * W + w) * ncv + cv) * 8, v);
+        if (fold.mean) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = as_stored<T>(apply_act(fmaf(v[e] - mu[e], fa[e], fb[e]), fold.act));
+        }
 #pragma unroll
         for (int e = 0; e < 8; ++e)
           if (bi[e] < 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = r * k + t; }

@@ -633,6 +633,20 @@ int residual_reader(const BlockPlan& bp, int j) {
 }
 // few enough rows for the whole-column BN kernels (one block per 8-channel slab)
 inline bool short_column(long M) { return M <= (long)kSmallThreads * kSmallRows; }
+// For student layer j: the index of a max-pool that is the only reader of j's output (the pool then normalises what
+// it reads and the normalised tensor is never written), else -1.
+int pool_reader(const BlockPlan& bp, int j, int batch) {
+  const OpPlan& p = bp.ops[j];
+  if (p.d.type != OP_CBA || j + 2 == (int)bp.shapes.size() || short_column((long)batch * p.out.h * p.out.w)) return -1;
+  int reader = -1, uses = 0;
+  for (int k = j + 1; k < (int)bp.ops.size(); ++k) {
+    const OpD& q = bp.ops[k].d;
+    const int nin = q.type == OP_ADD || q.type == OP_MIX ? q.nin : 1;
+    for (int i = 0; i < nin; ++i)
+      if (q.in[i] == j + 1) { ++uses; reader = k; }
+  }
+  return uses == 1 && bp.ops[reader].d.type == OP_POOL ? reader : -1;
+}
 
 template <class T> struct Exec {
   pbd_ctx* c;
@@ -1029,12 +1043,13 @@ template <class T> struct Exec {
     ProfScope ps(c, "join_fwd", bytes_of(op.out) * (j.n + 1), 0, net, blk, opi);
     launch(c, join_fwd_kernel<T>, grid_for(nvec), 256, 0, st, j, z, nvec, op.d.act);
   }
-  void pool_fwd(const OpPlan& op, const T* x, T* z, uint8_t* idx) {
+  // fold (optional): x is the producing layer's convolution output, normalised and activated as it is read
+  void pool_fwd(const OpPlan& op, const T* x, T* z, uint8_t* idx, NormFold fold = NormFold{}) {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
-    ProfScope ps(c, "maxpool_fwd", bytes_of(op.in) + bytes_of(op.out), 0, net, blk, opi);
+    ProfScope ps(c, fold.mean ? "bn_apply_maxpool" : "maxpool_fwd", bytes_of(op.in) + bytes_of(op.out) * (idx ? 1.5 : 1.0), 0, net, blk, opi);
     launch(c, maxpool_fwd_kernel<T>, grid_for(nvec), 256, 0, st, x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
-                                                          op.d.k, op.d.stride, op.d.pad);
+                                                          op.d.k, op.d.stride, op.d.pad, fold);
   }
 
   // =========================================================================
@@ -1269,7 +1284,7 @@ template <class T> struct Exec {
           launch(c, bn_finalize_kernel<T>, op.cout_p / kFinalizeChannels, 256, 0, st, 
               part, pivot, chunks, op.cout_p, (double)M, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_rmean),
               wsf(op.s_rvar), c->o.bn_eps, c->o.bn_momentum);
-          {
+          if (pool_reader(bp, (int)j, N) < 0) {
             const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);   // elementwise pass: many short workgroups
             // a residual add that only reads this layer's output rides along: the normalised tensor itself
             // is never written (the backward pass needs y and the sum, not it)
@@ -1290,7 +1305,12 @@ template <class T> struct Exec {
           }
         }
       } else if (op.d.type == OP_POOL) {
-        pool_fwd(op, x, z, reinterpret_cast<uint8_t*>(c->ws + scr + op.idx));
+        const int pv = op.d.in[0];
+        if (pv >= 1 && pool_reader(bp, pv - 1, N) == (int)j) {
+          const OpPlan& p = bp.ops[pv - 1];
+          pool_fwd(op, ws(scr + p.y), z, reinterpret_cast<uint8_t*>(c->ws + scr + op.idx),
+                   NormFold{wsf(p.s_mean), wsf(p.s_invstd), master + p.e_gamma, master + p.e_beta, p.d.act});
+        } else pool_fwd(op, x, z, reinterpret_cast<uint8_t*>(c->ws + scr + op.idx));
       } else {
         Join jn{};
         jn.n = op.d.nin;
@@ -2017,6 +2037,8 @@ int pbd_read_value(pbd_ctx* c, int32_t b, int32_t v, float* host, size_t n) {
   if (n != (size_t)c->o.batch * s.c * s.h * s.w) return fail(c, PBD_ESHAPE, "value has %zu elements, %zu asked", (size_t)c->o.batch * s.c * s.h * s.w, n);
   if (v > 0 && !short_column((long)c->o.batch * s.h * s.w) && residual_reader(bp, v - 1) >= 0)
     return fail(c, PBD_ESTATE, "value %d of block %d is not kept: the residual add that reads it is fused into its normalisation", v, b);
+  if (v > 0 && pool_reader(bp, v - 1, c->o.batch) >= 0)
+    return fail(c, PBD_ESTATE, "value %d of block %d is not kept: the max-pool that reads it normalises the convolution output itself", v, b);
   const char* dev = v == 0 ? relay_ptr(c, b) : c->ws + bp.scr_off + bp.val[v];
   return download_act(c, dev, s, host);
 }
