@@ -27,10 +27,11 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # and the kernel build they were measured on.
 HBM_TRAFFIC_PER_LAUNCH = {
     "resnet50_x1.5": ("profiles/resnet50_x1.5_step_hbm_traffic.md", {
-        "bn_bwd_apply": 369896112, "bn_bwd_reduce": 248323872, "join_bwd": 706513706, "mse_loss_grad": 578062948,
-        "wgrad_128x128": 310514046, "wgrad_192x256": 237289497, "wgrad_256x256": 218341152,
-        "igemm_fwd_256x192x64_store": 234847575, "igemm_dgrad_256x192x64_store": 167042916,
-        "igemm_fwd_256x256x64_affine": 111681087, "igemm_fwd_256x256x64_store": 221355566,
+        "bn_bwd_apply": 369895863, "bn_bwd_reduce": 201990541, "bn_bwd_reduce_add": 687340294,
+        "bn_bwd_reduce_add_mse": 773031012,
+        "wgrad_128x128": 307544684, "wgrad_192x256": 237281450, "wgrad_256x256": 218341131,
+        "igemm_fwd_256x192x64_store": 234804308, "igemm_dgrad_256x192x64_store": 167010262,
+        "igemm_fwd_256x256x64_affine": 111676392, "igemm_fwd_256x256x64_store": 221360500,
     }),
 }
 
