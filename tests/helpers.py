@@ -140,6 +140,23 @@ def layer_workloads():
             sc = s.cba(v1, 256, 1, 2, act=W.ACT_NONE)
         s.add(v, sc, W.ACT_RELU)
         wl(name, (24, 46, 46), t, s, 48)
+    # an inverted-residual block whose skip is the block's input (no gradient wanted there) and whose add is the
+    # block's last op: 6272 pixels, so the add's backward pass and the loss ride in the projection's batch-norm
+    # backward reduction
+    t, s = W.Block(), W.Block()
+    W._mbconv(t, 0, 32, 32, 3, 6, 1)
+    W._mbconv(s, 0, 32, 32, 7, 3, 1)
+    wl("l_res_from_input", (32, 14, 14), t, s, 32)
+    # two fused adds, 6400 pixels: the last one carries the loss; the first one's skip input already holds a
+    # gradient when its turn comes (a later layer reads the same value), so it keeps the separate add backward
+    t, s = W.Block(), W.Block()
+    t.cba(0, 24, 3)
+    v1 = s.cba(0, 24, 1)
+    c = s.cba(v1, 24, 3, act=W.ACT_NONE)
+    a = s.add(v1, c, W.ACT_RELU)
+    e = s.cba(v1, 24, 1, act=W.ACT_NONE)
+    s.add(a, e, W.ACT_RELU)
+    wl("l_add_bwd_paths", (24, 20, 20), t, s, 16)
     return out
 
 

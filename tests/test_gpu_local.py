@@ -28,6 +28,17 @@ def test_every_layer_of_the_real_graphs_against_the_plain_oracle(name, batch, hw
     print(f"[{name}] worst per kind over all blocks: " + ", ".join(f"{k} {v:.1e}" for k, v in sorted(worst.items())), flush=True)
 
 
+@pytest.mark.parametrize("name", ["l_res_from_input", "l_add_bwd_paths", "l_s2_classes", "l_stem7x7"])
+def test_layer_walk_where_adds_losses_and_pools_ride_in_other_kernels(name):
+    """Blocks whose residual adds are done inside the batch-norm passes of the layer before them (forward and
+    backward), whose loss is formed inside that backward reduction, or whose max-pool normalises what it reads:
+    every operation against the plain oracle primitives, as for the real graphs."""
+    from helpers import layer_workloads
+    wl, batch = [c for c in layer_workloads() if c[0].name == name][0]
+    worst = local_parity.run_and_check(wl, batch)
+    print(f"[{name}] worst per kind: " + ", ".join(f"{k} {v:.1e}" for k, v in sorted(worst.items())), flush=True)
+
+
 def test_layer_walk_catches_a_planted_mistake():
     """The walk is only worth something if a wrong tensor fails it: the same check against a reference whose
     parameters are off by a few per cent in one layer (a mistake planted on the oracle's side) must fail."""
