@@ -23,14 +23,16 @@ def test_resnet50_stage1_and_stage4_layers_at_full_batch():
     ops = wl.student[0].ops
     assert (ops[3].k, ops[3].c_out, ops[9].k, ops[9].act, ops[10].type) == (3, 96, 1, W.ACT_NONE, W.OP_ADD)
     assert (wl.student[3].ops[1].k, wl.student[3].ops[1].stride) == (3, 2)
+    assert (wl.student[3].ops[11].k, wl.student[3].ops[12].type, len(wl.student[3].ops)) == (1, W.OP_ADD, 13)
     sel = {
         # stage 1 (56 x 56, 802816 rows): 3 x 3 96 -> 96; 1 x 1 96 -> 256 whose output only the fused add reads;
         # value 11 = that add's output, read by a 1 x 1 (backward-data) and by the next add (two gradients meet)
         0: ({3, 9, 10}, {4, 10, 11}),
         # stage 4: the stride-2 3 x 3 768 -> 768 from 14 x 14 (its backward-data takes the input pixels parity class
         # by parity class and writes the gradient of value 1); at 7 x 7 (12544 rows) 3 x 3 768 -> 768 and
-        # 1 x 1 768 -> 2048 + fused add
-        3: ({1, 6, 7, 8}, {1, 7, 8}),
+        # 1 x 1 768 -> 2048 + fused add; op 11 = the block's last 1 x 1, whose batch-norm backward reduction also does
+        # the last add's backward pass and forms the loss and its gradient from S_4 and A_4
+        3: ({1, 6, 7, 8, 11}, {1, 7, 8, 12}),
     }
     worst = local_parity.run_and_check(wl, wl.batch, sel)
     print("worst per kind:", {k: f"{v:.1e}" for k, v in sorted(worst.items())}, flush=True)
