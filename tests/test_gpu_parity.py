@@ -55,6 +55,17 @@ def test_f32_path_matches_fp64_oracle(wl):
     _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
 
 
+@pytest.mark.parametrize("name", ["l_add_bwd_paths", "l_res_from_input", "l_stem7x7"])
+def test_f32_where_adds_losses_and_pools_ride_in_other_kernels(name):
+    """The kernels that do a residual add's backward pass (and the loss) inside a batch-norm backward reduction,
+    and the max-pool that normalises what it reads, are templates over the tensor type: in float32, on blocks long
+    enough to take them (more than 4096 pixels), every tensor of two consecutive steps against the fp64 oracle
+    at 1e-4."""
+    wl, batch = [c for c in layer_workloads() if c[0].name == name][0]
+    errs = parity.compare_step(wl, batch=batch, precision="f32", steps=2, kink_floor=KINK_FLOOR)
+    _assert_all({k: v for k, v in errs.items() if not k.endswith(".l2g")}, TOL_F32)
+
+
 @pytest.mark.parametrize("precision", ["f32", "bf16"])
 def test_long_columns_take_the_chunked_bn_kernels(precision):
     """Batch 96 gives the first two blocks M = 98304 and 24576 rows: above the whole-column limit (4096 rows
