@@ -50,6 +50,8 @@ template <> struct IO<float> {
   static __device__ __forceinline__ Raw ld_raw(const float* p) {
     Raw q; q.a = reinterpret_cast<const float4*>(p)[0]; q.b = reinterpret_cast<const float4*>(p)[1]; return q;
   }
+  template <bool STREAM> static __device__ __forceinline__ Raw ld_raw_t(const float* p) { return ld_raw(p); }
+  template <bool STREAM> static __device__ __forceinline__ void st_t(float* p, const float v[8]) { st(p, v); }
   static __device__ __forceinline__ void unpack(const Raw& q, float v[8]) {
     v[0] = q.a.x; v[1] = q.a.y; v[2] = q.a.z; v[3] = q.a.w; v[4] = q.b.x; v[5] = q.b.y; v[6] = q.b.z; v[7] = q.b.w;
   }
@@ -65,6 +67,19 @@ template <> struct IO<float> {
 template <> struct IO<bf16_t> {
   typedef uint4 Raw;
   static __device__ __forceinline__ Raw ld_raw(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  // STREAM: nontemporal forms for the passes over tensors far larger than the caches: a line that is read or
+  // written once per pass does not push out what the convolutions running beside the pass keep in L2
+  typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
+  template <bool STREAM> static __device__ __forceinline__ Raw ld_raw_t(const bf16_t* p) {
+    if (!STREAM) return ld_raw(p);
+    const u32x4_nt q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(p));
+    return make_uint4(q.x, q.y, q.z, q.w);
+  }
+  template <bool STREAM> static __device__ __forceinline__ void st_t(bf16_t* p, const float v[8]) {
+    if (!STREAM) { st(p, v); return; }
+    u32x4_nt q = {pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7])};
+    __builtin_nontemporal_store(q, reinterpret_cast<u32x4_nt*>(p));
+  }
   static __device__ __forceinline__ void unpack(const Raw& u, float v[8]) {
     v[0] = bf_lo(u.x); v[1] = bf_hi(u.x); v[2] = bf_lo(u.y); v[3] = bf_hi(u.y);
     v[4] = bf_lo(u.z); v[5] = bf_hi(u.z); v[6] = bf_lo(u.w); v[7] = bf_hi(u.w);
@@ -293,7 +308,7 @@ template <> __device__ __forceinline__ float as_stored<bf16_t>(float v) { return
 
 // res (optional): a residual add fused into the pass, z = res_act(stored(act(bn(y))) + res): the same
 // numbers as storing the normalised tensor and adding in a second kernel, without that tensor
-template <class T>
+template <class T, bool STREAM = false>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, T* __restrict__ z,
                                                        const float* __restrict__ mean,
                                                        const float* __restrict__ invstd,
@@ -316,10 +331,10 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
   for (; r + 3 * rl < r1; r += 4 * rl) {             // four rows (with a residual: eight loads) in flight
     typename IO<T>::Raw yr[4], sr[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+    for (int u = 0; u < 4; ++u) yr[u] = IO<T>::template ld_raw_t<STREAM>(y + ((r + u * rl) * ncv + cv) * 8);
     if (res) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) sr[u] = IO<T>::ld_raw(res + ((r + u * rl) * ncv + cv) * 8);
+      for (int u = 0; u < 4; ++u) sr[u] = IO<T>::template ld_raw_t<STREAM>(res + ((r + u * rl) * ncv + cv) * 8);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -334,7 +349,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
 #pragma unroll
         for (int k = 0; k < 8; ++k) v[k] = apply_act(as_stored<T>(v[k]) + s[k], res_act);
       }
-      IO<T>::st(z + ((r + u * rl) * ncv + cv) * 8, v);
+      IO<T>::template st_t<STREAM>(z + ((r + u * rl) * ncv + cv) * 8, v);
     }
   }
   for (; r < r1; r += rl) {
@@ -348,14 +363,14 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const T* __restrict__ y, 
 #pragma unroll
       for (int k = 0; k < 8; ++k) v[k] = apply_act(as_stored<T>(v[k]) + s[k], res_act);
     }
-    IO<T>::st(z + (r * ncv + cv) * 8, v);
+    IO<T>::template st_t<STREAM>(z + (r * ncv + cv) * 8, v);
   }
 }
 
 // part[chunk][0][c] = sum (y - piv), part[chunk][1][c] = sum (y - piv)^2 with the pivot
 // piv[c] = y[row 0][c]: shifting by a sample of the channel keeps the variance free of the
 // cancellation that  E[y^2] - mean^2  suffers when |mean| >> std
-template <class T>
+template <class T, bool STREAM = false>
 __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, float* __restrict__ part,
                                                        long M, int Cp, ColGrid g) {
   extern __shared__ float smem[];
@@ -374,7 +389,7 @@ __global__ __launch_bounds__(256) void bn_stats_kernel(const T* __restrict__ y, 
     for (; r + 3 * rl < r1; r += 4 * rl) {           // four rows in flight
       typename IO<T>::Raw yr[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+      for (int u = 0; u < 4; ++u) yr[u] = IO<T>::template ld_raw_t<STREAM>(y + ((r + u * rl) * ncv + cv) * 8);
       __builtin_amdgcn_sched_barrier(0);
       float v[4][8];
 #pragma unroll
@@ -481,7 +496,7 @@ __global__ void regroup_partials_kernel(const float* __restrict__ part, float* _
 // LOSS (with RES and zres): the add's output is the block's output S.  dz is then the teacher's activation A,
 // the gradient of the add's output is 2 (S - A) / M rounded as it would be stored (Sec. II-A, the loss of the
 // block's output), and loss_part[workgroup] = sum (S - A)^2 over the workgroup's elements.
-template <class T, bool RES = false, bool LOSS = false>
+template <class T, bool RES = false, bool LOSS = false, bool STREAM = false>
 __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
     const T* __restrict__ dz, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
@@ -513,12 +528,12 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
       typename IO<T>::Raw dr[4], yr[4], zr[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        dr[u] = IO<T>::ld_raw(dz + ((r + u * rl) * ncv + cv) * 8);
-        yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+        dr[u] = IO<T>::template ld_raw_t<STREAM>(dz + ((r + u * rl) * ncv + cv) * 8);
+        yr[u] = IO<T>::template ld_raw_t<STREAM>(y + ((r + u * rl) * ncv + cv) * 8);
       }
       if (RES && zres) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) zr[u] = IO<T>::ld_raw(zres + ((r + u * rl) * ncv + cv) * 8);
+        for (int u = 0; u < 4; ++u) zr[u] = IO<T>::template ld_raw_t<STREAM>(zres + ((r + u * rl) * ncv + cv) * 8);
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -541,7 +556,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 #pragma unroll
             for (int k = 0; k < 8; ++k) d[k] = act_pass(z[k], res_act) ? d[k] : 0.f;
           }
-          IO<T>::st(dstore + ((r + u * rl) * ncv + cv) * 8, d);
+          IO<T>::template st_t<STREAM>(dstore + ((r + u * rl) * ncv + cv) * 8, d);
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -571,7 +586,7 @@ __global__ __launch_bounds__(256) void bn_bwd_reduce_kernel(
 #pragma unroll
           for (int k = 0; k < 8; ++k) d[k] = act_pass(z[k], res_act) ? d[k] : 0.f;
         }
-        IO<T>::st(dstore + (r * ncv + cv) * 8, d);
+        IO<T>::template st_t<STREAM>(dstore + (r * ncv + cv) * 8, d);
       }
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
@@ -618,7 +633,7 @@ __global__ void bn_bwd_finalize_kernel(const float* __restrict__ part, int chunk
 
 // stage 3: gradient w.r.t. the convolution output, written to dy (dy == dz: in place; column-grid launch, each
 // thread reads its elements before it writes them)
-template <class T>
+template <class T, bool STREAM = false>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     const T* dz, T* dy, const T* __restrict__ y, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ invstd,
@@ -641,8 +656,8 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
     typename IO<T>::Raw dr[4], yr[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      dr[u] = IO<T>::ld_raw(dz + ((r + u * rl) * ncv + cv) * 8);
-      yr[u] = IO<T>::ld_raw(y + ((r + u * rl) * ncv + cv) * 8);
+      dr[u] = IO<T>::template ld_raw_t<STREAM>(dz + ((r + u * rl) * ncv + cv) * 8);
+      yr[u] = IO<T>::template ld_raw_t<STREAM>(y + ((r + u * rl) * ncv + cv) * 8);
     }
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -656,7 +671,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
         const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
         d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
       }
-      IO<T>::st(dy + ((r + u * rl) * ncv + cv) * 8, d);
+      IO<T>::template st_t<STREAM>(dy + ((r + u * rl) * ncv + cv) * 8, d);
     }
   }
   for (; r < r1; r += rl) {
@@ -669,7 +684,7 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(
       const float dp = act_pass(fmaf(yc, a[k], b[k]), act) ? d[k] : 0.f;
       d[k] = a[k] * (dp - c2[k] - yc * is[k] * c3[k]);
     }
-    IO<T>::st(dy + (r * ncv + cv) * 8, d);
+    IO<T>::template st_t<STREAM>(dy + (r * ncv + cv) * 8, d);
   }
 }
 
