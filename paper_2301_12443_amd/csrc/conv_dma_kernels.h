@@ -389,7 +389,13 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
               v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(r_.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(r_.w), g.res_act));
             }
           }
-          *reinterpret_cast<uint4*>(Out + out_row(row) * g.NC + col) = v;
+          if (g.stream_out) {                    // a tensor far larger than the caches: its lines are not kept there
+            typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
+            const u32x4_nt q = {v.x, v.y, v.z, v.w};
+            __builtin_nontemporal_store(q, reinterpret_cast<u32x4_nt*>(Out + out_row(row) * g.NC + col));
+          } else {
+            *reinterpret_cast<uint4*>(Out + out_row(row) * g.NC + col) = v;
+          }
         }
       }
     }

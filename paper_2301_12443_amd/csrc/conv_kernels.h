@@ -155,6 +155,8 @@ struct IgemmArgs {
   // igemm_dma_kernel, forward only: a tap gathers a run of 1 << pix_shift neighbouring pixels of CA >> pix_shift
   // channels each (CA contiguous elements; S counts such runs).  0: a tap is one pixel of CA channels
   int pix_shift;
+  // igemm_dma_kernel: the output is stored with nontemporal stores (tensors far larger than the caches)
+  int stream_out;
 };
 
 // EPI_PARTIAL: raw fp32 partial tile of a split-K launch, summed by splitk_epilogue_kernel

@@ -760,6 +760,7 @@ template <class T> struct Exec {
       else g.par_classes = 0;               // (the other kernels take the rows in pixel order)
     }
     if (dc.use && (epi == EPI_STORE || epi == EPI_AFFINE_ACT || epi == EPI_ACCUM)) {
+      g.stream_out = (double)g.M * g.NC * 2.0 >= 64.0 * 1048576.0;   // (as for the batch-norm passes: see streams())
       g.tiles_n = dc.tiles_n;
       g.tiles_m = dc.big_m + dc.tail_m;
       g.splits = 1;
