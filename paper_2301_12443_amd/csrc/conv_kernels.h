@@ -155,7 +155,7 @@ struct IgemmArgs {
   // igemm_dma_kernel, forward only: a tap gathers a run of 1 << pix_shift neighbouring pixels of CA >> pix_shift
   // channels each (CA contiguous elements; S counts such runs).  0: a tap is one pixel of CA channels
   int pix_shift;
-  // igemm_dma_kernel: the output is stored with nontemporal stores (tensors far larger than the caches)
+  // the staged stores of the output are nontemporal (tensors far larger than the caches)
   int stream_out;
 };
 
@@ -470,7 +470,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const bf16_t* __restrict__ A
           v.z = pack_bf2(apply_act(bf_lo(v.z) + bf_lo(r_.z), g.res_act), apply_act(bf_hi(v.z) + bf_hi(r_.z), g.res_act));
           v.w = pack_bf2(apply_act(bf_lo(v.w) + bf_lo(r_.w), g.res_act), apply_act(bf_hi(v.w) + bf_hi(r_.w), g.res_act));
         }
-        *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = v;
+        if (g.stream_out) {                      // a tensor far larger than the caches: its lines are not kept there
+          typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
+          const u32x4_nt q = {v.x, v.y, v.z, v.w};
+          __builtin_nontemporal_store(q, reinterpret_cast<u32x4_nt*>(Out + (size_t)row * g.NC + col));
+        } else {
+          *reinterpret_cast<uint4*>(Out + (size_t)row * g.NC + col) = v;
+        }
       }
     }
     if (EPI == EPI_STORE && g.stats) {

@@ -743,6 +743,7 @@ template <class T> struct Exec {
   void launch_igemm(IgemmArgs g, const bf16_t* A, const bf16_t* Bw, bf16_t* out, const float* a,
                     const float* b, int act, int epi, double bytes, double flops) {
     DmaCfg dc = dma_for(g.M, g.NC, g.Kred, g.CA, epi);
+    g.stream_out = (double)g.M * g.NC * 2.0 >= 64.0 * 1048576.0;   // (as for the batch-norm passes: see streams())
     if (MODE == 1 && g.par_classes) {
       // parity classes: par_classes x ceil(rows of a class / 256) row tiles, no tail tiles
       const long mc = (long)g.N * (g.HO / 2) * (g.WO / 2);
@@ -760,7 +761,6 @@ template <class T> struct Exec {
       else g.par_classes = 0;               // (the other kernels take the rows in pixel order)
     }
     if (dc.use && (epi == EPI_STORE || epi == EPI_AFFINE_ACT || epi == EPI_ACCUM)) {
-      g.stream_out = (double)g.M * g.NC * 2.0 >= 64.0 * 1048576.0;   // (as for the batch-norm passes: see streams())
       g.tiles_n = dc.tiles_n;
       g.tiles_m = dc.big_m + dc.tail_m;
       g.splits = 1;
