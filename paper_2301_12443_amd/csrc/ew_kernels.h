@@ -1457,7 +1457,7 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
                                                       bf16_t* dst, const float* __restrict__ a,
                                                       const float* __restrict__ b, int act, int accumulate,
                                                       int N, int H, int W, int ncv, int tiles_h, int tiles_w,
-                                                      unsigned x_bytes) {
+                                                      unsigned x_bytes, int stream) {
   constexpr int TH = kDwTileH, TW = kDwTileW, WS = 4, CVB = kDwTileCv, PIXB = kDwTilePitch;
   constexpr int IH = TH + K - 1, IW = TW + K - 1, NIN = WS + K - 1, pad = K / 2;
   constexpr int TOTAL = IH * IW * CVB, NLOAD = (TOTAL + 255) / 256;
@@ -1562,7 +1562,8 @@ __global__ __launch_bounds__(256) void dw_tile_kernel(const bf16_t* __restrict__
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[o][e] += old[e];
     }
-    IO<bf16_t>::st(out, acc[o]);
+    if (stream) IO<bf16_t>::st_t<true>(out, acc[o]);   // (outputs far larger than the caches)
+    else IO<bf16_t>::st(out, acc[o]);
   }
 }
 

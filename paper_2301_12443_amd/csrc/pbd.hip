@@ -949,7 +949,7 @@ template <class T> struct Exec {
         const int th = (op.out.h + kDwTileH - 1) / kDwTileH, tw = (op.out.w + kDwTileW - 1) / kDwTileW;
         const dim3 grid(N * th * tw, (ncv + kDwTileCv - 1) / kDwTileCv);
 #define PBD_DWT(K_) launch(c, dw_tile_kernel<K_, false>, grid, 256, 0, st, (const bf16_t*)x, (const bf16_t*)w, (bf16_t*)y, a, b, act, 0, \
-    N, op.in.h, op.in.w, ncv, th, tw, xe * 2u)
+    N, op.in.h, op.in.w, ncv, th, tw, xe * 2u, streams(op.out) ? 1 : 0)
         if (op.d.k == 3) PBD_DWT(3); else if (op.d.k == 5) PBD_DWT(5); else PBD_DWT(7);
 #undef PBD_DWT
       }
@@ -982,7 +982,7 @@ template <class T> struct Exec {
         const int th = (op.in.h + kDwTileH - 1) / kDwTileH, tw = (op.in.w + kDwTileW - 1) / kDwTileW;
         const dim3 grid(N * th * tw, (ncv + kDwTileCv - 1) / kDwTileCv);
 #define PBD_DWT(K_) launch(c, dw_tile_kernel<K_, true>, grid, 256, 0, st, (const bf16_t*)dy, (const bf16_t*)w, (bf16_t*)dx, (const float*)nullptr, \
-    (const float*)nullptr, 0, accumulate ? 1 : 0, N, op.out.h, op.out.w, ncv, th, tw, de * 2u)
+    (const float*)nullptr, 0, accumulate ? 1 : 0, N, op.out.h, op.out.w, ncv, th, tw, de * 2u, streams(op.in) ? 1 : 0)
         if (op.d.k == 3) PBD_DWT(3); else if (op.d.k == 5) PBD_DWT(5); else PBD_DWT(7);
 #undef PBD_DWT
       }
