@@ -27,11 +27,11 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # and the kernel build they were measured on.
 HBM_TRAFFIC_PER_LAUNCH = {
     "resnet50_x1.5": ("profiles/resnet50_x1.5_step_hbm_traffic.md", {
-        "bn_bwd_apply": 369895863, "bn_bwd_reduce": 201990541, "bn_bwd_reduce_add": 687340294,
-        "bn_bwd_reduce_add_mse": 773031012,
-        "wgrad_128x128": 307544684, "wgrad_192x256": 237281450, "wgrad_256x256": 218341131,
-        "igemm_fwd_256x192x64_store": 234804308, "igemm_dgrad_256x192x64_store": 167010262,
-        "igemm_fwd_256x256x64_affine": 111676392, "igemm_fwd_256x256x64_store": 221360500,
+        "bn_bwd_apply_nt": 529370651, "bn_bwd_apply": 109015133, "bn_bwd_reduce_nt": 316330953, "bn_bwd_reduce": 68897254,
+        "bn_bwd_reduce_add_nt": 783209522, "bn_bwd_reduce_add_mse_nt": 961378955,
+        "wgrad_128x128": 305761204, "wgrad_192x256": 237290720, "wgrad_256x256": 218338070,
+        "igemm_fwd_256x192x64_store": 233847553, "igemm_dgrad_256x192x64_store": 166704669,
+        "igemm_fwd_256x256x64_affine": 111676325, "igemm_fwd_256x256x64_store": 212658276,
     }),
 }
 

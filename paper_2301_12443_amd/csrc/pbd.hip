@@ -1283,7 +1283,7 @@ template <class T> struct Exec {
             }
           } else {
             const ColGrid g = bn_stats_grid(M, op.cout_p);
-            ProfScope ps(c, "bn_stats", bytes_of(op.out), 0, net, blk, opi);
+            ProfScope ps(c, streams(op.out) ? "bn_stats_nt" : "bn_stats", bytes_of(op.out), 0, net, blk, opi);
             launch(c, streams(op.out) ? bn_stats_kernel<T, true> : bn_stats_kernel<T, false>, dim3(g.slabs, g.chunks), 256,
                    256 * 16 * sizeof(float), st, y, red(), M, op.cout_p, g);
             chunks = g.chunks;
@@ -1305,7 +1305,8 @@ template <class T> struct Exec {
               z = value(rd + 1);
               fused[rd] = 1;
             }
-            ProfScope ps(c, res ? "bn_apply_add" : "bn_apply", (res ? 3 : 2) * bytes_of(op.out), 0, net, blk, opi);
+            const bool nt = streams(op.out);    // (profile classes: one per kernel instantiation)
+            ProfScope ps(c, res ? (nt ? "bn_apply_add_nt" : "bn_apply_add") : (nt ? "bn_apply_nt" : "bn_apply"), (res ? 3 : 2) * bytes_of(op.out), 0, net, blk, opi);
             launch(c, streams(op.out) ? bn_apply_kernel<T, true> : bn_apply_kernel<T, false>, dim3(ga.slabs, ga.chunks), 256, 0, st, y, z, wsf(op.s_mean), wsf(op.s_invstd),
                                                                        master + op.e_gamma, master + op.e_beta, M,
                                                                        op.cout_p, op.d.act, ga, res, res_act);
@@ -1400,7 +1401,7 @@ template <class T> struct Exec {
           if (ab.loss) {
             float* loss_part = red() + (size_t)g.chunks * 2 * op.cout_p;
             {
-              ProfScope ps(c, "bn_bwd_reduce_add_mse", 4 * bytes_of(op.out), 0, net, blk, opi);
+              ProfScope ps(c, streams(op.out) ? "bn_bwd_reduce_add_mse_nt" : "bn_bwd_reduce_add_mse", 4 * bytes_of(op.out), 0, net, blk, opi);
               launch(c, streams(op.out) ? bn_bwd_reduce_kernel<T, true, true, true> : bn_bwd_reduce_kernel<T, true, true, false>,
                   dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
                   ab.dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
@@ -1408,13 +1409,13 @@ template <class T> struct Exec {
             }
             launch(c, mse_final_kernel, 1, 256, 0, st, loss_part, g.slabs * g.chunks, 1.0 / (double)numel, loss_dev);
           } else if (ab.dz) {
-            ProfScope ps(c, "bn_bwd_reduce_add", (ab.z ? 4 : 3) * bytes_of(op.out), 0, net, blk, opi);
+            ProfScope ps(c, streams(op.out) ? "bn_bwd_reduce_add_nt" : "bn_bwd_reduce_add", (ab.z ? 4 : 3) * bytes_of(op.out), 0, net, blk, opi);
             launch(c, streams(op.out) ? bn_bwd_reduce_kernel<T, true, false, true> : bn_bwd_reduce_kernel<T, true, false, false>,
                 dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
                 ab.dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
                 op.d.act, g, ab.z, ab.act, ab.dstore, (float*)nullptr, 0.f);
           } else {
-            ProfScope ps(c, "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
+            ProfScope ps(c, streams(op.out) ? "bn_bwd_reduce_nt" : "bn_bwd_reduce", 2 * bytes_of(op.out), 0, net, blk, opi);
             launch(c, streams(op.out) ? bn_bwd_reduce_kernel<T, false, false, true> : bn_bwd_reduce_kernel<T, false, false, false>,
                 dim3(g.slabs, g.chunks), 256, 256 * 16 * sizeof(float), st,
                 (const T*)dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), red(), M, op.cout_p,
@@ -1425,7 +1426,7 @@ template <class T> struct Exec {
                                                                            wsf(op.s_k2), wsf(op.s_k3));
           {
             const ColGrid ga = col_grid(M, op.cout_p, 8, 4096);
-            ProfScope ps(c, "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
+            ProfScope ps(c, streams(op.out) ? "bn_bwd_apply_nt" : "bn_bwd_apply", 3 * bytes_of(op.out), 0, net, blk, opi);
             launch(c, streams(op.out) ? bn_bwd_apply_kernel<T, true> : bn_bwd_apply_kernel<T, false>, dim3(ga.slabs, ga.chunks), 256, 0, st,
                 dz_in, dz, y, master + op.e_gamma, master + op.e_beta, wsf(op.s_mean), wsf(op.s_invstd), wsf(op.s_k2),
                 wsf(op.s_k3), M, op.cout_p, op.d.act, ga);
