@@ -320,8 +320,15 @@ __device__ __forceinline__ void dma_tile(unsigned char* smem, float* ep_s, const
       for (int k = 0; k < CPT; ++k) {
         const int cidx = tid + k * ST;
         const int row = m0 + rbase + cidx / CPROW, col = n0 + (cidx % CPROW) * 8;
-        extra[k] = (full || (row < Mrows && col < g.NC)) ? *reinterpret_cast<const uint4*>(esrc + out_row(row) * g.NC + col)
-                                                       : make_uint4(0, 0, 0, 0);
+        const bool in = full || (row < Mrows && col < g.NC);
+        if (g.stream_out) {                      // (read once, like the output is written once: not kept in the caches)
+          typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
+          u32x4_nt q = {0u, 0u, 0u, 0u};
+          if (in) q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(esrc + out_row(row) * g.NC + col));
+          extra[k] = make_uint4(q.x, q.y, q.z, q.w);
+        } else {
+          extra[k] = in ? *reinterpret_cast<const uint4*>(esrc + out_row(row) * g.NC + col) : make_uint4(0, 0, 0, 0);
+        }
       }
     }
     if (pass) __syncthreads();                   // the previous pass has been read out

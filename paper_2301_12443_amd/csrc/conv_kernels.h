@@ -155,7 +155,8 @@ struct IgemmArgs {
   // igemm_dma_kernel, forward only: a tap gathers a run of 1 << pix_shift neighbouring pixels of CA >> pix_shift
   // channels each (CA contiguous elements; S counts such runs).  0: a tap is one pixel of CA channels
   int pix_shift;
-  // the staged stores of the output are nontemporal (tensors far larger than the caches)
+  // the staged stores of the output, and the loads of what they combine with (a fused residual, the gradient an
+  // accumulating launch adds to), are nontemporal (tensors far larger than the caches)
   int stream_out;
 };
 
