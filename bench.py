@@ -27,11 +27,11 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # and the kernel build they were measured on.
 HBM_TRAFFIC_PER_LAUNCH = {
     "resnet50_x1.5": ("profiles/resnet50_x1.5_step_hbm_traffic.md", {
-        "bn_bwd_apply_nt": 529370651, "bn_bwd_apply": 109015133, "bn_bwd_reduce_nt": 316330953, "bn_bwd_reduce": 68897254,
-        "bn_bwd_reduce_add_nt": 783209522, "bn_bwd_reduce_add_mse_nt": 961378955,
-        "wgrad_128x128": 305761204, "wgrad_192x256": 237290720, "wgrad_256x256": 218338070,
-        "igemm_fwd_256x192x64_store": 233847553, "igemm_dgrad_256x192x64_store": 166704669,
-        "igemm_fwd_256x256x64_affine": 111676325, "igemm_fwd_256x256x64_store": 212658276,
+        "bn_bwd_apply_nt": 529383287, "bn_bwd_apply": 109005079, "bn_bwd_reduce_nt": 316387844, "bn_bwd_reduce": 68893253,
+        "bn_bwd_reduce_add_nt": 783206636, "bn_bwd_reduce_add_mse_nt": 961378928,
+        "wgrad_128x128": 305537993, "wgrad_192x256": 237270696, "wgrad_256x256": 218341152,
+        "igemm_fwd_256x192x64_store": 233818122, "igemm_dgrad_256x192x64_store": 166823130,
+        "igemm_fwd_256x256x64_affine": 111692635, "igemm_fwd_256x256x64_store": 212696277,
     }),
 }
 
