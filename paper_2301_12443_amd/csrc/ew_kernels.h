@@ -944,6 +944,122 @@ __global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ z, u
   }
 }
 
+// The 3 x 3, stride-2, pad-1 pool (the ResNet stem's) with all nine taps of a window loaded before the first is looked at
+// (out-of-range taps read a clamped position and are skipped): one memory latency per window instead of one per
+// tap.  Same values and window positions as maxpool_fwd_kernel.
+template <class T>
+__global__ void maxpool_fwd_k3s2_kernel(const T* __restrict__ x, T* __restrict__ z, uint8_t* __restrict__ idx,
+                                        int N, int H, int W, int P, int Q, int ncv, NormFold fold) {
+  const long nvec = (long)N * P * Q * ncv;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int q = (int)(pix % Q); pix /= Q;
+    const int p = (int)(pix % P);
+    const int n = (int)(pix / P);
+    float mu[8], fa[8], fb[8];
+    if (fold.mean) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int ch = cv * 8 + e;
+        mu[e] = fold.mean[ch]; fa[e] = fold.gamma[ch] * fold.invstd[ch]; fb[e] = fold.beta[ch];
+      }
+    }
+    typename IO<T>::Raw raw[9];
+    unsigned ok = 0;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int h = 2 * p - 1 + tap / 3, w = 2 * q - 1 + tap % 3;
+      if (h >= 0 && h < H && w >= 0 && w < W) ok |= 1u << tap;
+      const int hc = min(max(h, 0), H - 1), wc = min(max(w, 0), W - 1);
+      raw[tap] = IO<T>::ld_raw(x + ((((long)n * H + hc) * W + wc) * ncv + cv) * 8);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float best[8];
+    int bi[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { best[e] = 0.f; bi[e] = -1; }
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      if (!(ok >> tap & 1)) continue;
+      float v[8];
+      IO<T>::unpack(raw[tap], v);
+      if (fold.mean) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = as_stored<T>(apply_act(fmaf(v[e] - mu[e], fa[e], fb[e]), fold.act));
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (bi[e] < 0 || v[e] > best[e]) { best[e] = v[e]; bi[e] = tap; }
+    }
+    IO<T>::st(z + i * 8, best);
+    if (idx) {
+      uint2 pk;
+      pk.x = (uint32_t)bi[0] | ((uint32_t)bi[1] << 8) | ((uint32_t)bi[2] << 16) | ((uint32_t)bi[3] << 24);
+      pk.y = (uint32_t)bi[4] | ((uint32_t)bi[5] << 8) | ((uint32_t)bi[6] << 16) | ((uint32_t)bi[7] << 24);
+      *reinterpret_cast<uint2*>(idx + i * 8) = pk;
+    }
+  }
+}
+
+// Its backward pass: an input pixel lies in one window per direction when its coordinate is even (tap 1) and in two when
+// it is odd (taps 0 and 2), so at most four windows, whose positions and gradients are all loaded before the first
+// comparison; contributions are added in the tap order of maxpool_bwd_kernel.
+template <class T>
+__global__ void maxpool_bwd_k3s2_kernel(const T* __restrict__ dz, const uint8_t* __restrict__ idx,
+                                        T* __restrict__ dx, int N, int H, int W, int P, int Q, int ncv, int accumulate) {
+  const long nvec = (long)N * H * W * ncv;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nvec; i += (long)gridDim.x * blockDim.x) {
+    const int cv = (int)(i % ncv);
+    long pix = i / ncv;
+    const int w = (int)(pix % W); pix /= W;
+    const int h = (int)(pix % H);
+    const int n = (int)(pix / H);
+    // candidate windows per direction, in tap order: odd coordinate: tap 0 of window (c + 1) / 2, tap 2 of (c - 1) / 2;
+    // even: tap 1 of window c / 2
+    int pr[2], rr[2], qc[2], tc[2];
+    bool pv[2], qv[2];
+    if (h & 1) { rr[0] = 0; pr[0] = (h + 1) >> 1; pv[0] = pr[0] < P; rr[1] = 2; pr[1] = (h - 1) >> 1; pv[1] = pr[1] < P; }
+    else { rr[0] = 1; pr[0] = h >> 1; pv[0] = pr[0] < P; rr[1] = 0; pr[1] = 0; pv[1] = false; }
+    if (w & 1) { tc[0] = 0; qc[0] = (w + 1) >> 1; qv[0] = qc[0] < Q; tc[1] = 2; qc[1] = (w - 1) >> 1; qv[1] = qc[1] < Q; }
+    else { tc[0] = 1; qc[0] = w >> 1; qv[0] = qc[0] < Q; tc[1] = 0; qc[1] = 0; qv[1] = false; }
+    uint2 pk[4];
+    typename IO<T>::Raw raw[4];
+    bool valid[4];
+    uint32_t me[4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const int k = a * 2 + b;
+        valid[k] = pv[a] && qv[b];
+        const int pp = min(pr[a], P - 1), qq = min(qc[b], Q - 1);
+        const long o = ((((long)n * P + pp) * Q + qq) * ncv + cv) * 8;
+        pk[k] = *reinterpret_cast<const uint2*>(idx + o);
+        raw[k] = IO<T>::ld_raw(dz + o);
+        me[k] = (uint32_t)(rr[a] * 3 + tc[b]);
+      }
+    float acc[8];
+    if (accumulate) IO<T>::ld(dx + i * 8, acc);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      float d[8];
+      IO<T>::unpack(raw[k], d);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t word = e < 4 ? pk[k].x : pk[k].y;
+        if (valid[k] && ((word >> (8 * (e & 3))) & 0xffu) == me[k]) acc[e] += d[e];
+      }
+    }
+    IO<T>::st(dx + i * 8, acc);
+  }
+}
+
 // gather form: every input pixel collects from the windows that chose it
 template <class T>
 __global__ void maxpool_bwd_kernel(const T* __restrict__ dz, const uint8_t* __restrict__ idx,

@@ -1054,8 +1054,11 @@ template <class T> struct Exec {
     const int N = c->o.batch, ncv = op.cout_p / 8;
     const long nvec = (long)N * op.out.h * op.out.w * ncv;
     ProfScope ps(c, fold.mean ? "bn_apply_maxpool" : "maxpool_fwd", bytes_of(op.in) + bytes_of(op.out) * (idx ? 1.5 : 1.0), 0, net, blk, opi);
-    launch(c, maxpool_fwd_kernel<T>, grid_for(nvec), 256, 0, st, x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
-                                                          op.d.k, op.d.stride, op.d.pad, fold);
+    if (op.d.k == 3 && op.d.stride == 2 && op.d.pad == 1)
+      launch(c, maxpool_fwd_k3s2_kernel<T>, grid_for(nvec), 256, 0, st, x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv, fold);
+    else
+      launch(c, maxpool_fwd_kernel<T>, grid_for(nvec), 256, 0, st, x, z, idx, N, op.in.h, op.in.w, op.out.h, op.out.w, ncv,
+                                                            op.d.k, op.d.stride, op.d.pad, fold);
   }
 
   // =========================================================================
@@ -1447,9 +1450,13 @@ template <class T> struct Exec {
           const int ncv = op.cout_p / 8;
           const long nvec = (long)N * op.in.h * op.in.w * ncv;
           ProfScope ps(c, "maxpool_bwd", bytes_of(op.in) + 1.5 * bytes_of(op.out), 0, net, blk, opi);
-          launch(c, maxpool_bwd_kernel<T>, grid_for(nvec), 256, 0, st, dz, reinterpret_cast<const uint8_t*>(c->ws + scr + op.idx),
-                                                                dvalue(iv), N, op.in.h, op.in.w, op.out.h, op.out.w,
-                                                                ncv, op.d.k, op.d.stride, op.d.pad, have[iv] ? 1 : 0);
+          if (op.d.k == 3 && op.d.stride == 2 && op.d.pad == 1)
+            launch(c, maxpool_bwd_k3s2_kernel<T>, grid_for(nvec), 256, 0, st, (const T*)dz, reinterpret_cast<const uint8_t*>(c->ws + scr + op.idx),
+                   dvalue(iv), N, op.in.h, op.in.w, op.out.h, op.out.w, ncv, have[iv] ? 1 : 0);
+          else
+            launch(c, maxpool_bwd_kernel<T>, grid_for(nvec), 256, 0, st, dz, reinterpret_cast<const uint8_t*>(c->ws + scr + op.idx),
+                                                                  dvalue(iv), N, op.in.h, op.in.w, op.out.h, op.out.w,
+                                                                  ncv, op.d.k, op.d.stride, op.d.pad, have[iv] ? 1 : 0);
           have[iv] = 1;
         }
       } else {
