@@ -27,11 +27,11 @@ LR_ALPHA = 0.005          # learning rate of the architecture parameters in the 
 # and the kernel build they were measured on.
 HBM_TRAFFIC_PER_LAUNCH = {
     "resnet50_x1.5": ("profiles/resnet50_x1.5_step_hbm_traffic.md", {
-        "bn_bwd_apply_nt": 529383287, "bn_bwd_apply": 109005079, "bn_bwd_reduce_nt": 316387844, "bn_bwd_reduce": 68893253,
-        "bn_bwd_reduce_add_nt": 783206636, "bn_bwd_reduce_add_mse_nt": 961378928,
-        "wgrad_128x128": 305537993, "wgrad_192x256": 237270696, "wgrad_256x256": 218341152,
-        "igemm_fwd_256x192x64_store": 233818122, "igemm_dgrad_256x192x64_store": 166823130,
-        "igemm_fwd_256x256x64_affine": 111692635, "igemm_fwd_256x256x64_store": 212696277,
+        "bn_bwd_apply_nt": 529362959, "bn_bwd_apply": 109015272, "bn_bwd_reduce_nt": 316315223, "bn_bwd_reduce": 68903370,
+        "bn_bwd_reduce_add_nt": 783209493, "bn_bwd_reduce_add_mse_nt": 961371582,
+        "wgrad_128x128": 305611219, "wgrad_192x256": 237289843, "wgrad_256x256": 218329889,
+        "igemm_fwd_256x192x64_store": 233869020, "igemm_dgrad_256x192x64_store": 166897786,
+        "igemm_fwd_256x256x64_affine": 111665417, "igemm_fwd_256x256x64_store": 212692777,
     }),
 }
 
